@@ -1,0 +1,352 @@
+"""Plain NumPy oracle of one worker's share of a HetSeq training step.
+
+TEST INFRASTRUCTURE ONLY.  This file is the slow, obviously-correct definition that
+the HIP kernels are compared with.  It is never part of the product path, shares no
+code with it and does not import it.
+
+What the paper (HetSeq, "Distributed GPU Training on Heterogeneous Infrastructure")
+fixes, and where:
+
+* Section "Optimizer and Learning Rate Scheduler": workers run unequal batches, so
+  every worker reports its loss together with a weight (batch size or token count)
+  and the weighted sum over workers, divided by the total weight, is what is
+  trained on.  Here: each micro-batch returns a loss SUM, gradients of the sums are
+  added, and the total is divided by the global sample count (`normalize`).
+* Section "Backpropagation": a worker without data runs a dummy batch whose gradient
+  is set to zero, i.e. it contributes nothing (`accumulate(..., ignore=True)`).
+* Section "Delayed Update (Gradient Accumulation)": several forward/backward passes
+  are aggregated before one update and the batch size scales with their number
+  (`accumulate` called once per micro-batch, sample counts added).
+* Section "Forward Pass": batches are formed under a max-instances or max-tokens
+  criterion (see `oracle/batcher.py`).
+* Section "BERT Language Model": Adam with beta1 0.9, beta2 0.999, eps 1e-8,
+  maximum learning rate 1e-4 (`adam_step`).
+
+The transformer encoder itself is only cited by the paper (BERT); the textbook
+definition is written out below: post-LN encoder layers, softmax attention that
+excludes padded keys, exact-erf GELU, LayerNorm with biased variance, a masked-LM
+head whose decoder is tied to the word embedding, cross-entropy summed over targets.
+
+Precision is a parameter (`dtype`): float32 is the reference precision, float64 is
+used for finite-difference checks and as a tighter reference on small cases.
+
+Pins (tests/test_oracle_*.py): central finite differences in float64 for every
+parameter tensor; a pure-Python loop re-implementation of the forward pass; SciPy's
+logsumexp/erf; padding invariance; the concatenation invariant
+sum_i grad_i / sum_i n_i == grad(concatenated batch)/D; the paper's worked example
+with local batch sizes 2,2,1,0; Adam closed forms.
+"""
+from __future__ import annotations
+
+import math
+from dataclasses import dataclass
+
+import numpy as np
+from scipy.special import erf
+
+PAD_ID = 0
+MASK_ID = 4
+
+
+@dataclass(frozen=True)
+class ModelCfg:
+    n_layers: int
+    hidden: int
+    n_heads: int
+    ffn: int
+    vocab: int
+    max_pos: int
+    ln_eps: float = 1e-12
+
+    @property
+    def head_dim(self) -> int:
+        return self.hidden // self.n_heads
+
+
+# --------------------------------------------------------------------------------------
+# flat parameter layout (the oracle's own statement of it; the HIP library has its own,
+# and a test checks that the two agree)
+# --------------------------------------------------------------------------------------
+def param_layout(cfg: ModelCfg):
+    """List of (name, offset, rows, cols); vectors have rows == 1.  Weights are
+    [out, in] row-major (y = x W^T + b)."""
+    H, F, V = cfg.hidden, cfg.ffn, cfg.vocab
+    shapes = [("emb.word", V, H), ("emb.pos", cfg.max_pos, H), ("emb.ln.g", 1, H), ("emb.ln.b", 1, H)]
+    for i in range(cfg.n_layers):
+        p = f"l{i}."
+        shapes += [
+            (p + "qkv.w", 3 * H, H), (p + "qkv.b", 1, 3 * H),
+            (p + "o.w", H, H), (p + "o.b", 1, H),
+            (p + "ln1.g", 1, H), (p + "ln1.b", 1, H),
+            (p + "ffn1.w", F, H), (p + "ffn1.b", 1, F),
+            (p + "ffn2.w", H, F), (p + "ffn2.b", 1, H),
+            (p + "ln2.g", 1, H), (p + "ln2.b", 1, H),
+        ]
+    shapes += [("head.t.w", H, H), ("head.t.b", 1, H), ("head.ln.g", 1, H), ("head.ln.b", 1, H),
+               ("head.dec.b", 1, V)]
+    out, off = [], 0
+    for name, r, c in shapes:
+        out.append((name, off, r, c))
+        off += r * c
+    return out
+
+
+def param_count(cfg: ModelCfg) -> int:
+    name, off, r, c = param_layout(cfg)[-1]
+    return off + r * c
+
+
+def param_views(cfg: ModelCfg, flat: np.ndarray) -> dict:
+    """Named views into a flat parameter (or gradient) vector; vectors are 1-D."""
+    assert flat.ndim == 1 and flat.size == param_count(cfg)
+    views = {}
+    for name, off, r, c in param_layout(cfg):
+        v = flat[off:off + r * c]
+        views[name] = v if r == 1 else v.reshape(r, c)
+    return views
+
+
+# --------------------------------------------------------------------------------------
+# building blocks
+# --------------------------------------------------------------------------------------
+def key_mask(lens: np.ndarray, L: int) -> np.ndarray:
+    """mask[b, l] = 1 where position l of sequence b is a real token."""
+    return (np.arange(L)[None, :] < np.asarray(lens)[:, None]).astype(np.uint8)
+
+
+def gelu(x):
+    return 0.5 * x * (1.0 + erf(x / math.sqrt(2.0)))
+
+
+def gelu_grad(x):
+    return 0.5 * (1.0 + erf(x / math.sqrt(2.0))) + x * np.exp(-0.5 * x * x) / math.sqrt(2.0 * math.pi)
+
+
+def layer_norm_fwd(x, gain, bias, eps):
+    """y = (x - mean) / sqrt(var + eps) * gain + bias, biased variance over the last axis."""
+    mu = x.mean(axis=-1, keepdims=True)
+    xc = x - mu
+    var = (xc * xc).mean(axis=-1, keepdims=True)
+    rstd = 1.0 / np.sqrt(var + x.dtype.type(eps))
+    xhat = xc * rstd
+    return xhat * gain + bias, (xhat, rstd)
+
+
+def layer_norm_bwd(dy, cache, gain):
+    xhat, rstd = cache
+    H = dy.shape[-1]
+    d_gain = (dy * xhat).reshape(-1, H).sum(axis=0)
+    d_bias = dy.reshape(-1, H).sum(axis=0)
+    dxhat = dy * gain
+    dx = rstd * (dxhat - dxhat.mean(axis=-1, keepdims=True)
+                 - xhat * (dxhat * xhat).mean(axis=-1, keepdims=True))
+    return dx, d_gain, d_bias
+
+
+# --------------------------------------------------------------------------------------
+# forward: encoder, then masked-LM head and loss SUM
+# --------------------------------------------------------------------------------------
+def encoder_forward(cfg: ModelCfg, theta: np.ndarray, ids: np.ndarray, lens: np.ndarray):
+    """ids [B, L] int, lens [B] (each >= 1).  Returns hidden [B, L, H] and a cache."""
+    P = param_views(cfg, theta)
+    dt = theta.dtype
+    B, L = ids.shape
+    H, A, d = cfg.hidden, cfg.n_heads, cfg.head_dim
+    assert L <= cfg.max_pos and np.all(np.asarray(lens) >= 1) and np.all(np.asarray(lens) <= L)
+    valid = key_mask(lens, L).astype(bool)                       # [B, L]
+
+    e = P["emb.word"][ids] + P["emb.pos"][:L][None, :, :]
+    x, c_emb = layer_norm_fwd(e, P["emb.ln.g"], P["emb.ln.b"], cfg.ln_eps)
+    cache = {"ids": ids, "lens": np.asarray(lens), "valid": valid, "emb_ln": c_emb, "layers": []}
+    scale = dt.type(1.0 / math.sqrt(d))
+    for i in range(cfg.n_layers):
+        p = f"l{i}."
+        qkv = x @ P[p + "qkv.w"].T + P[p + "qkv.b"]              # [B, L, 3H]
+        q, k, v = (qkv[..., j * H:(j + 1) * H].reshape(B, L, A, d).transpose(0, 2, 1, 3) for j in range(3))
+        s = (q @ k.transpose(0, 1, 3, 2)) * scale                # [B, A, L, L]
+        s = np.where(valid[:, None, None, :], s, -np.inf)       # padded keys are excluded
+        s_max = s.max(axis=-1, keepdims=True)
+        pexp = np.exp(s - s_max)
+        prob = pexp / pexp.sum(axis=-1, keepdims=True)
+        ctx = (prob @ v).transpose(0, 2, 1, 3).reshape(B, L, H)
+        y1 = x + ctx @ P[p + "o.w"].T + P[p + "o.b"]
+        x1, c_ln1 = layer_norm_fwd(y1, P[p + "ln1.g"], P[p + "ln1.b"], cfg.ln_eps)
+        hpre = x1 @ P[p + "ffn1.w"].T + P[p + "ffn1.b"]
+        h = gelu(hpre)
+        y2 = x1 + h @ P[p + "ffn2.w"].T + P[p + "ffn2.b"]
+        x2, c_ln2 = layer_norm_fwd(y2, P[p + "ln2.g"], P[p + "ln2.b"], cfg.ln_eps)
+        cache["layers"].append(dict(x=x, q=q, k=k, v=v, prob=prob, ctx=ctx, ln1=c_ln1, x1=x1,
+                                    hpre=hpre, h=h, ln2=c_ln2))
+        x = x2
+    return x, cache
+
+
+def mlm_loss_forward(cfg: ModelCfg, theta: np.ndarray, hidden: np.ndarray, mlm_pos, mlm_label):
+    """loss_sum = sum_m [logsumexp(logits_m) - logits_m[label_m]]; no division here: the
+    weight (sample or token count) travels beside the sum."""
+    P = param_views(cfg, theta)
+    H = cfg.hidden
+    mlm_pos = np.asarray(mlm_pos, dtype=np.int64)
+    mlm_label = np.asarray(mlm_label, dtype=np.int64)
+    g = hidden.reshape(-1, H)[mlm_pos]                          # [M, H]
+    tpre = g @ P["head.t.w"].T + P["head.t.b"]
+    tact = gelu(tpre)
+    t, c_ln = layer_norm_fwd(tact, P["head.ln.g"], P["head.ln.b"], cfg.ln_eps)
+    logits = t @ P["emb.word"].T + P["head.dec.b"]              # tied decoder
+    M = logits.shape[0]
+    if M == 0:
+        return theta.dtype.type(0.0), dict(M=0, mlm_pos=mlm_pos)
+    zmax = logits.max(axis=1, keepdims=True)
+    lse = zmax[:, 0] + np.log(np.exp(logits - zmax).sum(axis=1))
+    loss_sum = (lse - logits[np.arange(M), mlm_label]).sum()
+    cache = dict(M=M, mlm_pos=mlm_pos, mlm_label=mlm_label, g=g, tpre=tpre, tact=tact, t=t, ln=c_ln,
+                 logits=logits, lse=lse)
+    return loss_sum, cache
+
+
+# --------------------------------------------------------------------------------------
+# backward
+# --------------------------------------------------------------------------------------
+def mlm_loss_backward(cfg: ModelCfg, theta: np.ndarray, hidden_shape, cache, grad: np.ndarray):
+    """Adds the head's parameter gradients (and the decoder part of the tied word
+    embedding) into `grad`; returns d loss_sum / d hidden (zero off the target rows)."""
+    P = param_views(cfg, theta)
+    G = param_views(cfg, grad)
+    d_hidden = np.zeros(hidden_shape, dtype=theta.dtype)
+    M = cache["M"]
+    if M == 0:
+        return d_hidden
+    dlogits = np.exp(cache["logits"] - cache["lse"][:, None])    # softmax
+    dlogits[np.arange(M), cache["mlm_label"]] -= 1.0
+    G["head.dec.b"] += dlogits.sum(axis=0)
+    G["emb.word"] += dlogits.T @ cache["t"]
+    dt_ = dlogits @ P["emb.word"]
+    dtact, dg_, db_ = layer_norm_bwd(dt_, cache["ln"], P["head.ln.g"])
+    G["head.ln.g"] += dg_
+    G["head.ln.b"] += db_
+    dtpre = dtact * gelu_grad(cache["tpre"])
+    G["head.t.w"] += dtpre.T @ cache["g"]
+    G["head.t.b"] += dtpre.sum(axis=0)
+    dgath = dtpre @ P["head.t.w"]
+    flat = d_hidden.reshape(-1, cfg.hidden)
+    np.add.at(flat, cache["mlm_pos"], dgath)
+    return d_hidden
+
+
+def encoder_backward(cfg: ModelCfg, theta: np.ndarray, cache, d_hidden: np.ndarray, grad: np.ndarray):
+    """Chain rule through the encoder; parameter gradients are added into `grad`."""
+    P = param_views(cfg, theta)
+    G = param_views(cfg, grad)
+    dt = theta.dtype
+    H, A, d = cfg.hidden, cfg.n_heads, cfg.head_dim
+    B, L = cache["ids"].shape
+    T = B * L
+    scale = dt.type(1.0 / math.sqrt(d))
+    dx = d_hidden
+    for i in reversed(range(cfg.n_layers)):
+        p = f"l{i}."
+        c = cache["layers"][i]
+        dy2, dg_, db_ = layer_norm_bwd(dx, c["ln2"], P[p + "ln2.g"])
+        G[p + "ln2.g"] += dg_
+        G[p + "ln2.b"] += db_
+        dy2f = dy2.reshape(T, H)
+        G[p + "ffn2.b"] += dy2f.sum(axis=0)
+        G[p + "ffn2.w"] += dy2f.T @ c["h"].reshape(T, -1)
+        dh = dy2 @ P[p + "ffn2.w"]
+        dhpre = dh * gelu_grad(c["hpre"])
+        dhpf = dhpre.reshape(T, -1)
+        G[p + "ffn1.b"] += dhpf.sum(axis=0)
+        G[p + "ffn1.w"] += dhpf.T @ c["x1"].reshape(T, H)
+        dx1 = dy2 + dhpre @ P[p + "ffn1.w"]
+        dy1, dg_, db_ = layer_norm_bwd(dx1, c["ln1"], P[p + "ln1.g"])
+        G[p + "ln1.g"] += dg_
+        G[p + "ln1.b"] += db_
+        dy1f = dy1.reshape(T, H)
+        G[p + "o.b"] += dy1f.sum(axis=0)
+        G[p + "o.w"] += dy1f.T @ c["ctx"].reshape(T, H)
+        dctx = (dy1 @ P[p + "o.w"]).reshape(B, L, A, d).transpose(0, 2, 1, 3)     # [B, A, L, d]
+        prob, q, k, v = c["prob"], c["q"], c["k"], c["v"]
+        dv = prob.transpose(0, 1, 3, 2) @ dctx
+        dprob = dctx @ v.transpose(0, 1, 3, 2)
+        ds = prob * (dprob - (dprob * prob).sum(axis=-1, keepdims=True))          # softmax backward
+        dq = (ds @ k) * scale
+        dk = (ds.transpose(0, 1, 3, 2) @ q) * scale
+        dqkv = np.concatenate([a.transpose(0, 2, 1, 3).reshape(B, L, H) for a in (dq, dk, dv)], axis=-1)
+        dqkvf = dqkv.reshape(T, 3 * H)
+        G[p + "qkv.b"] += dqkvf.sum(axis=0)
+        G[p + "qkv.w"] += dqkvf.T @ c["x"].reshape(T, H)
+        dx = dy1 + dqkv @ P[p + "qkv.w"]
+    de, dg_, db_ = layer_norm_bwd(dx, cache["emb_ln"], P["emb.ln.g"])
+    G["emb.ln.g"] += dg_
+    G["emb.ln.b"] += db_
+    G["emb.pos"][:L] += de.sum(axis=0)
+    np.add.at(G["emb.word"], cache["ids"].reshape(-1), de.reshape(T, H))          # duplicates summed
+
+
+def micro_batch_grad(cfg: ModelCfg, theta: np.ndarray, ids, lens, mlm_pos, mlm_label):
+    """One forward/backward pass of one micro-batch.  Returns (loss_sum, flat gradient of
+    loss_sum, n_seq, n_tok)."""
+    ids = np.asarray(ids)
+    hidden, cache = encoder_forward(cfg, theta, ids, lens)
+    loss_sum, hcache = mlm_loss_forward(cfg, theta, hidden, mlm_pos, mlm_label)
+    grad = np.zeros_like(theta)
+    d_hidden = mlm_loss_backward(cfg, theta, hidden.shape, hcache, grad)
+    encoder_backward(cfg, theta, cache, d_hidden, grad)
+    return loss_sum, grad, ids.shape[0], int(hcache["M"])
+
+
+# --------------------------------------------------------------------------------------
+# accumulate, normalise, Adam
+# --------------------------------------------------------------------------------------
+def accumulate(G: np.ndarray, n_total, g, n, ignore: bool = False):
+    """Delayed update: G += g, n_total += n.  A dummy micro-batch (ignore) contributes
+    neither; its gradient is not even read."""
+    if ignore:
+        return G, n_total
+    G += g
+    return G, n_total + n
+
+
+def normalize(G: np.ndarray, denom):
+    """G <- G / D with D the global weight (sample count summed over all micro-batches
+    and workers)."""
+    assert denom > 0
+    G /= G.dtype.type(denom)
+    return G
+
+
+def adam_step(w, m, v, G, t: int, lr, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.0):
+    """Adam with bias correction, eps added to sqrt(v_hat); t is 1-based.  Weight decay,
+    when non-zero, is decoupled: w <- w - lr * wd * w.  Updates in place."""
+    assert t >= 1
+    ty = w.dtype.type
+    m *= ty(beta1)
+    m += ty(1.0 - beta1) * G
+    v *= ty(beta2)
+    v += ty(1.0 - beta2) * (G * G)
+    mhat = m / ty(1.0 - beta1 ** t)
+    vhat = v / ty(1.0 - beta2 ** t)
+    if weight_decay != 0.0:
+        w -= ty(lr * weight_decay) * w
+    w -= ty(lr) * mhat / (np.sqrt(vhat) + ty(eps))
+    return w, m, v
+
+
+def train_step(cfg: ModelCfg, theta, m, v, t, micro_batches, lr=1e-4, beta1=0.9, beta2=0.999,
+               eps=1e-8, weight_decay=0.0, denom=None):
+    """The whole hot path.  micro_batches: list of dicts with ids, lens, mlm_pos,
+    mlm_label and optionally dummy=True.  Returns (reported loss = sum of loss sums / D,
+    normalised gradient G, D).  theta, m, v are updated in place."""
+    G = np.zeros_like(theta)
+    n_total, loss_total = 0, 0.0
+    for mb in micro_batches:
+        if mb.get("dummy", False):
+            G, n_total = accumulate(G, n_total, None, 0, ignore=True)
+            continue
+        loss_sum, g, n_seq, _ = micro_batch_grad(cfg, theta, mb["ids"], mb["lens"], mb["mlm_pos"], mb["mlm_label"])
+        G, n_total = accumulate(G, n_total, g, n_seq)
+        loss_total += float(loss_sum)
+    D = n_total if denom is None else denom
+    normalize(G, D)
+    adam_step(theta, m, v, G, t, lr, beta1, beta2, eps, weight_decay)
+    return loss_total / D, G, D
