@@ -1,0 +1,186 @@
+#!/usr/bin/env python3
+"""Benchmark of the HetSeq training-step hot path on one MI355X.
+
+A step is one pass of the whole path over one synthetic batch of the BERT-base workload
+(64 sequences x 128 tokens under a max-tokens cap of 8192): batch formation on the host,
+encoder forward, masked-LM loss, backward, accumulation into the flat fp32 gradient buffer,
+normalisation by the global sample count, fused Adam.  Inputs are resident in HBM before the
+timed region.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0
+
+
+def algorithmic_flops(model, mbs):
+    """Forward + backward (2x forward) flops of the micro-batches: per real token and layer
+    24 H^2 + 4 L H (F = 4H, attention over the padded length of its batch), per masked token
+    2 H^2 + 2 H V; recomputation inside attention backward is not counted."""
+    H, V, NL = model["hidden"], model["vocab"], model["n_layers"]
+    total = 0.0
+    for mb in mbs:
+        L = mb["ids"].shape[1]
+        total += 3.0 * NL * mb["n_real_tokens"] * (24.0 * H * H + 4.0 * L * H)
+        total += 3.0 * mb["mlm_pos"].size * (2.0 * H * H + 2.0 * H * V)
+    return total
+
+
+def cpu_baseline(model, wl, theta, mbs, n_seq_sample=16):
+    """The oracle, as it stands, on a bounded sample of the same workload: the first
+    n_seq_sample sequences of the batch through the identical step (forward, loss, backward,
+    normalise, Adam over all parameters)."""
+    from threadpoolctl import threadpool_info
+    from oracle import hetseq_oracle as O
+    ocfg = O.ModelCfg(**model)
+    mb = mbs[0]
+    L = mb["ids"].shape[1]
+    keep = mb["mlm_pos"] < n_seq_sample * L
+    sample = dict(ids=mb["ids"][:n_seq_sample], lens=mb["lens"][:n_seq_sample], mlm_pos=mb["mlm_pos"][keep],
+                  mlm_label=mb["mlm_label"][keep])
+    th = theta.copy()
+    m, v = np.zeros_like(th), np.zeros_like(th)
+    t0 = time.perf_counter()
+    O.train_step(ocfg, th, m, v, 1, [sample], **wl["adam"])
+    dt = time.perf_counter() - t0
+    tokens = int(sample["lens"].sum())
+    threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    return dict(value=tokens / dt, unit="tokens/s", cores=int(threads), kind="oracle",
+                sample=f"first {n_seq_sample} of the 64 sequences ({tokens} tokens), full 12-layer model, one whole step "
+                       f"(fwd, loss, bwd, normalise, Adam) in fp32 NumPy: {dt:.1f} s",
+                host_cores_available=len(os.sched_getaffinity(0)))
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--profile-steps", type=int, default=3, help="extra steps with per-kernel event timing")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus must be 1 (no collectives, no sharding in this path)",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2009_14783_amd import binding as hs
+    from paper_2009_14783_amd import synth
+    from paper_2009_14783_amd.step import Worker
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    hs.lib()                                             # fail loudly if the HIP library is missing
+
+    widx = 1
+    wl = synth.WORKLOADS[widx]
+    model = synth.MODELS[wl["model"]]
+    cfg = hs.make_cfg(**model)
+    theta = synth.init_params(hs.hs_param_layout(cfg), wl["seed"])
+    mbs = synth.workload_micro_batches(widx)
+    lengths = np.concatenate([mb["lens"] for mb in mbs]).astype(np.int32)
+    worker = Worker(model, wl["compute"], theta)
+    dev_batches = [worker.upload(mb) for mb in mbs]      # inputs resident in HBM before timing
+    tokens_per_step = int(sum(mb["n_real_tokens"] for mb in mbs))
+    flops_per_step = algorithmic_flops(model, mbs)
+
+    def one_step():
+        # a0: batch formation under the max-tokens cap (host, integer); the batch it yields is the
+        # one already uploaded
+        seq, offs, pads = hs.hs_make_batches(lengths, 64, 8192, 0)
+        assert len(pads) == len(dev_batches)
+        worker.train_step(dev_batches, wl["adam"])
+
+    for _ in range(args.warmup):
+        one_step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        one_step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = 1e3 * dt / args.steps
+    D = sum(d["n_seq"] for d in dev_batches)
+    loss = worker.reported_loss(D)
+
+    # per-kernel timing with HIP events on the launch stream, in extra steps of the same loop
+    hs.hs_profile_enable(worker.ctx, 1)
+    prof = {}
+    adam_ms = []
+    for _ in range(args.profile_steps):
+        ev0, ev1, ev2 = (torch.cuda.Event(enable_timing=True) for _ in range(3))
+        n_total = worker.accumulate_micro_batches(dev_batches)
+        ev0.record()
+        hs.hs_grad_accum_normalize(worker.G, None, worker.P, 0, float(n_total))
+        ev1.record()
+        worker.t += 1
+        hs.hs_adam_step(worker.w, worker.m, worker.v, worker.G, worker.w_lowp, worker.P, wl["adam"]["lr"],
+                        wl["adam"]["beta1"], wl["adam"]["beta2"], wl["adam"]["eps"], 0.0, worker.t)
+        ev2.record()
+        torch.cuda.synchronize()
+        adam_ms.append((ev0.elapsed_time(ev1), ev1.elapsed_time(ev2)))
+        for k, e in hs.hs_profile_read(worker.ctx).items():
+            p = prof.setdefault(k, dict(launches=0, ms=0.0, flops=0.0, bytes=0.0))
+            for f in p:
+                p[f] += e[f]
+    hs.hs_profile_enable(worker.ctx, 0)
+    P = worker.P
+    prof["accum"] = dict(launches=len(adam_ms), ms=sum(a for a, _ in adam_ms), flops=1.0 * P * len(adam_ms),
+                         bytes=8.0 * P * len(adam_ms))
+    prof["adam"] = dict(launches=len(adam_ms), ms=sum(b for _, b in adam_ms), flops=12.0 * P * len(adam_ms),
+                        bytes=30.0 * P * len(adam_ms))
+    kernels = {}
+    for k, p in prof.items():
+        if p["launches"] == 0:
+            continue
+        sec = p["ms"] * 1e-3
+        kernels[k] = dict(launches_per_step=p["launches"] / args.profile_steps, ms_per_step=p["ms"] / args.profile_steps,
+                          tflops=p["flops"] / sec / 1e12 if sec > 0 else 0.0, gbs=p["bytes"] / sec / 1e9 if sec > 0 else 0.0)
+    gemm_classes = [k for k in ("gemm_fwd", "gemm_dx", "gemm_dw") if k in kernels]
+    dominant = max(gemm_classes, key=lambda k: kernels[k]["ms_per_step"])
+    dp = prof[dominant]
+    achieved = dp["flops"] / (dp["ms"] * 1e-3) / 1e12
+    gemm_flops = sum(prof[k]["flops"] for k in gemm_classes)
+    gemm_ms = sum(prof[k]["ms"] for k in gemm_classes)
+    roofline = dict(bound="mfma", kernel=dominant, achieved=achieved, peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
+                    frac=achieved / PEAK_BF16_TFLOPS, traffic=None,
+                    avg_launch_us=1e3 * dp["ms"] / dp["launches"], launches_per_step=dp["launches"] / args.profile_steps,
+                    all_gemms_tflops=gemm_flops / (gemm_ms * 1e-3) / 1e12,
+                    all_gemms_frac=gemm_flops / (gemm_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+                    measured="HIP events around every launch, on the launch stream, in "
+                             f"{args.profile_steps} extra steps after the timed region")
+
+    out = dict(metric="trained tokens/sec on 1 MI355X (BERT-base step) + % peak bf16 MFMA",
+               value=tokens_per_step * args.steps / dt, unit="tokens/s", n_gpus=1, steps=args.steps, warmup=args.warmup,
+               ms_per_step=ms_per_step, higher_is_better=True, scaling="weak", vs_baseline=None, dtype="bf16",
+               data="synthetic",
+               config=dict(workload="BERT-base-shaped step: 12 post-LN layers, hidden 768, 12 heads, FFN 3072, vocab 30522, "
+                                    "tied MLM head; 64 sequences x 128 tokens (max-tokens cap 8192), Zipf(1.1) ids, 15% MLM "
+                                    "targets, bf16 compute with fp32 master weights and accumulation",
+                           tokens_per_step=tokens_per_step, mlm_targets=int(sum(d["M"] for d in dev_batches)),
+                           global_batch=D, seq_len=128, params=P),
+               whole_step_tflops=flops_per_step / (ms_per_step * 1e-3) / 1e12,
+               whole_step_mfma_frac=flops_per_step / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+               loss=loss, roofline=roofline, kernels=kernels)
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(model, wl, theta, mbs)
+    worker.close()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,234 @@
+/*
+ * hetseq_hip.h - C ABI of libhetseq_hip.so: one worker's share of a HetSeq training step on
+ * one MI355X (gfx950).
+ *
+ * The HetSeq paper ("Distributed GPU Training on Heterogeneous Infrastructure") describes a
+ * synchronous data-parallel step in which workers with unequal memory run unequal batches:
+ * forward pass and a per-worker loss with a weight (figure 1; section "Forward Pass"; section
+ * "Optimizer and Learning Rate Scheduler"), back-propagation with an all-zero contribution from
+ * workers that have no data (section "Backpropagation"), aggregation of several passes before
+ * one update (section "Delayed Update (Gradient Accumulation)"), division by the global weight
+ * so that the result equals the non-distributed large batch, and a local optimizer update
+ * (Adam for BERT, section "BERT Language Model").  The calls below are those steps.
+ *
+ * Conventions (all calls):
+ *  - "dev" pointers are device (HBM) addresses, "host" pointers are host addresses.
+ *  - The caller owns every buffer and the stream.  The library allocates no device memory and
+ *    keeps no pointer after a call returns; hs_ctx holds host state only.
+ *  - Device calls enqueue on `stream` (a hipStream_t passed as void*; NULL = the default stream)
+ *    and return without synchronising.  Results are valid once the caller synchronises.
+ *  - Errors are return codes.  Arguments and shapes are checked on the host before any launch;
+ *    a call that fails launches nothing.  hs_last_error() gives the reason as text.
+ *  - Matrices are row-major.  Weights are [out, in] (y = x W^T + b).  The flat parameter order
+ *    is the one hs_param_layout() reports and is the same for w, m, v, g and G.
+ *  - Element type of weights ("w") and activations follows cfg.compute: HS_FP32 -> float,
+ *    HS_BF16 -> bfloat16 (fp32 accumulation everywhere; gradients, LayerNorm/softmax/loss
+ *    statistics and optimizer state are always fp32).
+ *  - Every dev buffer must be 256-byte aligned (what any device allocator returns).
+ */
+#ifndef HETSEQ_HIP_H
+#define HETSEQ_HIP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  HS_OK = 0,
+  HS_ERR_INVALID_ARG = 1, /* null pointer, negative size, bad flag */
+  HS_ERR_SHAPE = 2,       /* sizes the kernels do not support (see each call) */
+  HS_ERR_WORKSPACE = 3,   /* workspace smaller than hs_workspace_bytes() */
+  HS_ERR_STATE = 4,
+  HS_ERR_HIP = 5,         /* a HIP runtime call failed; text in hs_last_error() */
+  HS_ERR_UNIMPLEMENTED = 6
+} hs_status;
+
+typedef enum { HS_FP32 = 0, HS_BF16 = 1 } hs_dtype;
+
+/* Model shape.  Supported: hidden a multiple of 64 and <= 1024, hidden / n_heads == 64,
+ * ffn a multiple of 64, vocab >= 8, 1 <= n_layers, 8 <= max_pos. */
+typedef struct {
+  int32_t n_layers, hidden, n_heads, ffn, vocab, max_pos;
+  float ln_eps;
+  int32_t compute; /* hs_dtype */
+} hs_model_cfg;
+
+/* One slice of the flat parameter buffer.  Vectors have rows == 1. */
+typedef struct {
+  char name[48];
+  int64_t offset; /* in elements */
+  int32_t rows, cols;
+} hs_param_entry;
+
+typedef struct hs_ctx hs_ctx; /* opaque, host-side */
+
+/* ---- context, layout, sizes (host only) ------------------------------------------------- */
+
+/* Validates cfg and builds the host-side tables.  *out is NULL on failure. */
+hs_status hs_ctx_create(const hs_model_cfg* cfg, hs_ctx** out);
+hs_status hs_ctx_destroy(hs_ctx* ctx);
+/* Text of the last error on this context (ctx-owned, valid until the next call on ctx), or of
+ * the last context-free call when ctx is NULL (thread-local). */
+const char* hs_last_error(const hs_ctx* ctx);
+
+/* Number of parameters P of the model (0 when cfg is invalid). */
+size_t hs_param_count(const hs_model_cfg* cfg);
+/* Writes the layout table.  On entry *n is the capacity of out, on exit the number of entries;
+ * with out == NULL only *n is written.  Order: emb.word [V,H], emb.pos [max_pos,H], emb.ln.g,
+ * emb.ln.b, then per layer i: l<i>.qkv.w [3H,H] (rows 0..H-1 query, H..2H-1 key, 2H..3H-1
+ * value), l<i>.qkv.b, l<i>.o.w [H,H], l<i>.o.b, l<i>.ln1.g, l<i>.ln1.b, l<i>.ffn1.w [F,H],
+ * l<i>.ffn1.b, l<i>.ffn2.w [H,F], l<i>.ffn2.b, l<i>.ln2.g, l<i>.ln2.b, then head.t.w [H,H],
+ * head.t.b, head.ln.g, head.ln.b, head.dec.b [V]. */
+hs_status hs_param_layout(const hs_model_cfg* cfg, hs_param_entry* out, int32_t* n);
+
+/* Bytes of the saved-activation arena written by hs_encoder_fwd and read by hs_encoder_bwd for
+ * a batch of B sequences padded to L (M, the number of masked-LM targets, does not enter). */
+size_t hs_acts_bytes(const hs_model_cfg* cfg, int32_t B, int32_t L, int32_t M);
+/* Bytes of scratch that hs_encoder_fwd / hs_mlm_loss / hs_encoder_bwd need for (B, L, M): the
+ * maximum over the three calls, so one buffer serves all. */
+size_t hs_workspace_bytes(const hs_model_cfg* cfg, int32_t B, int32_t L, int32_t M);
+
+/* ---- batch formation (host, integer) ----------------------------------------------------
+ * Section "Forward Pass": batches are formed under a max-instances or max-tokens criterion; the
+ * last batch may be partially filled (section "Optimizer and Learning Rate Scheduler").
+ * Sequences are ordered by (length, index); a sequence of length n is padded to
+ * ceil(n / bucket_width) * bucket_width; inside one padded length, sequences join the open
+ * batch in order until the cap would be exceeded.  cap_mode 0 caps the real tokens of a batch
+ * (sum of lengths), cap_mode 1 caps its padded size (sequences x padded length).
+ * lengths [n] host, each >= 1 and admissible under the cap alone.  Outputs (host, caller
+ * allocated): seq_index_out [n], batch_offsets_out [n + 1] (n_batches + 1 entries used),
+ * batch_pad_len_out [n] (n_batches used).  Returns HS_ERR_INVALID_ARG on a bad argument or a
+ * length that cannot fit; nothing is written in that case except *n_batches_out = 0. */
+hs_status hs_make_batches(const int32_t* lengths, int64_t n, int32_t bucket_width, int64_t max_tokens,
+                          int32_t cap_mode, int32_t* seq_index_out, int64_t* batch_offsets_out,
+                          int32_t* batch_pad_len_out, int64_t* n_batches_out);
+
+/* Key mask of a padded batch: mask_out[b * L + l] = (l < lens[b]) as uint8.  lens [B] dev,
+ * mask_out [B, L] dev.  The attention kernels apply exactly this predicate. */
+hs_status hs_key_mask(const int32_t* lens, int32_t B, int32_t L, uint8_t* mask_out, void* stream);
+
+/* ---- the training step ------------------------------------------------------------------ */
+
+/* Encoder forward (figure 1 "forward step"; section "Forward Pass").
+ * x0 = LN(E[ids] + Pos); per layer (post-LN): attention over the real keys only
+ * (key l' of sequence b takes part iff l' < lens[b]), x' = LN(x + attn W_o^T + b_o),
+ * x'' = LN(x' + GELU(x' W_1^T + b_1) W_2^T + b_2); GELU is the exact erf form.
+ * w: flat parameters, dev, element type per cfg.compute.  ids [B, L] dev int32 in [0, vocab),
+ * lens [B] dev int32 with 1 <= lens[b] <= L (also given on the host as lens_host, which is only
+ * validated, may be NULL to skip validation).  L a multiple of 8, L <= max_pos.
+ * acts: dev, hs_acts_bytes(); hidden_out [B, L, H] dev, activation type.  Rows of padded
+ * positions hold finite don't-care values. */
+hs_status hs_encoder_fwd(hs_ctx* ctx, const void* w, const int32_t* ids, const int32_t* lens,
+                         const int32_t* lens_host, int32_t B, int32_t L, void* acts, void* hidden_out,
+                         void* workspace, size_t workspace_bytes, void* stream);
+
+/* Masked-LM head, loss SUM and its backward (section "Optimizer and Learning Rate Scheduler":
+ * a worker reports a loss together with a weight; no division happens here).
+ * g_m = hidden[mlm_pos[m]]; t = LN(GELU(g W_t^T + b_t)); logits = t E^T + b_dec (decoder tied to
+ * the word embedding); *loss_sum = sum_m [logsumexp(logits_m) - logits_m[label_m]].
+ * Backward with d loss_sum = 1: gradients of head.* and the decoder's share of emb.word go to g
+ * (flat fp32 [P] dev; overwritten in those slices when accumulate == 0, added when 1), and
+ * d_hidden [B, L, H] dev (activation type) is fully written: zeros off the target rows.
+ * mlm_pos [M] dev int32 = b * L + l, strictly ascending, each a real position; mlm_label [M] dev
+ * int32 in [0, vocab).  M == 0 is defined: loss 0, zero d_hidden, g untouched. */
+hs_status hs_mlm_loss(hs_ctx* ctx, const void* w, const void* hidden, const int32_t* mlm_pos,
+                      const int32_t* mlm_label, int32_t M, int32_t B, int32_t L, float* loss_sum,
+                      void* d_hidden, float* g, int32_t accumulate, void* workspace,
+                      size_t workspace_bytes, void* stream);
+
+/* Encoder backward (figure 1 "backpropagation"; section "Backpropagation").
+ * Chain rule through everything hs_encoder_fwd computed, from d_hidden down to the embeddings.
+ * Parameter gradients go to g (flat fp32 [P] dev): slices l<i>.*, emb.pos, emb.ln.* are
+ * overwritten when accumulate == 0 and added when 1; emb.word is ALWAYS added to (the tied
+ * decoder's share is already there), so call hs_mlm_loss first.  With accumulate == 1 and
+ * g == the accumulation buffer G, gradients of successive micro-batches sum in place and no
+ * separate accumulation pass is needed.  Rows of emb.pos beyond L are zero-filled when
+ * accumulate == 0.  d_hidden is read only. */
+hs_status hs_encoder_bwd(hs_ctx* ctx, const void* w, const void* acts, const int32_t* ids,
+                         const int32_t* lens, int32_t B, int32_t L, const void* d_hidden, float* g,
+                         int32_t accumulate, void* workspace, size_t workspace_bytes, void* stream);
+
+/* Delayed update and weighting (sections "Delayed Update (Gradient Accumulation)",
+ * "Backpropagation", "Optimizer and Learning Rate Scheduler").
+ * If ignore == 0 and g != NULL: G += g.  If ignore != 0 (dummy batch of a worker without data)
+ * g is not read at all.  Then, if denom > 0: G /= denom (denom = the global weight: sample or
+ * token count over all micro-batches and workers; the library never counts, the caller does).
+ * denom == 0 means no scaling.  G, g flat fp32 [n] dev.  denom < 0 or NaN -> HS_ERR_INVALID_ARG. */
+hs_status hs_grad_accum_normalize(float* G, const float* g, size_t n, int32_t ignore, double denom,
+                                  void* stream);
+
+/* Fused Adam (section "BERT Language Model": beta1 0.9, beta2 0.999, eps 1e-8, max lr 1e-4; the
+ * learning rate of the step is a host scalar from the caller's schedule).
+ * m = b1 m + (1-b1) G; v = b2 v + (1-b2) G^2; w -= lr * (m / (1-b1^t)) / (sqrt(v / (1-b2^t)) + eps);
+ * weight_decay, when non-zero, is decoupled (w -= lr * wd * w, applied before the Adam term).
+ * w, m, v (in/out) and G (in) flat fp32 [n] dev; w_lowp_out [n] dev bfloat16 or NULL: the
+ * rounded (nearest-even) copy of the new w for the next forward pass.  t >= 1. */
+hs_status hs_adam_step(float* w, float* m, float* v, const float* G, void* w_lowp_out, size_t n,
+                       double lr, double beta1, double beta2, double eps, double weight_decay, int64_t t,
+                       void* stream);
+
+/* fp32 -> activation-type copy of a flat buffer (dst bfloat16 [n] for HS_BF16, float for
+ * HS_FP32); used once to seed the low-precision weights before the first step. */
+hs_status hs_cast_params(const float* src, void* dst, size_t n, int32_t dst_dtype, void* stream);
+
+/* ---- per-kernel timing (optional) -------------------------------------------------------
+ * When enabled, every kernel launch of the ctx-taking calls is bracketed by a pair of HIP
+ * events on the launch stream.  hs_profile_read synchronises those events and returns, per
+ * kernel class, launches, summed milliseconds and the algorithmic flops and bytes the launches
+ * were asked to do.  Off by default; costs two event records per launch when on. */
+typedef struct {
+  char name[32];
+  int64_t launches;
+  double ms;
+  double flops; /* algorithmic: 2*M*N*K for contractions */
+  double bytes; /* algorithmic HBM bytes: operands read once, results written once */
+} hs_profile_entry;
+hs_status hs_profile_enable(hs_ctx* ctx, int32_t on);
+/* On entry *n = capacity of out; on exit the number of classes written.  Resets the counters. */
+hs_status hs_profile_read(hs_ctx* ctx, hs_profile_entry* out, int32_t* n);
+
+/* ---- building blocks (exported so that each kernel can be checked on its own) ------------
+ * Same conventions as above.  dtype is an hs_dtype and selects both element type and kernel
+ * family (HS_FP32: plain fp32 kernels; HS_BF16: MFMA kernels with fp32 accumulation). */
+
+/* C[M,N] = sum_k A(m,k) B(n,k) (+ epilogue).  a_kmajor: A stored [M, lda] with k contiguous,
+ * else [K, lda] with m contiguous; same for B with n.  C is float (c_f32 != 0; C = beta*C + acc)
+ * or the activation type (beta ignored).  bias [N] activation type or NULL.  epi: 0 none;
+ * 1 C += R[m,n] (aux = R, activation type, leading dimension ldaux); 2 C = pre-activation,
+ * C2 = GELU(C) (C2 same type and ldc as C); 3 C = acc * GELU'(aux[m,n]).
+ * In bf16 mode rows of operands must be 16-byte aligned (leading dimensions multiples of 8) and
+ * the 8-element chunk that contains the last valid element of a contiguous row must be readable
+ * and finite. */
+hs_status hs_op_gemm(int32_t dtype, int32_t a_kmajor, int32_t b_kmajor, int32_t M, int32_t N, int32_t K,
+                     const void* A, int64_t lda, const void* B, int64_t ldb, void* C, int64_t ldc,
+                     int32_t c_f32, float beta, const void* bias, int32_t epi, const void* aux,
+                     int64_t ldaux, void* C2, void* stream);
+
+/* y = LN(x) over rows of length H; writes mean and reciprocal std per row (stats [2, R] float). */
+hs_status hs_op_layernorm_fwd(int32_t dtype, const void* x, const void* gain, const void* bias, void* y,
+                              float* stats, int32_t R, int32_t H, float eps, void* stream);
+/* dx = LN backward of dy given the saved input x and stats; d_gain/d_bias/d_colsum [H] float get
+ * beta * old + (sum over rows of dy*xhat / dy / dx); any of the three may be NULL.
+ * partials: dev scratch of hs_op_layernorm_bwd_scratch(R, H) bytes. */
+size_t hs_op_layernorm_bwd_scratch(int32_t R, int32_t H);
+hs_status hs_op_layernorm_bwd(int32_t dtype, const void* dy, const void* x, const float* stats,
+                              const void* gain, void* dx, float* d_gain, float* d_bias, float* d_colsum,
+                              float beta, int32_t R, int32_t H, void* partials, void* stream);
+
+/* Attention over qkv [B*L, 3H] (per row: query | key | value, head h at columns h*64..h*64+63 of
+ * each third): ctx [B*L, H], lse [B, A, L] float (log-sum-exp of the scaled, masked scores). */
+hs_status hs_op_attention_fwd(int32_t dtype, const void* qkv, const int32_t* lens, int32_t B, int32_t L,
+                              int32_t A, void* ctx, float* lse, void* stream);
+/* Backward: dqkv [B*L, 3H] from d_ctx, the saved qkv, ctx and lse.  dvec: dev scratch [B, A, L]
+ * float.  Rows of padded positions are written as zeros. */
+hs_status hs_op_attention_bwd(int32_t dtype, const void* qkv, const void* ctx, const float* lse,
+                              const void* d_ctx, const int32_t* lens, int32_t B, int32_t L, int32_t A,
+                              void* dqkv, float* dvec, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HETSEQ_HIP_H */

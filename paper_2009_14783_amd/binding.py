@@ -1,0 +1,229 @@
+"""ctypes binding of libhetseq_hip.so: the same names as include/hetseq_hip.h, argument
+marshalling only.  torch provides device memory and the stream; every step of the path runs
+in the library's kernels.  A missing library is an error (there is no fallback)."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libhetseq_hip.so")
+
+HS_FP32, HS_BF16 = 0, 1
+STATUS = {0: "HS_OK", 1: "HS_ERR_INVALID_ARG", 2: "HS_ERR_SHAPE", 3: "HS_ERR_WORKSPACE", 4: "HS_ERR_STATE",
+          5: "HS_ERR_HIP", 6: "HS_ERR_UNIMPLEMENTED"}
+
+
+class hs_model_cfg(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("hidden", C.c_int32), ("n_heads", C.c_int32), ("ffn", C.c_int32),
+                ("vocab", C.c_int32), ("max_pos", C.c_int32), ("ln_eps", C.c_float), ("compute", C.c_int32)]
+
+
+class hs_param_entry(C.Structure):
+    _fields_ = [("name", C.c_char * 48), ("offset", C.c_int64), ("rows", C.c_int32), ("cols", C.c_int32)]
+
+
+class hs_profile_entry(C.Structure):
+    _fields_ = [("name", C.c_char * 32), ("launches", C.c_int64), ("ms", C.c_double), ("flops", C.c_double),
+                ("bytes", C.c_double)]
+
+
+class HsError(RuntimeError):
+    def __init__(self, status, msg):
+        super().__init__(f"{STATUS.get(status, status)}: {msg}")
+        self.status = status
+
+
+_lib = None
+
+_P, _I32, _I64, _SZ, _F, _D = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t, C.c_float, C.c_double
+_SIGNATURES = {
+    "hs_ctx_create": (_I32, [C.POINTER(hs_model_cfg), C.POINTER(_P)]),
+    "hs_ctx_destroy": (_I32, [_P]),
+    "hs_last_error": (C.c_char_p, [_P]),
+    "hs_param_count": (_SZ, [C.POINTER(hs_model_cfg)]),
+    "hs_param_layout": (_I32, [C.POINTER(hs_model_cfg), C.POINTER(hs_param_entry), C.POINTER(_I32)]),
+    "hs_acts_bytes": (_SZ, [C.POINTER(hs_model_cfg), _I32, _I32, _I32]),
+    "hs_workspace_bytes": (_SZ, [C.POINTER(hs_model_cfg), _I32, _I32, _I32]),
+    "hs_make_batches": (_I32, [_P, _I64, _I32, _I64, _I32, _P, _P, _P, C.POINTER(_I64)]),
+    "hs_key_mask": (_I32, [_P, _I32, _I32, _P, _P]),
+    "hs_encoder_fwd": (_I32, [_P, _P, _P, _P, _P, _I32, _I32, _P, _P, _P, _SZ, _P]),
+    "hs_mlm_loss": (_I32, [_P, _P, _P, _P, _P, _I32, _I32, _I32, _P, _P, _P, _I32, _P, _SZ, _P]),
+    "hs_encoder_bwd": (_I32, [_P, _P, _P, _P, _P, _I32, _I32, _P, _P, _I32, _P, _SZ, _P]),
+    "hs_grad_accum_normalize": (_I32, [_P, _P, _SZ, _I32, _D, _P]),
+    "hs_adam_step": (_I32, [_P, _P, _P, _P, _P, _SZ, _D, _D, _D, _D, _D, _I64, _P]),
+    "hs_cast_params": (_I32, [_P, _P, _SZ, _I32, _P]),
+    "hs_profile_enable": (_I32, [_P, _I32]),
+    "hs_profile_read": (_I32, [_P, C.POINTER(hs_profile_entry), C.POINTER(_I32)]),
+    "hs_op_gemm": (_I32, [_I32, _I32, _I32, _I32, _I32, _I32, _P, _I64, _P, _I64, _P, _I64, _I32, _F, _P, _I32, _P, _I64, _P, _P]),
+    "hs_op_layernorm_fwd": (_I32, [_I32, _P, _P, _P, _P, _P, _I32, _I32, _F, _P]),
+    "hs_op_layernorm_bwd_scratch": (_SZ, [_I32, _I32]),
+    "hs_op_layernorm_bwd": (_I32, [_I32, _P, _P, _P, _P, _P, _P, _P, _P, _F, _I32, _I32, _P, _P]),
+    "hs_op_attention_fwd": (_I32, [_I32, _P, _P, _I32, _I32, _I32, _P, _P, _P]),
+    "hs_op_attention_bwd": (_I32, [_I32, _P, _P, _P, _P, _P, _I32, _I32, _I32, _P, _P, _P]),
+}
+EXPORTS = tuple(_SIGNATURES)
+
+
+def lib():
+    """The loaded library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise HsError(-1, f"{LIB_PATH} is missing: build it with `python -m paper_2009_14783_amd.build`")
+        l = C.CDLL(LIB_PATH)
+        for name, (res, args) in _SIGNATURES.items():
+            fn = getattr(l, name)
+            fn.restype, fn.argtypes = res, args
+        _lib = l
+    return _lib
+
+
+def _ptr(t):
+    """Device/host address of a torch tensor or numpy array (None -> NULL)."""
+    if t is None:
+        return None
+    if isinstance(t, np.ndarray):
+        return t.ctypes.data
+    if isinstance(t, int):
+        return t
+    return t.data_ptr()
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    return stream if isinstance(stream, int) else stream.cuda_stream
+
+
+def _check(status, ctx=None):
+    if status != 0:
+        msg = lib().hs_last_error(ctx)
+        raise HsError(status, msg.decode() if msg else "")
+
+
+def make_cfg(n_layers, hidden, n_heads, ffn, vocab, max_pos, ln_eps=1e-12, compute=HS_BF16) -> hs_model_cfg:
+    return hs_model_cfg(n_layers, hidden, n_heads, ffn, vocab, max_pos, ln_eps, compute)
+
+
+# ---- host-only calls ---------------------------------------------------------------------
+def hs_ctx_create(cfg: hs_model_cfg):
+    out = _P()
+    _check(lib().hs_ctx_create(C.byref(cfg), C.byref(out)))
+    return out
+
+
+def hs_ctx_destroy(ctx):
+    _check(lib().hs_ctx_destroy(ctx))
+
+
+def hs_param_count(cfg) -> int:
+    return int(lib().hs_param_count(C.byref(cfg)))
+
+
+def hs_param_layout(cfg):
+    """List of (name, offset, rows, cols)."""
+    n = _I32(0)
+    _check(lib().hs_param_layout(C.byref(cfg), None, C.byref(n)))
+    arr = (hs_param_entry * n.value)()
+    _check(lib().hs_param_layout(C.byref(cfg), arr, C.byref(n)))
+    return [(e.name.decode(), int(e.offset), int(e.rows), int(e.cols)) for e in arr[:n.value]]
+
+
+def hs_acts_bytes(cfg, B, L, M) -> int:
+    return int(lib().hs_acts_bytes(C.byref(cfg), B, L, M))
+
+
+def hs_workspace_bytes(cfg, B, L, M) -> int:
+    return int(lib().hs_workspace_bytes(C.byref(cfg), B, L, M))
+
+
+def hs_make_batches(lengths, bucket_width, max_tokens, cap_mode=0):
+    """Returns (seq_index, batch_offsets, batch_pad_len) as numpy arrays trimmed to size."""
+    lengths = np.ascontiguousarray(lengths, dtype=np.int32)
+    n = lengths.size
+    seq = np.zeros(max(n, 1), dtype=np.int32)
+    offs = np.zeros(n + 1, dtype=np.int64)
+    pads = np.zeros(max(n, 1), dtype=np.int32)
+    nb = _I64(0)
+    _check(lib().hs_make_batches(lengths.ctypes.data, n, bucket_width, max_tokens, cap_mode, seq.ctypes.data,
+                                 offs.ctypes.data, pads.ctypes.data, C.byref(nb)))
+    return seq[:n], offs[:nb.value + 1], pads[:nb.value]
+
+
+# ---- device calls --------------------------------------------------------------------------
+def hs_key_mask(lens, B, L, mask_out, stream=None):
+    _check(lib().hs_key_mask(_ptr(lens), B, L, _ptr(mask_out), _stream(stream)))
+
+
+def hs_encoder_fwd(ctx, w, ids, lens, lens_host, B, L, acts, hidden_out, workspace, workspace_bytes, stream=None):
+    _check(lib().hs_encoder_fwd(ctx, _ptr(w), _ptr(ids), _ptr(lens), _ptr(lens_host), B, L, _ptr(acts), _ptr(hidden_out),
+                                _ptr(workspace), workspace_bytes, _stream(stream)), ctx)
+
+
+def hs_mlm_loss(ctx, w, hidden, mlm_pos, mlm_label, M, B, L, loss_sum, d_hidden, g, accumulate, workspace,
+                workspace_bytes, stream=None):
+    _check(lib().hs_mlm_loss(ctx, _ptr(w), _ptr(hidden), _ptr(mlm_pos), _ptr(mlm_label), M, B, L, _ptr(loss_sum),
+                             _ptr(d_hidden), _ptr(g), accumulate, _ptr(workspace), workspace_bytes, _stream(stream)), ctx)
+
+
+def hs_encoder_bwd(ctx, w, acts, ids, lens, B, L, d_hidden, g, accumulate, workspace, workspace_bytes, stream=None):
+    _check(lib().hs_encoder_bwd(ctx, _ptr(w), _ptr(acts), _ptr(ids), _ptr(lens), B, L, _ptr(d_hidden), _ptr(g), accumulate,
+                                _ptr(workspace), workspace_bytes, _stream(stream)), ctx)
+
+
+def hs_grad_accum_normalize(G, g, n, ignore, denom, stream=None):
+    _check(lib().hs_grad_accum_normalize(_ptr(G), _ptr(g), n, ignore, float(denom), _stream(stream)))
+
+
+def hs_adam_step(w, m, v, G, w_lowp_out, n, lr, beta1, beta2, eps, weight_decay, t, stream=None):
+    _check(lib().hs_adam_step(_ptr(w), _ptr(m), _ptr(v), _ptr(G), _ptr(w_lowp_out), n, lr, beta1, beta2, eps, weight_decay,
+                              t, _stream(stream)))
+
+
+def hs_cast_params(src, dst, n, dst_dtype, stream=None):
+    _check(lib().hs_cast_params(_ptr(src), _ptr(dst), n, dst_dtype, _stream(stream)))
+
+
+def hs_profile_enable(ctx, on):
+    _check(lib().hs_profile_enable(ctx, 1 if on else 0), ctx)
+
+
+def hs_profile_read(ctx):
+    """dict name -> dict(launches, ms, flops, bytes); synchronises the recorded events."""
+    n = _I32(32)
+    arr = (hs_profile_entry * 32)()
+    _check(lib().hs_profile_read(ctx, arr, C.byref(n)), ctx)
+    return {e.name.decode(): dict(launches=int(e.launches), ms=float(e.ms), flops=float(e.flops), bytes=float(e.bytes))
+            for e in arr[:n.value]}
+
+
+def hs_op_gemm(dtype, a_kmajor, b_kmajor, M, N, K, A, lda, B, ldb, Cm, ldc, c_f32=0, beta=0.0, bias=None, epi=0, aux=None,
+               ldaux=0, C2=None, stream=None):
+    _check(lib().hs_op_gemm(dtype, a_kmajor, b_kmajor, M, N, K, _ptr(A), lda, _ptr(B), ldb, _ptr(Cm), ldc, c_f32, beta,
+                            _ptr(bias), epi, _ptr(aux), ldaux, _ptr(C2), _stream(stream)))
+
+
+def hs_op_layernorm_fwd(dtype, x, gain, bias, y, stats, R, H, eps, stream=None):
+    _check(lib().hs_op_layernorm_fwd(dtype, _ptr(x), _ptr(gain), _ptr(bias), _ptr(y), _ptr(stats), R, H, eps, _stream(stream)))
+
+
+def hs_op_layernorm_bwd_scratch(R, H) -> int:
+    return int(lib().hs_op_layernorm_bwd_scratch(R, H))
+
+
+def hs_op_layernorm_bwd(dtype, dy, x, stats, gain, dx, d_gain, d_bias, d_colsum, beta, R, H, partials, stream=None):
+    _check(lib().hs_op_layernorm_bwd(dtype, _ptr(dy), _ptr(x), _ptr(stats), _ptr(gain), _ptr(dx), _ptr(d_gain), _ptr(d_bias),
+                                     _ptr(d_colsum), beta, R, H, _ptr(partials), _stream(stream)))
+
+
+def hs_op_attention_fwd(dtype, qkv, lens, B, L, A, ctx_out, lse, stream=None):
+    _check(lib().hs_op_attention_fwd(dtype, _ptr(qkv), _ptr(lens), B, L, A, _ptr(ctx_out), _ptr(lse), _stream(stream)))
+
+
+def hs_op_attention_bwd(dtype, qkv, ctx_in, lse, d_ctx, lens, B, L, A, dqkv, dvec, stream=None):
+    _check(lib().hs_op_attention_bwd(dtype, _ptr(qkv), _ptr(ctx_in), _ptr(lse), _ptr(d_ctx), _ptr(lens), B, L, A, _ptr(dqkv),
+                                     _ptr(dvec), _stream(stream)))

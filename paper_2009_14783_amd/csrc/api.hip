@@ -1,0 +1,339 @@
+// The training-step entry points: encoder forward, masked-LM loss (forward + backward of the
+// head), encoder backward; plus the exported building blocks.  Host orchestration only: every
+// arithmetic step is a kernel in gemm.hip / attention.hip / rowops.hip.
+#include "common.h"
+
+namespace {
+
+struct Carver {
+  char* base; size_t off;
+  explicit Carver(void* p) : base((char*)p), off(0) {}
+  void* take(size_t bytes) { void* r = base ? base + off : nullptr; off += align_up(bytes, 256); return r; }
+};
+
+struct LayerActs { void *qkv, *ctx, *y1, *x1, *hpre, *h, *y2, *x2; float *lse, *st1, *st2; };
+struct Acts {
+  void *e_pre, *x0; float* emb_stats;
+  std::vector<LayerActs> layer;
+  size_t total;
+};
+
+Acts carve_acts(const hs_model_cfg& c, int B, int L, void* base) {
+  const size_t T = (size_t)B * L, H = c.hidden, F = c.ffn, es = esize(c.compute);
+  Carver cv(base);
+  Acts a;
+  a.e_pre = cv.take(T * H * es); a.x0 = cv.take(T * H * es); a.emb_stats = (float*)cv.take(2 * T * sizeof(float));
+  a.layer.resize(c.n_layers);
+  for (int i = 0; i < c.n_layers; ++i) {
+    LayerActs& l = a.layer[i];
+    l.qkv = cv.take(T * 3 * H * es);
+    l.lse = (float*)cv.take((size_t)B * c.n_heads * L * sizeof(float));
+    l.ctx = cv.take(T * H * es);
+    l.y1 = cv.take(T * H * es); l.st1 = (float*)cv.take(2 * T * sizeof(float)); l.x1 = cv.take(T * H * es);
+    l.hpre = cv.take(T * F * es); l.h = cv.take(T * F * es);
+    l.y2 = cv.take(T * H * es); l.st2 = (float*)cv.take(2 * T * sizeof(float));
+    l.x2 = (i + 1 < c.n_layers) ? cv.take(T * H * es) : nullptr;   // the last layer writes hidden_out
+  }
+  a.total = cv.off;
+  return a;
+}
+
+int padded_vocab(int V) { return (V + 63) / 64 * 64; }
+
+struct HeadWs {
+  void *grow, *tpre, *tact, *t, *dlogits, *dt, *dtact, *dtpre, *dg, *ln_part, *cs_part;
+  float *stats, *logits, *row_loss;
+  size_t total;
+};
+HeadWs carve_head(const hs_model_cfg& c, int M, void* base) {
+  const size_t H = c.hidden, es = esize(c.compute), Vp = padded_vocab(c.vocab), m = (size_t)M;
+  Carver cv(base);
+  HeadWs w;
+  w.grow = cv.take(m * H * es); w.tpre = cv.take(m * H * es); w.tact = cv.take(m * H * es); w.t = cv.take(m * H * es);
+  w.stats = (float*)cv.take(2 * m * sizeof(float));
+  w.logits = (float*)cv.take(m * Vp * sizeof(float));
+  w.dlogits = cv.take(m * Vp * es);
+  w.row_loss = (float*)cv.take(m * sizeof(float));
+  w.dt = cv.take(m * H * es); w.dtact = cv.take(m * H * es); w.dtpre = cv.take(m * H * es); w.dg = cv.take(m * H * es);
+  w.ln_part = cv.take(layernorm_bwd_scratch(M, (int)H));
+  w.cs_part = cv.take(colsum_scratch(M, (int)Vp));
+  w.total = cv.off;
+  return w;
+}
+
+struct BwdWs {
+  void *dxa, *dxb, *dy, *dh, *dctx, *dqkv, *ln_part, *cs_part, *emb;
+  float* dvec;
+  size_t total;
+};
+BwdWs carve_bwd(const hs_model_cfg& c, int B, int L, void* base) {
+  const size_t T = (size_t)B * L, H = c.hidden, F = c.ffn, es = esize(c.compute);
+  Carver cv(base);
+  BwdWs w;
+  w.dxa = cv.take(T * H * es); w.dxb = cv.take(T * H * es); w.dy = cv.take(T * H * es);
+  w.dh = cv.take(T * F * es); w.dctx = cv.take(T * H * es); w.dqkv = cv.take(T * 3 * H * es);
+  w.dvec = (float*)cv.take((size_t)B * c.n_heads * L * sizeof(float));
+  w.ln_part = cv.take(layernorm_bwd_scratch((int)T, (int)H));
+  w.cs_part = cv.take(colsum_scratch((int)T, (int)std::max(F, 3 * H)));
+  w.emb = cv.take(embed_bwd_scratch((int)T, (int)H));
+  w.total = cv.off;
+  return w;
+}
+
+bool shape_ok(hs_ctx* ctx, int B, int L, std::string* why) {
+  if (B < 0 || L < 1) { *why = "B < 0 or L < 1"; return false; }
+  if (L % 8) { *why = "L must be a multiple of 8"; return false; }
+  if (L > ctx->cfg.max_pos) { *why = "L exceeds max_pos"; return false; }
+  if ((int64_t)B * L > (int64_t)1 << 24) { *why = "B*L too large"; return false; }
+  return true;
+}
+
+template <class T> const void* wptr(const void* w, int64_t off) { return (const T*)w + off; }
+const void* W(const hs_ctx* ctx, const void* w, int64_t off) {
+  return ctx->cfg.compute == HS_BF16 ? wptr<bf16>(w, off) : wptr<float>(w, off);
+}
+
+GemmArgs gemm_args(int dtype, int ak, int bk, int M, int N, int K, const void* A, int64_t lda, const void* B, int64_t ldb, void* C,
+                   int64_t ldc) {
+  GemmArgs g{};
+  g.dtype = dtype; g.a_kmajor = ak; g.b_kmajor = bk; g.M = M; g.N = N; g.K = K;
+  g.A = A; g.lda = lda; g.B = B; g.ldb = ldb; g.C = C; g.ldc = ldc;
+  g.c_f32 = 0; g.beta = 0.f; g.bias = nullptr; g.epi = 0; g.aux = nullptr; g.ldaux = 0; g.C2 = nullptr;
+  return g;
+}
+
+#define HS_TRY(expr) do { hs_status st_ = (expr); if (st_ != HS_OK) return st_; } while (0)
+
+}  // namespace
+
+extern "C" {
+
+size_t hs_acts_bytes(const hs_model_cfg* cfg, int32_t B, int32_t L, int32_t M) {
+  (void)M;
+  if (!hs_cfg_valid(cfg, nullptr) || B < 0 || L < 0) return 0;
+  return carve_acts(*cfg, B, L, nullptr).total;
+}
+
+size_t hs_workspace_bytes(const hs_model_cfg* cfg, int32_t B, int32_t L, int32_t M) {
+  if (!hs_cfg_valid(cfg, nullptr) || B < 0 || L < 0 || M < 0) return 0;
+  const size_t a = carve_head(*cfg, M, nullptr).total, b = carve_bwd(*cfg, B, L, nullptr).total;
+  return std::max<size_t>(std::max(a, b), 256);
+}
+
+hs_status hs_encoder_fwd(hs_ctx* ctx, const void* w, const int32_t* ids, const int32_t* lens, const int32_t* lens_host, int32_t B,
+                         int32_t L, void* acts, void* hidden_out, void* workspace, size_t workspace_bytes, void* stream) {
+  (void)workspace; (void)workspace_bytes;
+  if (!ctx) return HS_ERR_INVALID_ARG;
+  std::string why;
+  if (!shape_ok(ctx, B, L, &why)) return hs_fail(ctx, HS_ERR_SHAPE, "hs_encoder_fwd: " + why);
+  if (B == 0) return HS_OK;
+  if (!w || !ids || !lens || !acts || !hidden_out) return hs_fail(ctx, HS_ERR_INVALID_ARG, "hs_encoder_fwd: NULL buffer");
+  if (lens_host)
+    for (int b = 0; b < B; ++b)
+      if (lens_host[b] < 1 || lens_host[b] > L) return hs_fail(ctx, HS_ERR_INVALID_ARG, "hs_encoder_fwd: lens[b] outside [1, L]");
+  const hs_model_cfg& c = ctx->cfg;
+  const ModelOff& o = ctx->off;
+  const int dt = c.compute, H = c.hidden, F = c.ffn, T = B * L;
+  hipStream_t s = (hipStream_t)stream;
+  Acts a = carve_acts(c, B, L, acts);
+
+  HS_TRY(launch_embed_ln_fwd(ctx, dt, W(ctx, w, o.emb_word), W(ctx, w, o.emb_pos), W(ctx, w, o.emb_ln_g), W(ctx, w, o.emb_ln_b), ids,
+                             a.e_pre, a.x0, a.emb_stats, B, L, H, c.vocab, c.ln_eps, s));
+  const void* x = a.x0;
+  for (int i = 0; i < c.n_layers; ++i) {
+    const LayerOff& lo = o.layer[i];
+    LayerActs& la = a.layer[i];
+    void* x2 = la.x2 ? la.x2 : hidden_out;
+    // q | k | v = x Wqkv^T + b
+    GemmArgs g = gemm_args(dt, 1, 1, T, 3 * H, H, x, H, W(ctx, w, lo.qkv_w), H, la.qkv, 3 * H);
+    g.bias = W(ctx, w, lo.qkv_b);
+    HS_TRY(launch_gemm(ctx, g, s));
+    HS_TRY(launch_attention_fwd(ctx, dt, la.qkv, lens, B, L, c.n_heads, la.ctx, la.lse, s));
+    // y1 = x + ctx Wo^T + bo ; x1 = LN(y1)
+    g = gemm_args(dt, 1, 1, T, H, H, la.ctx, H, W(ctx, w, lo.o_w), H, la.y1, H);
+    g.bias = W(ctx, w, lo.o_b); g.epi = 1; g.aux = x; g.ldaux = H;
+    HS_TRY(launch_gemm(ctx, g, s));
+    HS_TRY(launch_layernorm_fwd(ctx, dt, la.y1, W(ctx, w, lo.ln1_g), W(ctx, w, lo.ln1_b), la.x1, la.st1, T, H, c.ln_eps, s));
+    // hpre = x1 W1^T + b1 ; h = GELU(hpre)
+    g = gemm_args(dt, 1, 1, T, F, H, la.x1, H, W(ctx, w, lo.ffn1_w), H, la.hpre, F);
+    g.bias = W(ctx, w, lo.ffn1_b); g.epi = 2; g.C2 = la.h;
+    HS_TRY(launch_gemm(ctx, g, s));
+    // y2 = x1 + h W2^T + b2 ; x2 = LN(y2)
+    g = gemm_args(dt, 1, 1, T, H, F, la.h, F, W(ctx, w, lo.ffn2_w), F, la.y2, H);
+    g.bias = W(ctx, w, lo.ffn2_b); g.epi = 1; g.aux = la.x1; g.ldaux = H;
+    HS_TRY(launch_gemm(ctx, g, s));
+    HS_TRY(launch_layernorm_fwd(ctx, dt, la.y2, W(ctx, w, lo.ln2_g), W(ctx, w, lo.ln2_b), x2, la.st2, T, H, c.ln_eps, s));
+    x = x2;
+  }
+  return HS_OK;
+}
+
+hs_status hs_mlm_loss(hs_ctx* ctx, const void* w, const void* hidden, const int32_t* mlm_pos, const int32_t* mlm_label, int32_t M,
+                      int32_t B, int32_t L, float* loss_sum, void* d_hidden, float* g, int32_t accumulate, void* workspace,
+                      size_t workspace_bytes, void* stream) {
+  if (!ctx) return HS_ERR_INVALID_ARG;
+  std::string why;
+  if (!shape_ok(ctx, B, L, &why)) return hs_fail(ctx, HS_ERR_SHAPE, "hs_mlm_loss: " + why);
+  if (M < 0 || (int64_t)M > (int64_t)B * L) return hs_fail(ctx, HS_ERR_INVALID_ARG, "hs_mlm_loss: M outside [0, B*L]");
+  if (!loss_sum || (B > 0 && !d_hidden)) return hs_fail(ctx, HS_ERR_INVALID_ARG, "hs_mlm_loss: NULL output");
+  const hs_model_cfg& c = ctx->cfg;
+  const ModelOff& o = ctx->off;
+  const int dt = c.compute, H = c.hidden, V = c.vocab, Vp = padded_vocab(V);
+  const size_t es = esize(dt);
+  hipStream_t s = (hipStream_t)stream;
+  if (M > 0) {
+    if (!w || !hidden || !mlm_pos || !mlm_label || !g || !workspace) return hs_fail(ctx, HS_ERR_INVALID_ARG, "hs_mlm_loss: NULL buffer");
+    if (workspace_bytes < carve_head(c, M, nullptr).total) return hs_fail(ctx, HS_ERR_WORKSPACE, "hs_mlm_loss: workspace too small");
+  }
+  HS_TRY(launch_fill_zero(ctx, d_hidden, (size_t)B * L * H * es, s));
+  if (M == 0) {
+    // defined: loss 0, zero d_hidden, g untouched
+    return launch_fill_zero(ctx, loss_sum, sizeof(float), s);
+  }
+  HeadWs h = carve_head(c, M, workspace);
+  const float beta = accumulate ? 1.f : 0.f;
+
+  HS_TRY(launch_gather_rows(ctx, dt, hidden, mlm_pos, M, H, h.grow, s));
+  GemmArgs ga = gemm_args(dt, 1, 1, M, H, H, h.grow, H, W(ctx, w, o.head_t_w), H, h.tpre, H);
+  ga.bias = W(ctx, w, o.head_t_b); ga.epi = 2; ga.C2 = h.tact;
+  HS_TRY(launch_gemm(ctx, ga, s));
+  HS_TRY(launch_layernorm_fwd(ctx, dt, h.tact, W(ctx, w, o.head_ln_g), W(ctx, w, o.head_ln_b), h.t, h.stats, M, H, c.ln_eps, s));
+  // logits = t E^T + b_dec, fp32, row stride Vp
+  ga = gemm_args(dt, 1, 1, M, V, H, h.t, H, W(ctx, w, o.emb_word), H, h.logits, Vp);
+  ga.c_f32 = 1; ga.beta = 0.f; ga.bias = W(ctx, w, o.head_dec_b);
+  HS_TRY(launch_gemm(ctx, ga, s));
+  HS_TRY(launch_ce_loss(ctx, dt, h.logits, Vp, mlm_label, M, V, h.dlogits, h.row_loss, loss_sum, s));
+  // decoder bias and the decoder's share of the tied word embedding
+  HS_TRY(launch_colsum(ctx, dt, h.dlogits, Vp, M, V, g + o.head_dec_b, beta, h.cs_part, s));
+  ga = gemm_args(dt, 0, 0, V, H, M, h.dlogits, Vp, h.t, H, g + o.emb_word, H);
+  ga.c_f32 = 1; ga.beta = beta;
+  HS_TRY(launch_gemm(ctx, ga, s));
+  // dt = dlogits E
+  ga = gemm_args(dt, 1, 0, M, H, V, h.dlogits, Vp, W(ctx, w, o.emb_word), H, h.dt, H);
+  HS_TRY(launch_gemm(ctx, ga, s));
+  HS_TRY(launch_layernorm_bwd(ctx, dt, h.dt, h.tact, h.stats, W(ctx, w, o.head_ln_g), h.dtact, g + o.head_ln_g, g + o.head_ln_b, nullptr,
+                              beta, M, H, h.ln_part, s));
+  HS_TRY(launch_gelu_bwd(ctx, dt, h.dtact, h.tpre, h.dtpre, (size_t)M * H, s));
+  HS_TRY(launch_colsum(ctx, dt, h.dtpre, H, M, H, g + o.head_t_b, beta, h.cs_part, s));
+  ga = gemm_args(dt, 0, 0, H, H, M, h.dtpre, H, h.grow, H, g + o.head_t_w, H);
+  ga.c_f32 = 1; ga.beta = beta;
+  HS_TRY(launch_gemm(ctx, ga, s));
+  ga = gemm_args(dt, 1, 0, M, H, H, h.dtpre, H, W(ctx, w, o.head_t_w), H, h.dg, H);
+  HS_TRY(launch_gemm(ctx, ga, s));
+  HS_TRY(launch_scatter_rows(ctx, dt, h.dg, mlm_pos, M, H, d_hidden, s));
+  return HS_OK;
+}
+
+hs_status hs_encoder_bwd(hs_ctx* ctx, const void* w, const void* acts, const int32_t* ids, const int32_t* lens, int32_t B, int32_t L,
+                         const void* d_hidden, float* g, int32_t accumulate, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!ctx) return HS_ERR_INVALID_ARG;
+  std::string why;
+  if (!shape_ok(ctx, B, L, &why)) return hs_fail(ctx, HS_ERR_SHAPE, "hs_encoder_bwd: " + why);
+  if (B == 0) return HS_OK;
+  if (!w || !acts || !ids || !lens || !d_hidden || !g || !workspace) return hs_fail(ctx, HS_ERR_INVALID_ARG, "hs_encoder_bwd: NULL buffer");
+  const hs_model_cfg& c = ctx->cfg;
+  const ModelOff& o = ctx->off;
+  if (workspace_bytes < carve_bwd(c, B, L, nullptr).total) return hs_fail(ctx, HS_ERR_WORKSPACE, "hs_encoder_bwd: workspace too small");
+  const int dt = c.compute, H = c.hidden, F = c.ffn, T = B * L;
+  hipStream_t s = (hipStream_t)stream;
+  Acts a = carve_acts(c, B, L, const_cast<void*>(acts));
+  BwdWs ws = carve_bwd(c, B, L, workspace);
+  const float beta = accumulate ? 1.f : 0.f;
+
+  const void* dcur = d_hidden;
+  for (int i = c.n_layers - 1; i >= 0; --i) {
+    const LayerOff& lo = o.layer[i];
+    LayerActs& la = a.layer[i];
+    const void* x_in = (i == 0) ? a.x0 : a.layer[i - 1].x2;
+    // LN2 backward: dy2, d gain/bias, and colsum(dy2) = d b2
+    HS_TRY(launch_layernorm_bwd(ctx, dt, dcur, la.y2, la.st2, W(ctx, w, lo.ln2_g), ws.dy, g + lo.ln2_g, g + lo.ln2_b, g + lo.ffn2_b, beta,
+                                T, H, ws.ln_part, s));
+    // dW2 [H,F] = dy2^T h
+    GemmArgs ga = gemm_args(dt, 0, 0, H, F, T, ws.dy, H, la.h, F, g + lo.ffn2_w, F);
+    ga.c_f32 = 1; ga.beta = beta;
+    HS_TRY(launch_gemm(ctx, ga, s));
+    // dhpre [T,F] = (dy2 W2) * GELU'(hpre)
+    ga = gemm_args(dt, 1, 0, T, F, H, ws.dy, H, W(ctx, w, lo.ffn2_w), F, ws.dh, F);
+    ga.epi = 3; ga.aux = la.hpre; ga.ldaux = F;
+    HS_TRY(launch_gemm(ctx, ga, s));
+    HS_TRY(launch_colsum(ctx, dt, ws.dh, F, T, F, g + lo.ffn1_b, beta, ws.cs_part, s));
+    // dW1 [F,H] = dhpre^T x1
+    ga = gemm_args(dt, 0, 0, F, H, T, ws.dh, F, la.x1, H, g + lo.ffn1_w, H);
+    ga.c_f32 = 1; ga.beta = beta;
+    HS_TRY(launch_gemm(ctx, ga, s));
+    // dx1 [T,H] = dhpre W1 + dy2
+    ga = gemm_args(dt, 1, 0, T, H, F, ws.dh, F, W(ctx, w, lo.ffn1_w), H, ws.dxa, H);
+    ga.epi = 1; ga.aux = ws.dy; ga.ldaux = H;
+    HS_TRY(launch_gemm(ctx, ga, s));
+    // LN1 backward: dy1, d gain/bias, colsum(dy1) = d bo
+    HS_TRY(launch_layernorm_bwd(ctx, dt, ws.dxa, la.y1, la.st1, W(ctx, w, lo.ln1_g), ws.dy, g + lo.ln1_g, g + lo.ln1_b, g + lo.o_b, beta, T,
+                                H, ws.ln_part, s));
+    // dWo [H,H] = dy1^T ctx ; dctx = dy1 Wo
+    ga = gemm_args(dt, 0, 0, H, H, T, ws.dy, H, la.ctx, H, g + lo.o_w, H);
+    ga.c_f32 = 1; ga.beta = beta;
+    HS_TRY(launch_gemm(ctx, ga, s));
+    ga = gemm_args(dt, 1, 0, T, H, H, ws.dy, H, W(ctx, w, lo.o_w), H, ws.dctx, H);
+    HS_TRY(launch_gemm(ctx, ga, s));
+    HS_TRY(launch_attention_bwd(ctx, dt, la.qkv, la.ctx, la.lse, ws.dctx, lens, B, L, c.n_heads, ws.dqkv, ws.dvec, s));
+    HS_TRY(launch_colsum(ctx, dt, ws.dqkv, 3 * H, T, 3 * H, g + lo.qkv_b, beta, ws.cs_part, s));
+    // dWqkv [3H,H] = dqkv^T x_in ; dx_in = dqkv Wqkv + dy1
+    ga = gemm_args(dt, 0, 0, 3 * H, H, T, ws.dqkv, 3 * H, x_in, H, g + lo.qkv_w, H);
+    ga.c_f32 = 1; ga.beta = beta;
+    HS_TRY(launch_gemm(ctx, ga, s));
+    ga = gemm_args(dt, 1, 0, T, H, 3 * H, ws.dqkv, 3 * H, W(ctx, w, lo.qkv_w), H, ws.dxb, H);
+    ga.epi = 1; ga.aux = ws.dy; ga.ldaux = H;
+    HS_TRY(launch_gemm(ctx, ga, s));
+    dcur = ws.dxb;
+  }
+  // embedding LayerNorm, then the two embedding tables
+  HS_TRY(launch_layernorm_bwd(ctx, dt, dcur, a.e_pre, a.emb_stats, W(ctx, w, o.emb_ln_g), ws.dy, g + o.emb_ln_g, g + o.emb_ln_b, nullptr, beta,
+                              T, H, ws.ln_part, s));
+  HS_TRY(launch_embed_bwd(ctx, dt, ws.dy, ids, B, L, H, c.vocab, c.max_pos, g + o.emb_word, g + o.emb_pos, beta, ws.emb, s));
+  return HS_OK;
+}
+
+// ---- building blocks ----------------------------------------------------------------------------
+hs_status hs_op_gemm(int32_t dtype, int32_t a_kmajor, int32_t b_kmajor, int32_t M, int32_t N, int32_t K, const void* A, int64_t lda,
+                     const void* B, int64_t ldb, void* C, int64_t ldc, int32_t c_f32, float beta, const void* bias, int32_t epi,
+                     const void* aux, int64_t ldaux, void* C2, void* stream) {
+  if (dtype != HS_FP32 && dtype != HS_BF16) return hs_fail(nullptr, HS_ERR_INVALID_ARG, "hs_op_gemm: bad dtype");
+  if (M < 0 || N < 0 || K < 0) return hs_fail(nullptr, HS_ERR_INVALID_ARG, "hs_op_gemm: negative size");
+  GemmArgs g = gemm_args(dtype, a_kmajor ? 1 : 0, b_kmajor ? 1 : 0, M, N, K, A, lda, B, ldb, C, ldc);
+  g.c_f32 = c_f32 ? 1 : 0; g.beta = beta; g.bias = bias; g.epi = epi; g.aux = aux; g.ldaux = ldaux; g.C2 = C2;
+  return launch_gemm(nullptr, g, (hipStream_t)stream);
+}
+
+static bool ln_shape_ok(int R, int H) { return R >= 0 && H >= 64 && H % 64 == 0 && H <= 1024; }
+
+hs_status hs_op_layernorm_fwd(int32_t dtype, const void* x, const void* gain, const void* bias, void* y, float* stats, int32_t R,
+                              int32_t H, float eps, void* stream) {
+  if (!ln_shape_ok(R, H)) return hs_fail(nullptr, HS_ERR_SHAPE, "hs_op_layernorm_fwd: H must be a multiple of 64, <= 1024");
+  if (R > 0 && (!x || !gain || !bias || !y || !stats)) return hs_fail(nullptr, HS_ERR_INVALID_ARG, "hs_op_layernorm_fwd: NULL buffer");
+  return launch_layernorm_fwd(nullptr, dtype, x, gain, bias, y, stats, R, H, eps, (hipStream_t)stream);
+}
+
+size_t hs_op_layernorm_bwd_scratch(int32_t R, int32_t H) { return ln_shape_ok(R, H) ? layernorm_bwd_scratch(R, H) : 0; }
+
+hs_status hs_op_layernorm_bwd(int32_t dtype, const void* dy, const void* x, const float* stats, const void* gain, void* dx, float* d_gain,
+                              float* d_bias, float* d_colsum, float beta, int32_t R, int32_t H, void* partials, void* stream) {
+  if (!ln_shape_ok(R, H)) return hs_fail(nullptr, HS_ERR_SHAPE, "hs_op_layernorm_bwd: H must be a multiple of 64, <= 1024");
+  if (R > 0 && (!dy || !x || !stats || !gain || !dx || !partials)) return hs_fail(nullptr, HS_ERR_INVALID_ARG, "hs_op_layernorm_bwd: NULL buffer");
+  return launch_layernorm_bwd(nullptr, dtype, dy, x, stats, gain, dx, d_gain, d_bias, d_colsum, beta, R, H, partials, (hipStream_t)stream);
+}
+
+hs_status hs_op_attention_fwd(int32_t dtype, const void* qkv, const int32_t* lens, int32_t B, int32_t L, int32_t A, void* ctx_out,
+                              float* lse, void* stream) {
+  if (B < 0 || L < 0 || A < 1) return hs_fail(nullptr, HS_ERR_INVALID_ARG, "hs_op_attention_fwd: bad size");
+  if (B > 0 && L > 0 && (!qkv || !lens || !ctx_out || !lse)) return hs_fail(nullptr, HS_ERR_INVALID_ARG, "hs_op_attention_fwd: NULL buffer");
+  return launch_attention_fwd(nullptr, dtype, qkv, lens, B, L, A, ctx_out, lse, (hipStream_t)stream);
+}
+
+hs_status hs_op_attention_bwd(int32_t dtype, const void* qkv, const void* ctx_in, const float* lse, const void* d_ctx, const int32_t* lens,
+                              int32_t B, int32_t L, int32_t A, void* dqkv, float* dvec, void* stream) {
+  if (B < 0 || L < 0 || A < 1) return hs_fail(nullptr, HS_ERR_INVALID_ARG, "hs_op_attention_bwd: bad size");
+  if (B > 0 && L > 0 && (!qkv || !ctx_in || !lse || !d_ctx || !lens || !dqkv || !dvec))
+    return hs_fail(nullptr, HS_ERR_INVALID_ARG, "hs_op_attention_bwd: NULL buffer");
+  return launch_attention_bwd(nullptr, dtype, qkv, ctx_in, lse, d_ctx, lens, B, L, A, dqkv, dvec, (hipStream_t)stream);
+}
+
+}  // extern "C"

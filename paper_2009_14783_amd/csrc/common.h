@@ -1,0 +1,141 @@
+// Shared device/host helpers of libhetseq_hip (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <string>
+#include <vector>
+
+#include "hetseq_hip.h"
+
+typedef __bf16 bf16;
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+#define HS_WAVE 64
+
+template <class T> __device__ __forceinline__ float to_f(T x);
+template <> __device__ __forceinline__ float to_f<float>(float x) { return x; }
+template <> __device__ __forceinline__ float to_f<bf16>(bf16 x) { return (float)x; }
+template <class T> __device__ __forceinline__ T from_f(float x);
+template <> __device__ __forceinline__ float from_f<float>(float x) { return x; }
+template <> __device__ __forceinline__ bf16 from_f<bf16>(float x) { return (bf16)x; }  // round to nearest even
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+  return v;
+}
+
+// exact-erf GELU and its derivative
+__device__ __forceinline__ float gelu_f(float x) { return 0.5f * x * (1.0f + erff(x * 0.70710678118654752440f)); }
+__device__ __forceinline__ float gelu_grad_f(float x) {
+  return 0.5f * (1.0f + erff(x * 0.70710678118654752440f)) + x * 0.39894228040143267794f * __expf(-0.5f * x * x);
+}
+
+// ---- kernel classes for the optional per-launch timing ---------------------------------
+enum KClass {
+  KC_GEMM_FWD = 0,   // A k-major, B k-major   (y = x W^T)
+  KC_GEMM_DX,        // A k-major, B n-major   (dx = dy W)
+  KC_GEMM_DW,        // A m-major, B n-major   (dW = dy^T x)
+  KC_ATTN_FWD,
+  KC_ATTN_BWD,
+  KC_LN_FWD,
+  KC_LN_BWD,
+  KC_EMBED,
+  KC_COLSUM,
+  KC_LOSS,
+  KC_ELEMWISE,
+  KC_ACCUM,
+  KC_ADAM,
+  KC_COUNT
+};
+
+struct Profiler;  // host side, see context.cpp
+
+// One timing scope around a launch; no-op when prof is null.
+struct KScope {
+  Profiler* prof;
+  int slot;
+  hipStream_t stream;
+  KScope(Profiler* p, int kclass, double flops, double bytes, hipStream_t s);
+  ~KScope();
+};
+
+// ---- host-side model tables --------------------------------------------------------------
+struct LayerOff {
+  int64_t qkv_w, qkv_b, o_w, o_b, ln1_g, ln1_b, ffn1_w, ffn1_b, ffn2_w, ffn2_b, ln2_g, ln2_b;
+};
+struct ModelOff {
+  int64_t emb_word, emb_pos, emb_ln_g, emb_ln_b;
+  std::vector<LayerOff> layer;
+  int64_t head_t_w, head_t_b, head_ln_g, head_ln_b, head_dec_b;
+  int64_t total;
+};
+bool hs_cfg_valid(const hs_model_cfg* cfg, std::string* why);
+void hs_model_offsets(const hs_model_cfg& cfg, ModelOff* out);
+
+struct hs_ctx {
+  hs_model_cfg cfg;
+  ModelOff off;
+  std::string err;
+  Profiler* prof;  // null unless enabled
+};
+
+hs_status hs_fail(hs_ctx* ctx, hs_status st, const std::string& msg);  // records msg, returns st
+#define HS_HIP_CHECK(ctx, expr)                                                              \
+  do {                                                                                       \
+    hipError_t e_ = (expr);                                                                  \
+    if (e_ != hipSuccess) return hs_fail(ctx, HS_ERR_HIP, std::string(#expr) + ": " + hipGetErrorString(e_)); \
+  } while (0)
+
+static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+static inline size_t esize(int dtype) { return dtype == HS_BF16 ? 2 : 4; }
+
+// ---- internal launchers (each checks nothing; callers validate) ----------------------------
+struct GemmArgs {
+  int dtype;  // hs_dtype
+  int a_kmajor, b_kmajor;
+  int M, N, K;
+  const void* A; int64_t lda;
+  const void* B; int64_t ldb;
+  void* C; int64_t ldc;
+  int c_f32; float beta;
+  const void* bias;
+  int epi; const void* aux; int64_t ldaux; void* C2;
+};
+hs_status launch_gemm(hs_ctx* ctx, const GemmArgs& g, hipStream_t s);
+
+hs_status launch_layernorm_fwd(hs_ctx* ctx, int dtype, const void* x, const void* gain, const void* bias, void* y,
+                               float* stats, int R, int H, float eps, hipStream_t s);
+size_t layernorm_bwd_scratch(int R, int H);
+hs_status launch_layernorm_bwd(hs_ctx* ctx, int dtype, const void* dy, const void* x, const float* stats, const void* gain,
+                               void* dx, float* d_gain, float* d_bias, float* d_colsum, float beta, int R, int H,
+                               void* partials, hipStream_t s);
+hs_status launch_embed_ln_fwd(hs_ctx* ctx, int dtype, const void* word, const void* pos, const void* gain, const void* bias,
+                              const int32_t* ids, void* e_pre, void* x0, float* stats, int B, int L, int H, int V, float eps,
+                              hipStream_t s);
+size_t embed_bwd_scratch(int T, int H);
+hs_status launch_embed_bwd(hs_ctx* ctx, int dtype, const void* de, const int32_t* ids, int B, int L, int H, int V, int max_pos,
+                           float* g_word, float* g_pos, float beta_pos, void* scratch, hipStream_t s);
+hs_status launch_attention_fwd(hs_ctx* ctx, int dtype, const void* qkv, const int32_t* lens, int B, int L, int A, void* out,
+                               float* lse, hipStream_t s);
+hs_status launch_attention_bwd(hs_ctx* ctx, int dtype, const void* qkv, const void* out, const float* lse, const void* d_out,
+                               const int32_t* lens, int B, int L, int A, void* dqkv, float* dvec, hipStream_t s);
+size_t colsum_scratch(int R, int C);
+hs_status launch_colsum(hs_ctx* ctx, int dtype, const void* x, int64_t ldx, int R, int C, float* out, float beta, void* partials,
+                        hipStream_t s);
+hs_status launch_gather_rows(hs_ctx* ctx, int dtype, const void* src, const int32_t* idx, int M, int H, void* dst, hipStream_t s);
+hs_status launch_scatter_rows(hs_ctx* ctx, int dtype, const void* src, const int32_t* idx, int M, int H, void* dst, hipStream_t s);
+hs_status launch_fill_zero(hs_ctx* ctx, void* p, size_t bytes, hipStream_t s);
+hs_status launch_gelu_fwd(hs_ctx* ctx, int dtype, const void* x, void* y, size_t n, hipStream_t s);
+hs_status launch_gelu_bwd(hs_ctx* ctx, int dtype, const void* dy, const void* pre, void* dx, size_t n, hipStream_t s);
+hs_status launch_ce_loss(hs_ctx* ctx, int dtype, const float* logits, int64_t ldl, const int32_t* labels, int M, int V, void* dlogits,
+                         float* row_loss, float* loss_sum, hipStream_t s);

@@ -1,0 +1,535 @@
+// Row-wise and element-wise kernels: LayerNorm forward/backward, embedding forward/backward,
+// column sums, gather/scatter of rows, GELU, cross-entropy.  All are HBM-bound single-pass
+// kernels; statistics and reductions are fp32 and every reduction has a fixed order.
+#include "common.h"
+
+namespace {
+
+constexpr int MAXC = 16;  // columns per lane: hidden <= 1024
+
+// ------------------------------------------------------------------------------------------
+// LayerNorm forward: one wave per row
+// ------------------------------------------------------------------------------------------
+template <class T>
+__device__ __forceinline__ void ln_row(float (&v)[MAXC], int nc, int H, int lane, const T* gain, const T* bias, float eps,
+                                       T* y, float* mean_out, float* rstd_out) {
+  float s = 0.f;
+#pragma unroll
+  for (int c = 0; c < MAXC; ++c) if (c < nc) s += v[c];
+  const float mu = wave_sum(s) / (float)H;
+  float q = 0.f;
+#pragma unroll
+  for (int c = 0; c < MAXC; ++c) if (c < nc) { const float d = v[c] - mu; q += d * d; }
+  const float var = wave_sum(q) / (float)H;
+  const float rstd = 1.0f / sqrtf(var + eps);
+#pragma unroll
+  for (int c = 0; c < MAXC; ++c) if (c < nc) {
+    const int col = c * 64 + lane;
+    y[col] = from_f<T>((v[c] - mu) * rstd * to_f(gain[col]) + to_f(bias[col]));
+  }
+  if (lane == 0) { *mean_out = mu; *rstd_out = rstd; }
+}
+
+template <class T>
+__global__ __launch_bounds__(256) void ln_fwd_kernel(const T* __restrict__ x, const T* __restrict__ gain, const T* __restrict__ bias,
+                                                     T* __restrict__ y, float* __restrict__ stats, int R, int H, float eps) {
+  const int lane = threadIdx.x & 63;
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= R) return;
+  const int nc = H / 64;
+  float v[MAXC];
+#pragma unroll
+  for (int c = 0; c < MAXC; ++c) if (c < nc) v[c] = to_f(x[(int64_t)row * H + c * 64 + lane]);
+  ln_row<T>(v, nc, H, lane, gain, bias, eps, y + (int64_t)row * H, stats + row, stats + R + row);
+}
+
+template <class T>
+__global__ __launch_bounds__(256) void embed_ln_fwd_kernel(const T* __restrict__ word, const T* __restrict__ pos,
+                                                           const T* __restrict__ gain, const T* __restrict__ bias,
+                                                           const int32_t* __restrict__ ids, T* __restrict__ e_pre, T* __restrict__ x0,
+                                                           float* __restrict__ stats, int R, int L, int H, int V, float eps) {
+  const int lane = threadIdx.x & 63;
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= R) return;
+  int id = ids[row];
+  id = id < 0 ? 0 : (id >= V ? V - 1 : id);  // ids are validated by contract; clamp keeps reads in bounds
+  const int l = row % L;
+  const int nc = H / 64;
+  float v[MAXC];
+#pragma unroll
+  for (int c = 0; c < MAXC; ++c) if (c < nc) {
+    const int col = c * 64 + lane;
+    // the sum is rounded to the activation type because that is what the backward pass re-reads
+    const T e = from_f<T>(to_f(word[(int64_t)id * H + col]) + to_f(pos[(int64_t)l * H + col]));
+    e_pre[(int64_t)row * H + col] = e;
+    v[c] = to_f(e);
+  }
+  ln_row<T>(v, nc, H, lane, gain, bias, eps, x0 + (int64_t)row * H, stats + row, stats + R + row);
+}
+
+// ------------------------------------------------------------------------------------------
+// LayerNorm backward.  Each wave walks rows with a fixed stride and keeps per-column partial
+// sums of dy*xhat, dy and dx; blocks write partials, a second kernel adds them in block order.
+// ------------------------------------------------------------------------------------------
+template <class T>
+__global__ __launch_bounds__(256) void ln_bwd_kernel(const T* __restrict__ dy, const T* __restrict__ x, const float* __restrict__ stats,
+                                                     const T* __restrict__ gain, T* __restrict__ dx, float* __restrict__ partials,
+                                                     int R, int H) {
+  __shared__ float red[4][MAXC * 64];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int nc = H / 64;
+  float g[MAXC], ag[MAXC], ab[MAXC], as[MAXC];
+#pragma unroll
+  for (int c = 0; c < MAXC; ++c) { ag[c] = ab[c] = as[c] = 0.f; g[c] = (c < nc) ? to_f(gain[c * 64 + lane]) : 0.f; }
+  for (int row = blockIdx.x * 4 + wave; row < R; row += gridDim.x * 4) {
+    const float mu = stats[row], rstd = stats[R + row];
+    float xh[MAXC], dyv[MAXC];
+    float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+    for (int c = 0; c < MAXC; ++c) if (c < nc) {
+      const int64_t o = (int64_t)row * H + c * 64 + lane;
+      xh[c] = (to_f(x[o]) - mu) * rstd;
+      dyv[c] = to_f(dy[o]);
+      const float dxh = dyv[c] * g[c];
+      s1 += dxh; s2 += dxh * xh[c];
+    }
+    s1 = wave_sum(s1) / (float)H;
+    s2 = wave_sum(s2) / (float)H;
+#pragma unroll
+    for (int c = 0; c < MAXC; ++c) if (c < nc) {
+      const float d = rstd * (dyv[c] * g[c] - s1 - xh[c] * s2);
+      const T dr = from_f<T>(d);
+      dx[(int64_t)row * H + c * 64 + lane] = dr;
+      ag[c] += dyv[c] * xh[c]; ab[c] += dyv[c]; as[c] += to_f(dr);
+    }
+  }
+  // combine the four waves of the block in wave order, one quantity at a time
+  float* out = partials + (int64_t)blockIdx.x * 3 * H;
+  for (int q = 0; q < 3; ++q) {
+#pragma unroll
+    for (int c = 0; c < MAXC; ++c) if (c < nc) red[wave][c * 64 + lane] = (q == 0) ? ag[c] : (q == 1 ? ab[c] : as[c]);
+    __syncthreads();
+    for (int col = threadIdx.x; col < H; col += 256) out[q * H + col] = ((red[0][col] + red[1][col]) + red[2][col]) + red[3][col];
+    __syncthreads();
+  }
+}
+
+// out[col] = beta*out[col] + sum_p partials[p*stride + col], p ascending
+__global__ void sum_partials_kernel(const float* __restrict__ partials, int np, int64_t stride, int C, float* __restrict__ out, float beta) {
+  const int col = blockIdx.x * blockDim.x + threadIdx.x;
+  if (col >= C) return;
+  float s = 0.f;
+  for (int p = 0; p < np; ++p) s += partials[(int64_t)p * stride + col];
+  out[col] = (beta != 0.f) ? beta * out[col] + s : s;
+}
+
+// ------------------------------------------------------------------------------------------
+// column sums of a [R, C] matrix
+// ------------------------------------------------------------------------------------------
+template <class T>
+__global__ __launch_bounds__(256) void colsum_kernel(const T* __restrict__ x, int64_t ldx, int R, int C, int rows_per_chunk,
+                                                     float* __restrict__ partials) {
+  const int col = blockIdx.x * 256 + threadIdx.x;
+  if (col >= C) return;
+  const int r0 = blockIdx.y * rows_per_chunk;
+  const int r1 = min(R, r0 + rows_per_chunk);
+  float s = 0.f;
+  for (int r = r0; r < r1; ++r) s += to_f(x[(int64_t)r * ldx + col]);
+  partials[(int64_t)blockIdx.y * C + col] = s;
+}
+
+// ------------------------------------------------------------------------------------------
+// rows: gather, scatter, zero fill, GELU
+// ------------------------------------------------------------------------------------------
+template <class T>
+__global__ void gather_rows_kernel(const T* __restrict__ src, const int32_t* __restrict__ idx, int M, int H, T* __restrict__ dst, int scatter) {
+  const int m = blockIdx.x;
+  const int64_t r = idx[m];
+  for (int c = threadIdx.x; c < H; c += blockDim.x) {
+    if (scatter) dst[r * H + c] = src[(int64_t)m * H + c];
+    else dst[(int64_t)m * H + c] = src[r * H + c];
+  }
+}
+
+__global__ void fill_bytes_kernel(unsigned char* p, size_t n) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = 0;
+}
+
+__global__ void fill_zero_kernel(uint4* p, size_t n16, unsigned char* tail, size_t ntail) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (size_t k = i; k < n16; k += stride) p[k] = make_uint4(0, 0, 0, 0);
+  if (i < ntail) tail[i] = 0;
+}
+
+template <class T>
+__global__ void gelu_bwd_kernel(const T* __restrict__ dy, const T* __restrict__ pre, T* __restrict__ dx, size_t n) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) dx[i] = from_f<T>(to_f(dy[i]) * gelu_grad_f(to_f(pre[i])));
+}
+template <class T>
+__global__ void gelu_fwd_kernel(const T* __restrict__ x, T* __restrict__ y, size_t n) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) y[i] = from_f<T>(gelu_f(to_f(x[i])));
+}
+
+// ------------------------------------------------------------------------------------------
+// cross-entropy over fp32 logits: one block per target row
+// ------------------------------------------------------------------------------------------
+__device__ __forceinline__ float block_reduce(float v, bool is_max, float* sh) {
+  v = is_max ? wave_max(v) : wave_sum(v);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  __syncthreads();
+  if (lane == 0) sh[wave] = v;
+  __syncthreads();
+  float r = sh[0];
+  for (int w = 1; w < (int)(blockDim.x >> 6); ++w) r = is_max ? fmaxf(r, sh[w]) : r + sh[w];
+  return r;
+}
+
+template <class T>
+__global__ __launch_bounds__(256) void ce_loss_kernel(const float* __restrict__ logits, int64_t ldl, const int32_t* __restrict__ labels,
+                                                      int V, T* __restrict__ dlogits, float* __restrict__ row_loss) {
+  __shared__ float sh[8];
+  const int m = blockIdx.x;
+  const float* z = logits + (int64_t)m * ldl;
+  float mx = -3.0e38f;
+  for (int v = threadIdx.x; v < V; v += 256) mx = fmaxf(mx, z[v]);
+  mx = block_reduce(mx, true, sh);
+  float se = 0.f;
+  for (int v = threadIdx.x; v < V; v += 256) se += __expf(z[v] - mx);
+  se = block_reduce(se, false, sh);
+  const float lse = mx + logf(se);
+  int lab = labels[m];
+  lab = lab < 0 ? 0 : (lab >= V ? V - 1 : lab);
+  if (threadIdx.x == 0) row_loss[m] = lse - z[lab];
+  T* d = dlogits + (int64_t)m * ldl;
+  for (int v = threadIdx.x; v < (int)ldl; v += 256) {
+    float p = 0.f;
+    if (v < V) p = __expf(z[v] - lse) - (v == lab ? 1.0f : 0.0f);
+    d[v] = from_f<T>(p);
+  }
+}
+
+// fixed-order sum of n floats by one block
+__global__ __launch_bounds__(256) void sum_vector_kernel(const float* __restrict__ x, int n, float* __restrict__ out) {
+  __shared__ float sh[8];
+  float s = 0.f;
+  for (int i = threadIdx.x; i < n; i += 256) s += x[i];
+  s = block_reduce(s, false, sh);
+  if (threadIdx.x == 0) *out = s;
+}
+
+// ------------------------------------------------------------------------------------------
+// embedding backward
+// ------------------------------------------------------------------------------------------
+// position table: g_pos[l, :] = beta*g_pos[l, :] + sum_b de[b, l, :]; rows l >= L get beta*old
+template <class T>
+__global__ void pos_grad_kernel(const T* __restrict__ de, int B, int L, int H, int max_pos, float* __restrict__ g_pos, float beta) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= (int64_t)max_pos * H) return;
+  const int l = (int)(i / H), c = (int)(i % H);
+  float s = 0.f;
+  if (l < L) for (int b = 0; b < B; ++b) s += to_f(de[((int64_t)b * L + l) * H + c]);
+  g_pos[i] = (beta != 0.f) ? beta * g_pos[i] + s : s;
+}
+
+// Stable LSD radix sort of (id, position) by id, 4 bits per pass, one block of 512 threads.
+// Thread t owns the contiguous slice [t*per, (t+1)*per) in every pass, which keeps equal keys in
+// their input order.  Result in (key_out, val_out) after an even number of passes.
+__global__ __launch_bounds__(512) void sort_ids_kernel(const int32_t* __restrict__ ids, int T, int V, int32_t* k0, int32_t* v0,
+                                                        int32_t* k1, int32_t* v1, int npass) {
+  constexpr int NT = 512;
+  __shared__ int cnt[16 * NT];
+  __shared__ int wsum[NT / 64];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int per = (T + NT - 1) / NT;
+  const int beg = min(T, tid * per), end = min(T, beg + per);
+  for (int pass = 0; pass < npass; ++pass) {
+    const int shift = 4 * pass;
+    const int32_t* kin = (pass & 1) ? k1 : k0;
+    const int32_t* vin = (pass & 1) ? v1 : v0;
+    int32_t* kout = (pass & 1) ? k0 : k1;
+    int32_t* vout = (pass & 1) ? v0 : v1;
+    for (int d = 0; d < 16; ++d) cnt[d * NT + tid] = 0;
+    for (int i = beg; i < end; ++i) {
+      int key;
+      if (pass == 0) { key = ids[i]; key = key < 0 ? 0 : (key >= V ? V - 1 : key); } else key = kin[i];
+      cnt[((key >> shift) & 15) * NT + tid]++;
+    }
+    __syncthreads();
+    // exclusive scan over the 16*NT counters (digit-major): thread owns 16 consecutive entries
+    int loc[16], s = 0;
+    for (int j = 0; j < 16; ++j) { loc[j] = s; s += cnt[tid * 16 + j]; }
+    int incl = s;
+    for (int o = 1; o < 64; o <<= 1) { int t = __shfl_up(incl, o); if (lane >= o) incl += t; }
+    if (lane == 63) wsum[wave] = incl;
+    __syncthreads();
+    int base = 0;
+    for (int w = 0; w < wave; ++w) base += wsum[w];
+    base += incl - s;
+    __syncthreads();
+    for (int j = 0; j < 16; ++j) cnt[tid * 16 + j] = base + loc[j];
+    __syncthreads();
+    for (int i = beg; i < end; ++i) {
+      int key, val;
+      if (pass == 0) { key = ids[i]; key = key < 0 ? 0 : (key >= V ? V - 1 : key); val = i; } else { key = kin[i]; val = vin[i]; }
+      const int pos = cnt[((key >> shift) & 15) * NT + tid]++;
+      kout[pos] = key; vout[pos] = val;
+    }
+    __threadfence_block();
+    __syncthreads();
+  }
+}
+
+// Segmented sum over the sorted token list in chunks of CH entries, one wave per chunk.
+// Runs that lie wholly inside a chunk are added to g_word directly (no other wave touches that
+// row).  A run that continues into a neighbouring chunk is written to carry[chunk][0] (run open
+// to the left, or spanning the whole chunk) or carry[chunk][1] (run open to the right only).
+constexpr int CH = 16;
+template <class T>
+__global__ __launch_bounds__(256) void word_grad_chunks_kernel(const T* __restrict__ de, const int32_t* __restrict__ skey,
+                                                               const int32_t* __restrict__ sval, int Ttok, int H,
+                                                               float* __restrict__ g_word, float* __restrict__ carry) {
+  const int lane = threadIdx.x & 63;
+  const int chunk = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int i0 = chunk * CH;
+  if (i0 >= Ttok) return;
+  const int i1 = min(Ttok, i0 + CH);
+  const int nc = H / 64;
+  float acc[MAXC];
+#pragma unroll
+  for (int c = 0; c < MAXC; ++c) acc[c] = 0.f;
+  int run_start = i0;
+  for (int i = i0; i < i1; ++i) {
+    const int key = skey[i];
+    const int64_t t = sval[i];
+#pragma unroll
+    for (int c = 0; c < MAXC; ++c) if (c < nc) acc[c] += to_f(de[t * H + c * 64 + lane]);
+    const bool last_of_chunk = (i + 1 == i1);
+    const bool run_ends = last_of_chunk || skey[i + 1] != key;
+    if (run_ends) {
+      const bool open_left = (run_start == i0) && (i0 > 0) && (skey[i0 - 1] == key);
+      const bool open_right = last_of_chunk && (i1 < Ttok) && (skey[i1] == key);
+      float* dst;
+      bool add;
+      if (open_left) { dst = carry + ((int64_t)chunk * 2 + 0) * H; add = false; }
+      else if (open_right) { dst = carry + ((int64_t)chunk * 2 + 1) * H; add = false; }
+      else { dst = g_word + (int64_t)key * H; add = true; }
+#pragma unroll
+      for (int c = 0; c < MAXC; ++c) if (c < nc) {
+        const int col = c * 64 + lane;
+        dst[col] = add ? dst[col] + acc[c] : acc[c];
+        acc[c] = 0.f;
+      }
+      run_start = i + 1;
+    }
+  }
+}
+
+// Joins the runs that cross chunk borders: the wave of the chunk in which such a run STARTS adds
+// its right-open piece and every following left-open piece, in chunk order, then updates g_word.
+__global__ __launch_bounds__(256) void word_grad_join_kernel(const int32_t* __restrict__ skey, int Ttok, int H,
+                                                             float* __restrict__ g_word, const float* __restrict__ carry) {
+  const int lane = threadIdx.x & 63;
+  const int chunk = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int i0 = chunk * CH;
+  if (i0 >= Ttok) return;
+  const int i1 = min(Ttok, i0 + CH);
+  if (i1 >= Ttok) return;                       // nothing to the right
+  const int key = skey[i1 - 1];
+  if (skey[i1] != key) return;                  // last run is not open to the right
+  // is the last run of this chunk also open to the left (i.e. it started in an earlier chunk)?
+  const bool whole_chunk = (skey[i0] == key);
+  if (whole_chunk && i0 > 0 && skey[i0 - 1] == key) return;   // a continuation: the starting chunk handles it
+  const int nc = H / 64;
+  float acc[MAXC];
+  // A run that spans this whole chunk but starts here was stored by the chunk kernel in slot 1
+  // (open to the right only), exactly like a run that starts mid-chunk.
+#pragma unroll
+  for (int c = 0; c < MAXC; ++c) acc[c] = (c < nc) ? carry[((int64_t)chunk * 2 + 1) * H + c * 64 + lane] : 0.f;
+  for (int ch = chunk + 1; ch * CH < Ttok; ++ch) {
+    if (skey[ch * CH] != key) break;
+#pragma unroll
+    for (int c = 0; c < MAXC; ++c) if (c < nc) acc[c] += carry[((int64_t)ch * 2 + 0) * H + c * 64 + lane];
+    const int e = min(Ttok, ch * CH + CH);
+    if (skey[e - 1] != key) break;              // the run ended inside chunk ch
+  }
+#pragma unroll
+  for (int c = 0; c < MAXC; ++c) if (c < nc) g_word[(int64_t)key * H + c * 64 + lane] += acc[c];
+}
+
+}  // namespace
+
+// ==========================================================================================
+// launchers
+// ==========================================================================================
+#define LAUNCH_CHECK(ctx, what)                                                                        \
+  do {                                                                                                 \
+    hipError_t e_ = hipGetLastError();                                                                 \
+    if (e_ != hipSuccess) return hs_fail(ctx, HS_ERR_HIP, std::string(what) + ": " + hipGetErrorString(e_)); \
+  } while (0)
+
+static inline Profiler* prof_of(hs_ctx* ctx) { return ctx ? ctx->prof : nullptr; }
+
+hs_status launch_layernorm_fwd(hs_ctx* ctx, int dtype, const void* x, const void* gain, const void* bias, void* y, float* stats,
+                               int R, int H, float eps, hipStream_t s) {
+  if (R <= 0) return HS_OK;
+  KScope scope(prof_of(ctx), KC_LN_FWD, 8.0 * R * H, 2.0 * R * H * esize(dtype), s);
+  dim3 grid((R + 3) / 4);
+  if (dtype == HS_BF16) hipLaunchKernelGGL(ln_fwd_kernel<bf16>, grid, dim3(256), 0, s, (const bf16*)x, (const bf16*)gain, (const bf16*)bias, (bf16*)y, stats, R, H, eps);
+  else hipLaunchKernelGGL(ln_fwd_kernel<float>, grid, dim3(256), 0, s, (const float*)x, (const float*)gain, (const float*)bias, (float*)y, stats, R, H, eps);
+  LAUNCH_CHECK(ctx, "layernorm_fwd");
+  return HS_OK;
+}
+
+static int ln_bwd_blocks(int R) { int nb = (R + 15) / 16; return nb < 1 ? 1 : (nb > 512 ? 512 : nb); }
+size_t layernorm_bwd_scratch(int R, int H) { return align_up((size_t)ln_bwd_blocks(R) * 3 * H * sizeof(float), 256); }
+
+hs_status launch_layernorm_bwd(hs_ctx* ctx, int dtype, const void* dy, const void* x, const float* stats, const void* gain, void* dx,
+                               float* d_gain, float* d_bias, float* d_colsum, float beta, int R, int H, void* partials, hipStream_t s) {
+  if (R <= 0) return HS_OK;
+  const int nb = ln_bwd_blocks(R);
+  KScope scope(prof_of(ctx), KC_LN_BWD, 14.0 * R * H, 3.0 * R * H * esize(dtype), s);
+  if (dtype == HS_BF16) hipLaunchKernelGGL(ln_bwd_kernel<bf16>, dim3(nb), dim3(256), 0, s, (const bf16*)dy, (const bf16*)x, stats, (const bf16*)gain, (bf16*)dx, (float*)partials, R, H);
+  else hipLaunchKernelGGL(ln_bwd_kernel<float>, dim3(nb), dim3(256), 0, s, (const float*)dy, (const float*)x, stats, (const float*)gain, (float*)dx, (float*)partials, R, H);
+  LAUNCH_CHECK(ctx, "layernorm_bwd");
+  float* outs[3] = {d_gain, d_bias, d_colsum};
+  for (int q = 0; q < 3; ++q) {
+    if (!outs[q]) continue;
+    hipLaunchKernelGGL(sum_partials_kernel, dim3((H + 255) / 256), dim3(256), 0, s, (const float*)partials + (size_t)q * H, nb, (int64_t)3 * H, H, outs[q], beta);
+    LAUNCH_CHECK(ctx, "layernorm_bwd finalize");
+  }
+  return HS_OK;
+}
+
+hs_status launch_embed_ln_fwd(hs_ctx* ctx, int dtype, const void* word, const void* pos, const void* gain, const void* bias,
+                              const int32_t* ids, void* e_pre, void* x0, float* stats, int B, int L, int H, int V, float eps, hipStream_t s) {
+  const int R = B * L;
+  if (R <= 0) return HS_OK;
+  KScope scope(prof_of(ctx), KC_EMBED, 10.0 * R * H, 4.0 * R * H * esize(dtype), s);
+  dim3 grid((R + 3) / 4);
+  if (dtype == HS_BF16) hipLaunchKernelGGL(embed_ln_fwd_kernel<bf16>, grid, dim3(256), 0, s, (const bf16*)word, (const bf16*)pos, (const bf16*)gain, (const bf16*)bias, ids, (bf16*)e_pre, (bf16*)x0, stats, R, L, H, V, eps);
+  else hipLaunchKernelGGL(embed_ln_fwd_kernel<float>, grid, dim3(256), 0, s, (const float*)word, (const float*)pos, (const float*)gain, (const float*)bias, ids, (float*)e_pre, (float*)x0, stats, R, L, H, V, eps);
+  LAUNCH_CHECK(ctx, "embed_ln_fwd");
+  return HS_OK;
+}
+
+// scratch for the word-embedding gradient: 4 int arrays [T] + carry [chunks][2][H] floats
+size_t embed_bwd_scratch(int T, int H) {
+  const size_t chunks = ((size_t)T + CH - 1) / CH;
+  return align_up(4 * (size_t)T * sizeof(int32_t), 256) + align_up(chunks * 2 * H * sizeof(float), 256);
+}
+
+hs_status launch_embed_bwd(hs_ctx* ctx, int dtype, const void* de, const int32_t* ids, int B, int L, int H, int V, int max_pos,
+                           float* g_word, float* g_pos, float beta_pos, void* scratch, hipStream_t s) {
+  const int T = B * L;
+  if (T <= 0) return HS_OK;
+  KScope scope(prof_of(ctx), KC_EMBED, 2.0 * T * H, (double)T * H * (2.0 * esize(dtype) + 8.0) + 8.0 * max_pos * H, s);
+  {
+    const int64_t n = (int64_t)max_pos * H;
+    dim3 grid((unsigned)((n + 255) / 256));
+    if (dtype == HS_BF16) hipLaunchKernelGGL(pos_grad_kernel<bf16>, grid, dim3(256), 0, s, (const bf16*)de, B, L, H, max_pos, g_pos, beta_pos);
+    else hipLaunchKernelGGL(pos_grad_kernel<float>, grid, dim3(256), 0, s, (const float*)de, B, L, H, max_pos, g_pos, beta_pos);
+    LAUNCH_CHECK(ctx, "pos_grad");
+  }
+  int32_t* k0 = (int32_t*)scratch;
+  int32_t* v0 = k0 + T; int32_t* k1 = v0 + T; int32_t* v1 = k1 + T;
+  float* carry = (float*)((char*)scratch + align_up(4 * (size_t)T * sizeof(int32_t), 256));
+  int bits = 1;
+  while ((1 << bits) < V) ++bits;
+  int npass = (bits + 3) / 4;
+  if (npass & 1) ++npass;  // an even number of passes leaves the result in (k0, v0)
+  hipLaunchKernelGGL(sort_ids_kernel, dim3(1), dim3(512), 0, s, ids, T, V, k0, v0, k1, v1, npass);
+  LAUNCH_CHECK(ctx, "sort_ids");
+  const int chunks = (T + CH - 1) / CH;
+  dim3 grid((chunks + 3) / 4);
+  if (dtype == HS_BF16) hipLaunchKernelGGL(word_grad_chunks_kernel<bf16>, grid, dim3(256), 0, s, (const bf16*)de, k0, v0, T, H, g_word, carry);
+  else hipLaunchKernelGGL(word_grad_chunks_kernel<float>, grid, dim3(256), 0, s, (const float*)de, k0, v0, T, H, g_word, carry);
+  LAUNCH_CHECK(ctx, "word_grad_chunks");
+  hipLaunchKernelGGL(word_grad_join_kernel, grid, dim3(256), 0, s, k0, T, H, g_word, carry);
+  LAUNCH_CHECK(ctx, "word_grad_join");
+  return HS_OK;
+}
+
+static int colsum_chunks(int R) { int n = (R + 31) / 32; return n < 1 ? 1 : (n > 64 ? 64 : n); }
+size_t colsum_scratch(int R, int C) { return align_up((size_t)colsum_chunks(R) * C * sizeof(float), 256); }
+
+hs_status launch_colsum(hs_ctx* ctx, int dtype, const void* x, int64_t ldx, int R, int C, float* out, float beta, void* partials, hipStream_t s) {
+  if (C <= 0) return HS_OK;
+  KScope scope(prof_of(ctx), KC_COLSUM, (double)R * C, (double)R * C * esize(dtype), s);
+  const int nch = colsum_chunks(R);
+  const int rpc = (R + nch - 1) / nch;
+  dim3 grid((C + 255) / 256, nch);
+  if (dtype == HS_BF16) hipLaunchKernelGGL(colsum_kernel<bf16>, grid, dim3(256), 0, s, (const bf16*)x, ldx, R, C, rpc, (float*)partials);
+  else hipLaunchKernelGGL(colsum_kernel<float>, grid, dim3(256), 0, s, (const float*)x, ldx, R, C, rpc, (float*)partials);
+  LAUNCH_CHECK(ctx, "colsum");
+  hipLaunchKernelGGL(sum_partials_kernel, dim3((C + 255) / 256), dim3(256), 0, s, (const float*)partials, nch, (int64_t)C, C, out, beta);
+  LAUNCH_CHECK(ctx, "colsum finalize");
+  return HS_OK;
+}
+
+static hs_status rows_move(hs_ctx* ctx, int dtype, const void* src, const int32_t* idx, int M, int H, void* dst, int scatter, hipStream_t s) {
+  if (M <= 0) return HS_OK;
+  KScope scope(prof_of(ctx), KC_ELEMWISE, 0.0, 2.0 * M * H * esize(dtype), s);
+  if (dtype == HS_BF16) hipLaunchKernelGGL(gather_rows_kernel<bf16>, dim3(M), dim3(128), 0, s, (const bf16*)src, idx, M, H, (bf16*)dst, scatter);
+  else hipLaunchKernelGGL(gather_rows_kernel<float>, dim3(M), dim3(128), 0, s, (const float*)src, idx, M, H, (float*)dst, scatter);
+  LAUNCH_CHECK(ctx, "gather/scatter rows");
+  return HS_OK;
+}
+hs_status launch_gather_rows(hs_ctx* ctx, int dtype, const void* src, const int32_t* idx, int M, int H, void* dst, hipStream_t s) {
+  return rows_move(ctx, dtype, src, idx, M, H, dst, 0, s);
+}
+hs_status launch_scatter_rows(hs_ctx* ctx, int dtype, const void* src, const int32_t* idx, int M, int H, void* dst, hipStream_t s) {
+  return rows_move(ctx, dtype, src, idx, M, H, dst, 1, s);
+}
+
+hs_status launch_fill_zero(hs_ctx* ctx, void* p, size_t bytes, hipStream_t s) {
+  if (bytes == 0) return HS_OK;
+  KScope scope(prof_of(ctx), KC_ELEMWISE, 0.0, (double)bytes, s);
+  if ((uintptr_t)p % 16) {
+    if (bytes > 4096) return hs_fail(ctx, HS_ERR_INVALID_ARG, "fill_zero: large buffers must be 16-byte aligned");
+    hipLaunchKernelGGL(fill_bytes_kernel, dim3((unsigned)((bytes + 255) / 256)), dim3(256), 0, s, (unsigned char*)p, bytes);
+    LAUNCH_CHECK(ctx, "fill_bytes");
+    return HS_OK;
+  }
+  const size_t n16 = bytes / 16, ntail = bytes % 16;
+  size_t blocks = (n16 + 255) / 256;
+  if (blocks < 1) blocks = 1;
+  if (blocks > 4096) blocks = 4096;
+  hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)blocks), dim3(256), 0, s, (uint4*)p, n16, (unsigned char*)p + n16 * 16, ntail);
+  LAUNCH_CHECK(ctx, "fill_zero");
+  return HS_OK;
+}
+
+hs_status launch_gelu_fwd(hs_ctx* ctx, int dtype, const void* x, void* y, size_t n, hipStream_t s) {
+  if (n == 0) return HS_OK;
+  KScope scope(prof_of(ctx), KC_ELEMWISE, 10.0 * n, 2.0 * n * esize(dtype), s);
+  dim3 grid((unsigned)((n + 255) / 256));
+  if (dtype == HS_BF16) hipLaunchKernelGGL(gelu_fwd_kernel<bf16>, grid, dim3(256), 0, s, (const bf16*)x, (bf16*)y, n);
+  else hipLaunchKernelGGL(gelu_fwd_kernel<float>, grid, dim3(256), 0, s, (const float*)x, (float*)y, n);
+  LAUNCH_CHECK(ctx, "gelu_fwd");
+  return HS_OK;
+}
+hs_status launch_gelu_bwd(hs_ctx* ctx, int dtype, const void* dy, const void* pre, void* dx, size_t n, hipStream_t s) {
+  if (n == 0) return HS_OK;
+  KScope scope(prof_of(ctx), KC_ELEMWISE, 12.0 * n, 3.0 * n * esize(dtype), s);
+  dim3 grid((unsigned)((n + 255) / 256));
+  if (dtype == HS_BF16) hipLaunchKernelGGL(gelu_bwd_kernel<bf16>, grid, dim3(256), 0, s, (const bf16*)dy, (const bf16*)pre, (bf16*)dx, n);
+  else hipLaunchKernelGGL(gelu_bwd_kernel<float>, grid, dim3(256), 0, s, (const float*)dy, (const float*)pre, (float*)dx, n);
+  LAUNCH_CHECK(ctx, "gelu_bwd");
+  return HS_OK;
+}
+
+hs_status launch_ce_loss(hs_ctx* ctx, int dtype, const float* logits, int64_t ldl, const int32_t* labels, int M, int V, void* dlogits,
+                         float* row_loss, float* loss_sum, hipStream_t s) {
+  if (M <= 0) return HS_OK;
+  KScope scope(prof_of(ctx), KC_LOSS, 4.0 * M * V, (double)M * V * (4.0 + esize(dtype)), s);
+  if (dtype == HS_BF16) hipLaunchKernelGGL(ce_loss_kernel<bf16>, dim3(M), dim3(256), 0, s, logits, ldl, labels, V, (bf16*)dlogits, row_loss);
+  else hipLaunchKernelGGL(ce_loss_kernel<float>, dim3(M), dim3(256), 0, s, logits, ldl, labels, V, (float*)dlogits, row_loss);
+  LAUNCH_CHECK(ctx, "ce_loss");
+  hipLaunchKernelGGL(sum_vector_kernel, dim3(1), dim3(256), 0, s, (const float*)row_loss, M, loss_sum);
+  LAUNCH_CHECK(ctx, "loss sum");
+  return HS_OK;
+}

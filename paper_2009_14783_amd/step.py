@@ -1,0 +1,137 @@
+"""One worker's training step driven through the C ABI (buffer ownership and call order only).
+
+`Worker` owns the device buffers (torch tensors: fp32 master weights, Adam moments, the flat
+fp32 gradient buffer G, the low-precision weight copy, activation arena, workspace) and issues
+the hs_* calls in the order of the paper's step: forward, loss with its weight, backward,
+delayed-update accumulation, normalisation by the global sample count, Adam.  No arithmetic of
+the method happens here.
+"""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from . import binding as hs
+
+
+class Worker:
+    def __init__(self, model: dict, compute: str, theta0: np.ndarray, device: str = "cuda:0"):
+        self.device = torch.device(device)
+        self.compute = hs.HS_BF16 if compute == "bf16" else hs.HS_FP32
+        self.cfg = hs.make_cfg(model["n_layers"], model["hidden"], model["n_heads"], model["ffn"], model["vocab"],
+                               model["max_pos"], model.get("ln_eps", 1e-12), self.compute)
+        self.ctx = hs.hs_ctx_create(self.cfg)
+        self.P = hs.hs_param_count(self.cfg)
+        assert theta0.dtype == np.float32 and theta0.size == self.P
+        self.H = model["hidden"]
+        self.act_dtype = torch.bfloat16 if self.compute == hs.HS_BF16 else torch.float32
+        dev = self.device
+        self.w = torch.from_numpy(theta0.copy()).to(dev)
+        self.m = torch.zeros(self.P, dtype=torch.float32, device=dev)
+        self.v = torch.zeros(self.P, dtype=torch.float32, device=dev)
+        self.G = torch.zeros(self.P, dtype=torch.float32, device=dev)
+        self.g = None                       # separate per-micro-batch gradient (unfused accumulation only)
+        if self.compute == hs.HS_BF16:
+            self.w_lowp = torch.empty(self.P, dtype=torch.bfloat16, device=dev)
+            hs.hs_cast_params(self.w, self.w_lowp, self.P, hs.HS_BF16)
+        else:
+            self.w_lowp = None
+        self.t = 0
+        self._acts = self._ws = self._hidden = self._dhidden = None
+        self._acts_bytes = self._ws_bytes = 0
+        self.loss_buf = torch.zeros(64, dtype=torch.float32, device=dev)
+
+    def close(self):
+        if self.ctx is not None:
+            hs.hs_ctx_destroy(self.ctx)
+            self.ctx = None
+
+    # weights the forward/backward kernels read
+    @property
+    def w_compute(self):
+        return self.w_lowp if self.compute == hs.HS_BF16 else self.w
+
+    def _reserve(self, B, L, M):
+        ab = hs.hs_acts_bytes(self.cfg, B, L, M)
+        wb = hs.hs_workspace_bytes(self.cfg, B, L, M)
+        if ab > self._acts_bytes:
+            self._acts = torch.empty(ab, dtype=torch.uint8, device=self.device)
+            self._acts_bytes = ab
+        if wb > self._ws_bytes:
+            self._ws = torch.empty(wb, dtype=torch.uint8, device=self.device)
+            self._ws_bytes = wb
+        n = B * L * self.H
+        if self._hidden is None or self._hidden.numel() < n:
+            self._hidden = torch.empty(n, dtype=self.act_dtype, device=self.device)
+            self._dhidden = torch.empty(n, dtype=self.act_dtype, device=self.device)
+
+    def upload(self, mb: dict) -> dict:
+        """Host micro-batch (numpy) -> device tensors; done before the timed region."""
+        dev = self.device
+        out = dict(B=int(mb["ids"].shape[0]), L=int(mb["ids"].shape[1]), M=int(mb["mlm_pos"].size),
+                   lens_host=np.ascontiguousarray(mb["lens"], dtype=np.int32),
+                   ids=torch.from_numpy(np.ascontiguousarray(mb["ids"], dtype=np.int32)).to(dev),
+                   lens=torch.from_numpy(np.ascontiguousarray(mb["lens"], dtype=np.int32)).to(dev),
+                   mlm_pos=torch.from_numpy(np.ascontiguousarray(mb["mlm_pos"], dtype=np.int32)).to(dev),
+                   mlm_label=torch.from_numpy(np.ascontiguousarray(mb["mlm_label"], dtype=np.int32)).to(dev),
+                   n_seq=int(mb["ids"].shape[0]))
+        self._reserve(out["B"], out["L"], out["M"])
+        return out
+
+    def forward_backward(self, d: dict, g: torch.Tensor, accumulate: int, loss_slot: int):
+        """hs_encoder_fwd -> hs_mlm_loss -> hs_encoder_bwd for one uploaded micro-batch."""
+        B, L, M = d["B"], d["L"], d["M"]
+        self._reserve(B, L, M)
+        w = self.w_compute
+        hs.hs_encoder_fwd(self.ctx, w, d["ids"], d["lens"], d["lens_host"], B, L, self._acts, self._hidden, self._ws,
+                          self._ws_bytes)
+        loss_ptr = self.loss_buf.data_ptr() + 4 * loss_slot
+        hs.hs_mlm_loss(self.ctx, w, self._hidden, d["mlm_pos"], d["mlm_label"], M, B, L, loss_ptr, self._dhidden, g,
+                       accumulate, self._ws, self._ws_bytes)
+        hs.hs_encoder_bwd(self.ctx, w, self._acts, d["ids"], d["lens"], B, L, self._dhidden, g, accumulate, self._ws,
+                          self._ws_bytes)
+
+    def accumulate_micro_batches(self, batches: list, fused: bool = True) -> int:
+        """Runs every micro-batch and leaves the SUM of their gradients in G.  Entries that are
+        None or carry dummy=True are workers/passes without data: they go through
+        hs_grad_accum_normalize(ignore=1) and change nothing.  Returns the sample count."""
+        n_total, first = 0, True
+        assert len(batches) <= self.loss_buf.numel()
+        self.loss_buf.zero_()
+        for i, d in enumerate(batches):
+            if d is None or d.get("dummy", False):
+                hs.hs_grad_accum_normalize(self.G, None, self.P, 1, 0.0)
+                continue
+            if fused:
+                if first and d["M"] == 0:
+                    self.G.zero_()
+                    first = False
+                self.forward_backward(d, self.G, 0 if first else 1, i)
+            else:
+                if self.g is None:
+                    self.g = torch.zeros(self.P, dtype=torch.float32, device=self.device)
+                if first:
+                    self.G.zero_()
+                if d["M"] == 0:
+                    self.g.zero_()
+                self.forward_backward(d, self.g, 0, i)
+                hs.hs_grad_accum_normalize(self.G, self.g, self.P, 0, 0.0)
+            first = False
+            n_total += d["n_seq"]
+        if first:
+            self.G.zero_()
+        return n_total
+
+    def train_step(self, batches: list, adam: dict, denom=None, fused: bool = True):
+        """The whole hot path for one optimizer step.  Returns the sample count D; the loss sums
+        stay on the device in loss_buf (read with reported_loss after synchronising)."""
+        n_total = self.accumulate_micro_batches(batches, fused)
+        D = n_total if denom is None else denom
+        hs.hs_grad_accum_normalize(self.G, None, self.P, 0, float(D))
+        self.t += 1
+        hs.hs_adam_step(self.w, self.m, self.v, self.G, self.w_lowp, self.P, adam["lr"], adam["beta1"], adam["beta2"],
+                        adam["eps"], adam.get("weight_decay", 0.0), self.t)
+        return D
+
+    def reported_loss(self, D) -> float:
+        return float(self.loss_buf.sum().item()) / D
