@@ -73,6 +73,12 @@ def lib():
     if _lib is None:
         if not os.path.exists(LIB_PATH):
             raise HsError(-1, f"{LIB_PATH} is missing: build it with `python -m paper_2009_14783_amd.build`")
+        # torch ships its own HIP runtime under the same soname; it must be in the process first so
+        # that this library binds to it (two runtimes in one process do not share devices or streams)
+        try:
+            import torch  # noqa: F401
+        except ImportError:
+            pass
         l = C.CDLL(LIB_PATH)
         for name, (res, args) in _SIGNATURES.items():
             fn = getattr(l, name)
