@@ -151,18 +151,21 @@ def main():
         kernels[k] = dict(launches_per_step=p["launches"] / args.profile_steps, ms_per_step=p["ms"] / args.profile_steps,
                           tflops=p["flops"] / sec / 1e12 if sec > 0 else 0.0, gbs=p["bytes"] / sec / 1e9 if sec > 0 else 0.0)
     gemm_classes = [k for k in ("gemm_fwd", "gemm_dx", "gemm_dw") if k in kernels]
-    dominant = max(gemm_classes, key=lambda k: kernels[k]["ms_per_step"])
-    dp = prof[dominant]
-    achieved = dp["flops"] / (dp["ms"] * 1e-3) / 1e12
-    gemm_flops = sum(prof[k]["flops"] for k in gemm_classes)
-    gemm_ms = sum(prof[k]["ms"] for k in gemm_classes)
-    roofline = dict(bound="mfma", kernel=dominant, achieved=achieved, peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
-                    frac=achieved / PEAK_BF16_TFLOPS, traffic=None,
-                    avg_launch_us=1e3 * dp["ms"] / dp["launches"], launches_per_step=dp["launches"] / args.profile_steps,
-                    all_gemms_tflops=gemm_flops / (gemm_ms * 1e-3) / 1e12,
-                    all_gemms_frac=gemm_flops / (gemm_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
-                    measured="HIP events around every launch, on the launch stream, in "
-                             f"{args.profile_steps} extra steps after the timed region")
+    roofline = None
+    if gemm_classes:
+        dominant = max(gemm_classes, key=lambda k: kernels[k]["ms_per_step"])
+        dp = prof[dominant]
+        achieved = dp["flops"] / (dp["ms"] * 1e-3) / 1e12
+        gemm_flops = sum(prof[k]["flops"] for k in gemm_classes)
+        gemm_ms = sum(prof[k]["ms"] for k in gemm_classes)
+        roofline = dict(bound="mfma", kernel=dominant, achieved=achieved, peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
+                        frac=achieved / PEAK_BF16_TFLOPS, traffic=None,
+                        avg_launch_us=1e3 * dp["ms"] / dp["launches"],
+                        launches_per_step=dp["launches"] / args.profile_steps,
+                        all_gemms_tflops=gemm_flops / (gemm_ms * 1e-3) / 1e12,
+                        all_gemms_frac=gemm_flops / (gemm_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+                        measured="HIP events around every launch, on the launch stream, in "
+                                 f"{args.profile_steps} extra steps after the timed region")
 
     out = dict(metric="trained tokens/sec on 1 MI355X (BERT-base step) + % peak bf16 MFMA",
                value=tokens_per_step * args.steps / dt, unit="tokens/s", n_gpus=1, steps=args.steps, warmup=args.warmup,

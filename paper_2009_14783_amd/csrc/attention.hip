@@ -2,8 +2,9 @@
 // qkv is [B*L, 3H]: per token the query, key and value vectors of all heads; head h occupies
 // columns h*64 .. h*64+63 of each third.  Key l' of sequence b takes part iff l' < lens[b].
 //
-// Reference-precision kernels (any element type): one thread per query (or key) row, K/V (or
-// Q/dO) blocks of 64 rows staged in LDS as fp32, online softmax, fp32 everywhere.
+// This file: the fp32 kernels (one thread per query or key row, K/V or Q/dO blocks of 64 rows
+// staged in LDS as fp32, online softmax) and the dispatch; the bf16 MFMA kernels are in
+// attention_mfma.hip.
 #include "common.h"
 
 namespace {
@@ -169,6 +170,10 @@ __global__ __launch_bounds__(64) void attn_bwd_dkv_simt(const T* __restrict__ qk
 
 }  // namespace
 
+void launch_attention_fwd_mfma(const void* qkv, const int32_t* lens, int B, int L, int A, void* out, float* lse, hipStream_t s);
+void launch_attention_bwd_mfma(const void* qkv, const void* out, const float* lse, const void* d_out, const int32_t* lens, int B, int L,
+                               int A, void* dqkv, float* dvec, hipStream_t s);
+
 hs_status launch_attention_fwd(hs_ctx* ctx, int dtype, const void* qkv, const int32_t* lens, int B, int L, int A, void* out, float* lse,
                                hipStream_t s) {
   if (B <= 0 || L <= 0) return HS_OK;
@@ -176,7 +181,7 @@ hs_status launch_attention_fwd(hs_ctx* ctx, int dtype, const void* qkv, const in
   const double by = (double)B * L * A * D * 4.0 * esize(dtype);
   KScope scope(ctx ? ctx->prof : nullptr, KC_ATTN_FWD, fl, by, s);
   dim3 grid((L + 63) / 64, A, B);
-  if (dtype == HS_BF16) hipLaunchKernelGGL(attn_fwd_simt<bf16>, grid, dim3(64), 0, s, (const bf16*)qkv, lens, L, A, (bf16*)out, lse);
+  if (dtype == HS_BF16) launch_attention_fwd_mfma(qkv, lens, B, L, A, out, lse, s);
   else hipLaunchKernelGGL(attn_fwd_simt<float>, grid, dim3(64), 0, s, (const float*)qkv, lens, L, A, (float*)out, lse);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return hs_fail(ctx, HS_ERR_HIP, std::string("attention_fwd: ") + hipGetErrorString(e));
@@ -191,8 +196,7 @@ hs_status launch_attention_bwd(hs_ctx* ctx, int dtype, const void* qkv, const vo
   KScope scope(ctx ? ctx->prof : nullptr, KC_ATTN_BWD, fl, by, s);
   dim3 grid((L + 63) / 64, A, B);
   if (dtype == HS_BF16) {
-    hipLaunchKernelGGL(attn_bwd_dq_simt<bf16>, grid, dim3(64), 0, s, (const bf16*)qkv, (const bf16*)out, lse, (const bf16*)d_out, lens, L, A, (bf16*)dqkv, dvec);
-    hipLaunchKernelGGL(attn_bwd_dkv_simt<bf16>, grid, dim3(64), 0, s, (const bf16*)qkv, lse, (const bf16*)d_out, (const float*)dvec, lens, L, A, (bf16*)dqkv);
+    launch_attention_bwd_mfma(qkv, out, lse, d_out, lens, B, L, A, dqkv, dvec, s);
   } else {
     hipLaunchKernelGGL(attn_bwd_dq_simt<float>, grid, dim3(64), 0, s, (const float*)qkv, (const float*)out, lse, (const float*)d_out, lens, L, A, (float*)dqkv, dvec);
     hipLaunchKernelGGL(attn_bwd_dkv_simt<float>, grid, dim3(64), 0, s, (const float*)qkv, lse, (const float*)d_out, (const float*)dvec, lens, L, A, (float*)dqkv);

@@ -1,0 +1,337 @@
+// bf16 MFMA attention (head dimension 64), forward and backward, fp32 softmax statistics.
+//
+// Every kernel has the same shape.  A wave OWNS 32 rows (queries, or keys in the dK/dV kernel)
+// whose vectors stay in registers as MFMA B operands, and STREAMS the other side through LDS in
+// blocks of 64 rows kept in their natural [row][64] layout.  Score tiles are computed transposed,
+// tile[streamed row][owned row], so that each lane holds ONE owned row (lane % 32) and 16 streamed
+// rows: reductions over the streamed index are then in-lane plus one exchange between the two
+// half-waves.  The second product needs the score tile as a B operand and the streamed block
+// transposed as the A operand; the transposed fragment comes from the LDS transpose read, with
+// the 16 contraction slots ordered exactly as the result registers of the score tile are
+// (register r of lane l is streamed row 8*(r/4) + 4*(l/32) + r%4), so no data moves between lanes.
+#include "common.h"
+
+namespace {
+
+constexpr int DH = 64;
+constexpr int LDT = 72;                 // LDS row stride in elements (144 B: conflict-free 16-byte row reads)
+constexpr float LOG2E = 1.4426950408889634f;
+constexpr float LN2 = 0.6931471805599453f;
+constexpr float SCALE2 = 0.125f * LOG2E;   // 1/sqrt(64) folded with the change to base 2
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// rows r0..r0+63 of a [*, ld] bf16 matrix (64 columns starting at the given pointer) -> LDS tile;
+// rows at or beyond row_limit are zero.  256 threads, two 16-byte chunks each.
+__device__ __forceinline__ void stage64(bf16* tile, const bf16* __restrict__ src, int64_t ld, int r0, int row_limit, int tid) {
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int c = tid + i * 256;
+    const int r = c >> 3, col = (c & 7) * 8;
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (r0 + r < row_limit) v = *(const uint4*)(src + (int64_t)(r0 + r) * ld + col);
+    *(uint4*)(tile + r * LDT + col) = v;
+  }
+}
+
+// A/B fragment of tile rows: lane gets row rbase + lane%32, columns 16*ks + 8*(lane/32) .. +7
+__device__ __forceinline__ bf16x8 frag_rows(const bf16* tile, int rbase, int ks, int lane) {
+  return *(const bf16x8*)(tile + (rbase + (lane & 31)) * LDT + ks * 16 + (lane >> 5) * 8);
+}
+// the same fragment straight from global memory for the owned rows (zero beyond row_limit)
+__device__ __forceinline__ bf16x8 frag_rows_global(const bf16* __restrict__ src, int64_t ld, int row, int row_limit, int ks, int lane) {
+  bf16x8 z;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) z[e] = (bf16)0.0f;
+  if (row < row_limit) z = *(const bf16x8*)(src + (int64_t)row * ld + ks * 16 + (lane >> 5) * 8);
+  return z;
+}
+// Transposed A fragment: MFMA row i = tile column c0 + lane%32; contraction slot (g = lane/32, e)
+// = tile row rb + 16*step + 4*g + (e & 3) + 8*(e >> 2).
+__device__ __forceinline__ bf16x8 frag_cols_t(const bf16* tile, int rb, int step, int c0, int lane) {
+  const int row = rb + 16 * step + 4 * (lane >> 5) + ((lane & 15) >> 2);
+  const int col = c0 + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+  typedef s16x4 __attribute__((address_space(3))) * lds_v4;
+  union { struct { s16x4 lo, hi; } p; bf16x8 v; } u;
+  u.p.lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(tile + row * LDT + col));
+  u.p.hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4)(tile + (row + 8) * LDT + col));
+  return u.v;
+}
+// streamed-row index (within a 32-row tile) of result register r
+__device__ __forceinline__ int tile_row(int r, int lane) { return 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3); }
+
+__device__ __forceinline__ bf16x8 pack8(const f32x16& v, int step) {
+  bf16x8 o;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) o[e] = (bf16)v[8 * step + e];
+  return o;
+}
+
+// writes a transposed [64 x 32] fp32 accumulator pair (two 32-row column blocks) as 32 rows of
+// 64 bf16: lane owns row (lane%32) and, per register quad, 4 consecutive columns
+__device__ __forceinline__ void store_owned_rows(bf16* __restrict__ dst_row, const f32x16 (&acc)[2], float scale, int lane) {
+#pragma unroll
+  for (int db = 0; db < 2; ++db)
+#pragma unroll
+    for (int qd = 0; qd < 4; ++qd) {
+      bf16x4 o;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) o[e] = (bf16)(acc[db][4 * qd + e] * scale);
+      *(bf16x4*)(dst_row + 32 * db + 8 * qd + 4 * (lane >> 5)) = o;
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// forward: wave owns 32 queries, streams keys/values
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void attn_fwd_mfma(const bf16* __restrict__ qkv, const int32_t* __restrict__ lens, int L, int A,
+                                                     bf16* __restrict__ out, float* __restrict__ lse) {
+  __shared__ __attribute__((aligned(16))) bf16 Ks[64 * LDT];
+  __shared__ __attribute__((aligned(16))) bf16 Vs[64 * LDT];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int b = blockIdx.z, h = blockIdx.y;
+  const int H = A * DH;
+  const int64_t ld = 3 * (int64_t)H;
+  int len = lens[b];
+  len = len < 1 ? 1 : (len > L ? L : len);
+  const bf16* base = qkv + (int64_t)b * L * ld + h * DH;
+  const int q = blockIdx.x * 128 + wave * 32 + (lane & 31);     // the query this lane owns
+
+  bf16x8 qf[4];
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) qf[ks] = frag_rows_global(base, ld, q, L, ks, lane);
+  f32x16 o[2];
+#pragma unroll
+  for (int db = 0; db < 2; ++db)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) o[db][r] = 0.f;
+  float m2 = -1.0e30f, lsum = 0.f;
+
+  for (int k0 = 0; k0 < len; k0 += 64) {
+    __syncthreads();
+    stage64(Ks, base + H, ld, k0, len, tid);
+    stage64(Vs, base + 2 * H, ld, k0, len, tid);
+    __syncthreads();
+#pragma unroll
+    for (int sub = 0; sub < 2; ++sub) {
+      const int kb = 32 * sub;
+      if (k0 + kb < len) {
+        f32x16 st;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) st[r] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(Ks, kb, ks, lane), qf[ks], st, 0, 0, 0);
+        float mloc = -1.0e30f;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const bool ok = k0 + kb + tile_row(r, lane) < len;
+          st[r] = ok ? st[r] * SCALE2 : -1.0e30f;
+          mloc = fmaxf(mloc, st[r]);
+        }
+        mloc = fmaxf(mloc, __shfl_xor(mloc, 32));
+        const float mn = fmaxf(m2, mloc);
+        const float alpha = fast_exp2(m2 - mn);
+        float ps = 0.f;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const bool ok = k0 + kb + tile_row(r, lane) < len;
+          const float p = ok ? fast_exp2(st[r] - mn) : 0.f;
+          st[r] = p;
+          ps += p;
+        }
+        lsum = lsum * alpha + ps;
+        m2 = mn;
+#pragma unroll
+        for (int db = 0; db < 2; ++db)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
+        const bf16x8 p0 = pack8(st, 0), p1 = pack8(st, 1);
+#pragma unroll
+        for (int db = 0; db < 2; ++db) {
+          o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols_t(Vs, kb, 0, 32 * db, lane), p0, o[db], 0, 0, 0);
+          o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols_t(Vs, kb, 1, 32 * db, lane), p1, o[db], 0, 0, 0);
+        }
+      }
+    }
+  }
+  lsum += __shfl_xor(lsum, 32);
+  if (q < L) {
+    store_owned_rows(out + ((int64_t)b * L + q) * H + h * DH, o, 1.0f / lsum, lane);
+    if (lane < 32) lse[((int64_t)b * A + h) * L + q] = (m2 + __log2f(lsum)) * LN2;
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// backward 1: wave owns 32 queries, streams keys/values -> dq and dvec[q] = sum_d dO[q,d] O[q,d]
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void attn_bwd_dq_mfma(const bf16* __restrict__ qkv, const bf16* __restrict__ out,
+                                                        const float* __restrict__ lse, const bf16* __restrict__ d_out,
+                                                        const int32_t* __restrict__ lens, int L, int A, bf16* __restrict__ dqkv,
+                                                        float* __restrict__ dvec) {
+  __shared__ __attribute__((aligned(16))) bf16 Ks[64 * LDT];
+  __shared__ __attribute__((aligned(16))) bf16 Vs[64 * LDT];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int b = blockIdx.z, h = blockIdx.y;
+  const int H = A * DH;
+  const int64_t ld = 3 * (int64_t)H;
+  int len = lens[b];
+  len = len < 1 ? 1 : (len > L ? L : len);
+  const bf16* base = qkv + (int64_t)b * L * ld + h * DH;
+  const bf16* go = d_out + (int64_t)b * L * H + h * DH;
+  const bf16* oo = out + (int64_t)b * L * H + h * DH;
+  const int q = blockIdx.x * 128 + wave * 32 + (lane & 31);
+
+  // padded queries (q >= len) own all-zero fragments and therefore produce zero rows
+  bf16x8 qf[4], gf[4];
+  float dpart = 0.f;
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) {
+    qf[ks] = frag_rows_global(base, ld, q, len, ks, lane);
+    gf[ks] = frag_rows_global(go, H, q, len, ks, lane);
+    const bf16x8 of = frag_rows_global(oo, H, q, len, ks, lane);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) dpart = fmaf((float)gf[ks][e], (float)of[e], dpart);
+  }
+  const float dq_row = dpart + __shfl_xor(dpart, 32);
+  const float lse2 = (q < len) ? lse[((int64_t)b * A + h) * L + q] * LOG2E : 0.f;
+  f32x16 acc[2];
+#pragma unroll
+  for (int db = 0; db < 2; ++db)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[db][r] = 0.f;
+
+  for (int k0 = 0; k0 < len; k0 += 64) {
+    __syncthreads();
+    stage64(Ks, base + H, ld, k0, len, tid);
+    stage64(Vs, base + 2 * H, ld, k0, len, tid);
+    __syncthreads();
+#pragma unroll
+    for (int sub = 0; sub < 2; ++sub) {
+      const int kb = 32 * sub;
+      if (k0 + kb < len) {
+        f32x16 st, dp;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) { st[r] = 0.f; dp[r] = 0.f; }
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+          st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(Ks, kb, ks, lane), qf[ks], st, 0, 0, 0);
+          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(Vs, kb, ks, lane), gf[ks], dp, 0, 0, 0);
+        }
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const bool ok = (k0 + kb + tile_row(r, lane) < len) && (q < len);
+          const float p = ok ? fast_exp2(st[r] * SCALE2 - lse2) : 0.f;
+          st[r] = p * (dp[r] - dq_row);
+        }
+        const bf16x8 s0 = pack8(st, 0), s1 = pack8(st, 1);
+#pragma unroll
+        for (int db = 0; db < 2; ++db) {
+          acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols_t(Ks, kb, 0, 32 * db, lane), s0, acc[db], 0, 0, 0);
+          acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols_t(Ks, kb, 1, 32 * db, lane), s1, acc[db], 0, 0, 0);
+        }
+      }
+    }
+  }
+  if (q < L) {
+    store_owned_rows(dqkv + ((int64_t)b * L + q) * ld + h * DH, acc, 0.125f, lane);
+    if (lane < 32) dvec[((int64_t)b * A + h) * L + q] = dq_row;
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// backward 2: wave owns 32 keys, streams queries / output gradients -> dk, dv
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void attn_bwd_dkv_mfma(const bf16* __restrict__ qkv, const float* __restrict__ lse,
+                                                         const bf16* __restrict__ d_out, const float* __restrict__ dvec,
+                                                         const int32_t* __restrict__ lens, int L, int A, bf16* __restrict__ dqkv) {
+  __shared__ __attribute__((aligned(16))) bf16 Qs[64 * LDT];
+  __shared__ __attribute__((aligned(16))) bf16 Gs[64 * LDT];
+  __shared__ float lse2_s[64], dvec_s[64];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int b = blockIdx.z, h = blockIdx.y;
+  const int H = A * DH;
+  const int64_t ld = 3 * (int64_t)H;
+  int len = lens[b];
+  len = len < 1 ? 1 : (len > L ? L : len);
+  const bf16* base = qkv + (int64_t)b * L * ld + h * DH;
+  const bf16* go = d_out + (int64_t)b * L * H + h * DH;
+  const int kj = blockIdx.x * 128 + wave * 32 + (lane & 31);    // the key this lane owns
+  const bool wave_active = blockIdx.x * 128 + wave * 32 < len;  // wave-uniform
+
+  bf16x8 kf[4], vf[4];
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) {
+    kf[ks] = frag_rows_global(base + H, ld, kj, len, ks, lane);
+    vf[ks] = frag_rows_global(base + 2 * H, ld, kj, len, ks, lane);
+  }
+  f32x16 dk[2], dv[2];
+#pragma unroll
+  for (int db = 0; db < 2; ++db)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { dk[db][r] = 0.f; dv[db][r] = 0.f; }
+
+  for (int q0 = 0; q0 < len; q0 += 64) {        // padded queries carry no gradient
+    __syncthreads();
+    stage64(Qs, base, ld, q0, len, tid);
+    stage64(Gs, go, H, q0, len, tid);
+    if (tid < 64) {
+      const bool ok = q0 + tid < len;
+      lse2_s[tid] = ok ? lse[((int64_t)b * A + h) * L + q0 + tid] * LOG2E : 0.f;
+      dvec_s[tid] = ok ? dvec[((int64_t)b * A + h) * L + q0 + tid] : 0.f;
+    }
+    __syncthreads();
+    if (wave_active) {
+#pragma unroll
+      for (int sub = 0; sub < 2; ++sub) {
+        const int qb = 32 * sub;
+        if (q0 + qb < len) {
+          f32x16 st, dp;
+#pragma unroll
+          for (int r = 0; r < 16; ++r) { st[r] = 0.f; dp[r] = 0.f; }
+#pragma unroll
+          for (int ks = 0; ks < 4; ++ks) {
+            st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(Qs, qb, ks, lane), kf[ks], st, 0, 0, 0);
+            dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(Gs, qb, ks, lane), vf[ks], dp, 0, 0, 0);
+          }
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int qi = qb + tile_row(r, lane);
+            const bool ok = (q0 + qi < len) && (kj < len);
+            const float p = ok ? fast_exp2(st[r] * SCALE2 - lse2_s[qi]) : 0.f;
+            st[r] = p;
+            dp[r] = p * (dp[r] - dvec_s[qi]);
+          }
+          const bf16x8 p0 = pack8(st, 0), p1 = pack8(st, 1), s0 = pack8(dp, 0), s1 = pack8(dp, 1);
+#pragma unroll
+          for (int db = 0; db < 2; ++db) {
+            dv[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols_t(Gs, qb, 0, 32 * db, lane), p0, dv[db], 0, 0, 0);
+            dv[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols_t(Gs, qb, 1, 32 * db, lane), p1, dv[db], 0, 0, 0);
+            dk[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols_t(Qs, qb, 0, 32 * db, lane), s0, dk[db], 0, 0, 0);
+            dk[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols_t(Qs, qb, 1, 32 * db, lane), s1, dk[db], 0, 0, 0);
+          }
+        }
+      }
+    }
+  }
+  if (kj < L) {
+    bf16* row = dqkv + ((int64_t)b * L + kj) * ld + h * DH;
+    store_owned_rows(row + H, dk, 0.125f, lane);
+    store_owned_rows(row + 2 * H, dv, 1.0f, lane);
+  }
+}
+
+}  // namespace
+
+void launch_attention_fwd_mfma(const void* qkv, const int32_t* lens, int B, int L, int A, void* out, float* lse, hipStream_t s) {
+  dim3 grid((L + 127) / 128, A, B);
+  hipLaunchKernelGGL(attn_fwd_mfma, grid, dim3(256), 0, s, (const bf16*)qkv, lens, L, A, (bf16*)out, lse);
+}
+
+void launch_attention_bwd_mfma(const void* qkv, const void* out, const float* lse, const void* d_out, const int32_t* lens, int B, int L,
+                               int A, void* dqkv, float* dvec, hipStream_t s) {
+  dim3 grid((L + 127) / 128, A, B);
+  hipLaunchKernelGGL(attn_bwd_dq_mfma, grid, dim3(256), 0, s, (const bf16*)qkv, (const bf16*)out, lse, (const bf16*)d_out, lens, L, A,
+                     (bf16*)dqkv, dvec);
+  hipLaunchKernelGGL(attn_bwd_dkv_mfma, grid, dim3(256), 0, s, (const bf16*)qkv, lse, (const bf16*)d_out, (const float*)dvec, lens, L, A,
+                     (bf16*)dqkv);
+}

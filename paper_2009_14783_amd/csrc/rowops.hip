@@ -114,13 +114,37 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(const T* __restrict__ dy, c
   }
 }
 
-// out[col] = beta*out[col] + sum_p partials[p*stride + col], p ascending
-__global__ void sum_partials_kernel(const float* __restrict__ partials, int np, int64_t stride, int C, float* __restrict__ out, float beta) {
-  const int col = blockIdx.x * blockDim.x + threadIdx.x;
-  if (col >= C) return;
+// out_q[col] = beta*out_q[col] + sum_p partials[p*pstride + q*qstride + col] for up to three quantities q
+// (blockIdx.y).  Fixed summation tree: wave w of the block adds p = w, w+4, w+8, ... in ascending order,
+// then the four wave sums are added in wave order.
+__global__ __launch_bounds__(256) void sum_partials_kernel(const float* __restrict__ partials, int np, int64_t pstride, int64_t qstride,
+                                                           int C, float* __restrict__ out0, float* __restrict__ out1,
+                                                           float* __restrict__ out2, float beta) {
+  __shared__ float red[4][64];
+  const int q = blockIdx.y;
+  float* out = q == 0 ? out0 : (q == 1 ? out1 : out2);
+  if (!out) return;                                   // uniform over the block
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int col = blockIdx.x * 64 + lane;
   float s = 0.f;
-  for (int p = 0; p < np; ++p) s += partials[(int64_t)p * stride + col];
-  out[col] = (beta != 0.f) ? beta * out[col] + s : s;
+  if (col < C) {
+    const float* src = partials + q * qstride + col;
+    int p = wave;
+    for (; p + 28 < np; p += 32) {
+      float a[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) a[u] = src[(int64_t)(p + 4 * u) * pstride];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) s += a[u];
+    }
+    for (; p < np; p += 4) s += src[(int64_t)p * pstride];
+  }
+  red[wave][lane] = s;
+  __syncthreads();
+  if (wave == 0 && col < C) {
+    const float t = ((red[0][lane] + red[1][lane]) + red[2][lane]) + red[3][lane];
+    out[col] = (beta != 0.f) ? beta * out[col] + t : t;
+  }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -134,7 +158,15 @@ __global__ __launch_bounds__(256) void colsum_kernel(const T* __restrict__ x, in
   const int r0 = blockIdx.y * rows_per_chunk;
   const int r1 = min(R, r0 + rows_per_chunk);
   float s = 0.f;
-  for (int r = r0; r < r1; ++r) s += to_f(x[(int64_t)r * ldx + col]);
+  int r = r0;
+  for (; r + 8 <= r1; r += 8) {
+    float a[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) a[u] = to_f(x[(int64_t)(r + u) * ldx + col]);
+#pragma unroll
+    for (int u = 0; u < 8; ++u) s += a[u];
+  }
+  for (; r < r1; ++r) s += to_f(x[(int64_t)r * ldx + col]);
   partials[(int64_t)blockIdx.y * C + col] = s;
 }
 
@@ -384,7 +416,7 @@ hs_status launch_layernorm_fwd(hs_ctx* ctx, int dtype, const void* x, const void
   return HS_OK;
 }
 
-static int ln_bwd_blocks(int R) { int nb = (R + 15) / 16; return nb < 1 ? 1 : (nb > 512 ? 512 : nb); }
+static int ln_bwd_blocks(int R) { int nb = (R + 15) / 16; return nb < 1 ? 1 : (nb > 256 ? 256 : nb); }
 size_t layernorm_bwd_scratch(int R, int H) { return align_up((size_t)ln_bwd_blocks(R) * 3 * H * sizeof(float), 256); }
 
 hs_status launch_layernorm_bwd(hs_ctx* ctx, int dtype, const void* dy, const void* x, const float* stats, const void* gain, void* dx,
@@ -395,10 +427,9 @@ hs_status launch_layernorm_bwd(hs_ctx* ctx, int dtype, const void* dy, const voi
   if (dtype == HS_BF16) hipLaunchKernelGGL(ln_bwd_kernel<bf16>, dim3(nb), dim3(256), 0, s, (const bf16*)dy, (const bf16*)x, stats, (const bf16*)gain, (bf16*)dx, (float*)partials, R, H);
   else hipLaunchKernelGGL(ln_bwd_kernel<float>, dim3(nb), dim3(256), 0, s, (const float*)dy, (const float*)x, stats, (const float*)gain, (float*)dx, (float*)partials, R, H);
   LAUNCH_CHECK(ctx, "layernorm_bwd");
-  float* outs[3] = {d_gain, d_bias, d_colsum};
-  for (int q = 0; q < 3; ++q) {
-    if (!outs[q]) continue;
-    hipLaunchKernelGGL(sum_partials_kernel, dim3((H + 255) / 256), dim3(256), 0, s, (const float*)partials + (size_t)q * H, nb, (int64_t)3 * H, H, outs[q], beta);
+  if (d_gain || d_bias || d_colsum) {
+    hipLaunchKernelGGL(sum_partials_kernel, dim3((H + 63) / 64, 3), dim3(256), 0, s, (const float*)partials, nb, (int64_t)3 * H, (int64_t)H, H,
+                       d_gain, d_bias, d_colsum, beta);
     LAUNCH_CHECK(ctx, "layernorm_bwd finalize");
   }
   return HS_OK;
@@ -453,7 +484,7 @@ hs_status launch_embed_bwd(hs_ctx* ctx, int dtype, const void* de, const int32_t
   return HS_OK;
 }
 
-static int colsum_chunks(int R) { int n = (R + 31) / 32; return n < 1 ? 1 : (n > 64 ? 64 : n); }
+static int colsum_chunks(int R) { int n = (R + 31) / 32; return n < 1 ? 1 : (n > 256 ? 256 : n); }
 size_t colsum_scratch(int R, int C) { return align_up((size_t)colsum_chunks(R) * C * sizeof(float), 256); }
 
 hs_status launch_colsum(hs_ctx* ctx, int dtype, const void* x, int64_t ldx, int R, int C, float* out, float beta, void* partials, hipStream_t s) {
@@ -465,7 +496,8 @@ hs_status launch_colsum(hs_ctx* ctx, int dtype, const void* x, int64_t ldx, int 
   if (dtype == HS_BF16) hipLaunchKernelGGL(colsum_kernel<bf16>, grid, dim3(256), 0, s, (const bf16*)x, ldx, R, C, rpc, (float*)partials);
   else hipLaunchKernelGGL(colsum_kernel<float>, grid, dim3(256), 0, s, (const float*)x, ldx, R, C, rpc, (float*)partials);
   LAUNCH_CHECK(ctx, "colsum");
-  hipLaunchKernelGGL(sum_partials_kernel, dim3((C + 255) / 256), dim3(256), 0, s, (const float*)partials, nch, (int64_t)C, C, out, beta);
+  hipLaunchKernelGGL(sum_partials_kernel, dim3((C + 63) / 64, 1), dim3(256), 0, s, (const float*)partials, nch, (int64_t)C, (int64_t)0, C, out,
+                     (float*)nullptr, (float*)nullptr, beta);
   LAUNCH_CHECK(ctx, "colsum finalize");
   return HS_OK;
 }
