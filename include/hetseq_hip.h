@@ -201,11 +201,13 @@ hs_status hs_profile_read(hs_ctx* ctx, hs_profile_entry* out, int32_t* n);
  * C2 = GELU(C) (C2 same type and ldc as C); 3 C = acc * GELU'(aux[m,n]).
  * In bf16 mode rows of operands must be 16-byte aligned (leading dimensions multiples of 8) and
  * the 8-element chunk that contains the last valid element of a contiguous row must be readable
- * and finite. */
+ * and finite.  scratch (dev, scratch_bytes, may be NULL): when given and the output has too few
+ * tiles to fill the chip, the contraction is split, the fp32 partial sums go to scratch and are
+ * added in a fixed order. */
 hs_status hs_op_gemm(int32_t dtype, int32_t a_kmajor, int32_t b_kmajor, int32_t M, int32_t N, int32_t K,
                      const void* A, int64_t lda, const void* B, int64_t ldb, void* C, int64_t ldc,
                      int32_t c_f32, float beta, const void* bias, int32_t epi, const void* aux,
-                     int64_t ldaux, void* C2, void* stream);
+                     int64_t ldaux, void* C2, void* scratch, size_t scratch_bytes, void* stream);
 
 /* y = LN(x) over rows of length H; writes mean and reciprocal std per row (stats [2, R] float). */
 hs_status hs_op_layernorm_fwd(int32_t dtype, const void* x, const void* gain, const void* bias, void* y,

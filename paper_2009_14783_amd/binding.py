@@ -57,7 +57,7 @@ _SIGNATURES = {
     "hs_cast_params": (_I32, [_P, _P, _SZ, _I32, _P]),
     "hs_profile_enable": (_I32, [_P, _I32]),
     "hs_profile_read": (_I32, [_P, C.POINTER(hs_profile_entry), C.POINTER(_I32)]),
-    "hs_op_gemm": (_I32, [_I32, _I32, _I32, _I32, _I32, _I32, _P, _I64, _P, _I64, _P, _I64, _I32, _F, _P, _I32, _P, _I64, _P, _P]),
+    "hs_op_gemm": (_I32, [_I32, _I32, _I32, _I32, _I32, _I32, _P, _I64, _P, _I64, _P, _I64, _I32, _F, _P, _I32, _P, _I64, _P, _P, _SZ, _P]),
     "hs_op_layernorm_fwd": (_I32, [_I32, _P, _P, _P, _P, _P, _I32, _I32, _F, _P]),
     "hs_op_layernorm_bwd_scratch": (_SZ, [_I32, _I32]),
     "hs_op_layernorm_bwd": (_I32, [_I32, _P, _P, _P, _P, _P, _P, _P, _P, _F, _I32, _I32, _P, _P]),
@@ -208,9 +208,9 @@ def hs_profile_read(ctx):
 
 
 def hs_op_gemm(dtype, a_kmajor, b_kmajor, M, N, K, A, lda, B, ldb, Cm, ldc, c_f32=0, beta=0.0, bias=None, epi=0, aux=None,
-               ldaux=0, C2=None, stream=None):
+               ldaux=0, C2=None, scratch=None, scratch_bytes=0, stream=None):
     _check(lib().hs_op_gemm(dtype, a_kmajor, b_kmajor, M, N, K, _ptr(A), lda, _ptr(B), ldb, _ptr(Cm), ldc, c_f32, beta,
-                            _ptr(bias), epi, _ptr(aux), ldaux, _ptr(C2), _stream(stream)))
+                            _ptr(bias), epi, _ptr(aux), ldaux, _ptr(C2), _ptr(scratch), scratch_bytes, _stream(stream)))
 
 
 def hs_op_layernorm_fwd(dtype, x, gain, bias, y, stats, R, H, eps, stream=None):

@@ -40,10 +40,15 @@ Acts carve_acts(const hs_model_cfg& c, int B, int L, void* base) {
 
 int padded_vocab(int V) { return (V + 63) / 64 * 64; }
 
+// scratch for split-K partial sums: room for 8 partial copies of the largest weight-gradient matrix
+size_t gemm_scratch_bytes(const hs_model_cfg& c) {
+  return std::max<size_t>((size_t)32 << 20, (size_t)8 * c.hidden * std::max(c.ffn, 3 * c.hidden) * sizeof(float));
+}
+
 struct HeadWs {
-  void *grow, *tpre, *tact, *t, *dlogits, *dt, *dtact, *dtpre, *dg, *ln_part, *cs_part;
+  void *grow, *tpre, *tact, *t, *dlogits, *dt, *dtact, *dtpre, *dg, *ln_part, *cs_part, *gemm_ws;
   float *stats, *logits, *row_loss;
-  size_t total;
+  size_t total, gemm_ws_bytes;
 };
 HeadWs carve_head(const hs_model_cfg& c, int M, void* base) {
   const size_t H = c.hidden, es = esize(c.compute), Vp = padded_vocab(c.vocab), m = (size_t)M;
@@ -57,14 +62,16 @@ HeadWs carve_head(const hs_model_cfg& c, int M, void* base) {
   w.dt = cv.take(m * H * es); w.dtact = cv.take(m * H * es); w.dtpre = cv.take(m * H * es); w.dg = cv.take(m * H * es);
   w.ln_part = cv.take(layernorm_bwd_scratch(M, (int)H));
   w.cs_part = cv.take(colsum_scratch(M, (int)Vp));
+  w.gemm_ws_bytes = gemm_scratch_bytes(c);
+  w.gemm_ws = cv.take(w.gemm_ws_bytes);
   w.total = cv.off;
   return w;
 }
 
 struct BwdWs {
-  void *dxa, *dxb, *dy, *dh, *dctx, *dqkv, *ln_part, *cs_part, *emb;
+  void *dxa, *dxb, *dy, *dh, *dctx, *dqkv, *ln_part, *cs_part, *emb, *gemm_ws;
   float* dvec;
-  size_t total;
+  size_t total, gemm_ws_bytes;
 };
 BwdWs carve_bwd(const hs_model_cfg& c, int B, int L, void* base) {
   const size_t T = (size_t)B * L, H = c.hidden, F = c.ffn, es = esize(c.compute);
@@ -76,6 +83,8 @@ BwdWs carve_bwd(const hs_model_cfg& c, int B, int L, void* base) {
   w.ln_part = cv.take(layernorm_bwd_scratch((int)T, (int)H));
   w.cs_part = cv.take(colsum_scratch((int)T, (int)std::max(F, 3 * H)));
   w.emb = cv.take(embed_bwd_scratch((int)T, (int)H));
+  w.gemm_ws_bytes = gemm_scratch_bytes(c);
+  w.gemm_ws = cv.take(w.gemm_ws_bytes);
   w.total = cv.off;
   return w;
 }
@@ -99,6 +108,7 @@ GemmArgs gemm_args(int dtype, int ak, int bk, int M, int N, int K, const void* A
   g.dtype = dtype; g.a_kmajor = ak; g.b_kmajor = bk; g.M = M; g.N = N; g.K = K;
   g.A = A; g.lda = lda; g.B = B; g.ldb = ldb; g.C = C; g.ldc = ldc;
   g.c_f32 = 0; g.beta = 0.f; g.bias = nullptr; g.epi = 0; g.aux = nullptr; g.ldaux = 0; g.C2 = nullptr;
+  g.ws = nullptr; g.ws_bytes = 0;
   return g;
 }
 
@@ -192,34 +202,35 @@ hs_status hs_mlm_loss(hs_ctx* ctx, const void* w, const void* hidden, const int3
   }
   HeadWs h = carve_head(c, M, workspace);
   const float beta = accumulate ? 1.f : 0.f;
+  auto run_gemm = [&](GemmArgs& a) { a.ws = h.gemm_ws; a.ws_bytes = h.gemm_ws_bytes; return launch_gemm(ctx, a, s); };
 
   HS_TRY(launch_gather_rows(ctx, dt, hidden, mlm_pos, M, H, h.grow, s));
   GemmArgs ga = gemm_args(dt, 1, 1, M, H, H, h.grow, H, W(ctx, w, o.head_t_w), H, h.tpre, H);
   ga.bias = W(ctx, w, o.head_t_b); ga.epi = 2; ga.C2 = h.tact;
-  HS_TRY(launch_gemm(ctx, ga, s));
+  HS_TRY(run_gemm(ga));
   HS_TRY(launch_layernorm_fwd(ctx, dt, h.tact, W(ctx, w, o.head_ln_g), W(ctx, w, o.head_ln_b), h.t, h.stats, M, H, c.ln_eps, s));
   // logits = t E^T + b_dec, fp32, row stride Vp
   ga = gemm_args(dt, 1, 1, M, V, H, h.t, H, W(ctx, w, o.emb_word), H, h.logits, Vp);
   ga.c_f32 = 1; ga.beta = 0.f; ga.bias = W(ctx, w, o.head_dec_b);
-  HS_TRY(launch_gemm(ctx, ga, s));
+  HS_TRY(run_gemm(ga));
   HS_TRY(launch_ce_loss(ctx, dt, h.logits, Vp, mlm_label, M, V, h.dlogits, h.row_loss, loss_sum, s));
   // decoder bias and the decoder's share of the tied word embedding
   HS_TRY(launch_colsum(ctx, dt, h.dlogits, Vp, M, V, g + o.head_dec_b, beta, h.cs_part, s));
   ga = gemm_args(dt, 0, 0, V, H, M, h.dlogits, Vp, h.t, H, g + o.emb_word, H);
   ga.c_f32 = 1; ga.beta = beta;
-  HS_TRY(launch_gemm(ctx, ga, s));
+  HS_TRY(run_gemm(ga));
   // dt = dlogits E
   ga = gemm_args(dt, 1, 0, M, H, V, h.dlogits, Vp, W(ctx, w, o.emb_word), H, h.dt, H);
-  HS_TRY(launch_gemm(ctx, ga, s));
+  HS_TRY(run_gemm(ga));
   HS_TRY(launch_layernorm_bwd(ctx, dt, h.dt, h.tact, h.stats, W(ctx, w, o.head_ln_g), h.dtact, g + o.head_ln_g, g + o.head_ln_b, nullptr,
                               beta, M, H, h.ln_part, s));
   HS_TRY(launch_gelu_bwd(ctx, dt, h.dtact, h.tpre, h.dtpre, (size_t)M * H, s));
   HS_TRY(launch_colsum(ctx, dt, h.dtpre, H, M, H, g + o.head_t_b, beta, h.cs_part, s));
   ga = gemm_args(dt, 0, 0, H, H, M, h.dtpre, H, h.grow, H, g + o.head_t_w, H);
   ga.c_f32 = 1; ga.beta = beta;
-  HS_TRY(launch_gemm(ctx, ga, s));
+  HS_TRY(run_gemm(ga));
   ga = gemm_args(dt, 1, 0, M, H, H, h.dtpre, H, W(ctx, w, o.head_t_w), H, h.dg, H);
-  HS_TRY(launch_gemm(ctx, ga, s));
+  HS_TRY(run_gemm(ga));
   HS_TRY(launch_scatter_rows(ctx, dt, h.dg, mlm_pos, M, H, d_hidden, s));
   return HS_OK;
 }
@@ -239,6 +250,7 @@ hs_status hs_encoder_bwd(hs_ctx* ctx, const void* w, const void* acts, const int
   Acts a = carve_acts(c, B, L, const_cast<void*>(acts));
   BwdWs ws = carve_bwd(c, B, L, workspace);
   const float beta = accumulate ? 1.f : 0.f;
+  auto run_gemm = [&](GemmArgs& a) { a.ws = ws.gemm_ws; a.ws_bytes = ws.gemm_ws_bytes; return launch_gemm(ctx, a, s); };
 
   const void* dcur = d_hidden;
   for (int i = c.n_layers - 1; i >= 0; --i) {
@@ -251,38 +263,38 @@ hs_status hs_encoder_bwd(hs_ctx* ctx, const void* w, const void* acts, const int
     // dW2 [H,F] = dy2^T h
     GemmArgs ga = gemm_args(dt, 0, 0, H, F, T, ws.dy, H, la.h, F, g + lo.ffn2_w, F);
     ga.c_f32 = 1; ga.beta = beta;
-    HS_TRY(launch_gemm(ctx, ga, s));
+    HS_TRY(run_gemm(ga));
     // dhpre [T,F] = (dy2 W2) * GELU'(hpre)
     ga = gemm_args(dt, 1, 0, T, F, H, ws.dy, H, W(ctx, w, lo.ffn2_w), F, ws.dh, F);
     ga.epi = 3; ga.aux = la.hpre; ga.ldaux = F;
-    HS_TRY(launch_gemm(ctx, ga, s));
+    HS_TRY(run_gemm(ga));
     HS_TRY(launch_colsum(ctx, dt, ws.dh, F, T, F, g + lo.ffn1_b, beta, ws.cs_part, s));
     // dW1 [F,H] = dhpre^T x1
     ga = gemm_args(dt, 0, 0, F, H, T, ws.dh, F, la.x1, H, g + lo.ffn1_w, H);
     ga.c_f32 = 1; ga.beta = beta;
-    HS_TRY(launch_gemm(ctx, ga, s));
+    HS_TRY(run_gemm(ga));
     // dx1 [T,H] = dhpre W1 + dy2
     ga = gemm_args(dt, 1, 0, T, H, F, ws.dh, F, W(ctx, w, lo.ffn1_w), H, ws.dxa, H);
     ga.epi = 1; ga.aux = ws.dy; ga.ldaux = H;
-    HS_TRY(launch_gemm(ctx, ga, s));
+    HS_TRY(run_gemm(ga));
     // LN1 backward: dy1, d gain/bias, colsum(dy1) = d bo
     HS_TRY(launch_layernorm_bwd(ctx, dt, ws.dxa, la.y1, la.st1, W(ctx, w, lo.ln1_g), ws.dy, g + lo.ln1_g, g + lo.ln1_b, g + lo.o_b, beta, T,
                                 H, ws.ln_part, s));
     // dWo [H,H] = dy1^T ctx ; dctx = dy1 Wo
     ga = gemm_args(dt, 0, 0, H, H, T, ws.dy, H, la.ctx, H, g + lo.o_w, H);
     ga.c_f32 = 1; ga.beta = beta;
-    HS_TRY(launch_gemm(ctx, ga, s));
+    HS_TRY(run_gemm(ga));
     ga = gemm_args(dt, 1, 0, T, H, H, ws.dy, H, W(ctx, w, lo.o_w), H, ws.dctx, H);
-    HS_TRY(launch_gemm(ctx, ga, s));
+    HS_TRY(run_gemm(ga));
     HS_TRY(launch_attention_bwd(ctx, dt, la.qkv, la.ctx, la.lse, ws.dctx, lens, B, L, c.n_heads, ws.dqkv, ws.dvec, s));
     HS_TRY(launch_colsum(ctx, dt, ws.dqkv, 3 * H, T, 3 * H, g + lo.qkv_b, beta, ws.cs_part, s));
     // dWqkv [3H,H] = dqkv^T x_in ; dx_in = dqkv Wqkv + dy1
     ga = gemm_args(dt, 0, 0, 3 * H, H, T, ws.dqkv, 3 * H, x_in, H, g + lo.qkv_w, H);
     ga.c_f32 = 1; ga.beta = beta;
-    HS_TRY(launch_gemm(ctx, ga, s));
+    HS_TRY(run_gemm(ga));
     ga = gemm_args(dt, 1, 0, T, H, 3 * H, ws.dqkv, 3 * H, W(ctx, w, lo.qkv_w), H, ws.dxb, H);
     ga.epi = 1; ga.aux = ws.dy; ga.ldaux = H;
-    HS_TRY(launch_gemm(ctx, ga, s));
+    HS_TRY(run_gemm(ga));
     dcur = ws.dxb;
   }
   // embedding LayerNorm, then the two embedding tables
@@ -295,11 +307,12 @@ hs_status hs_encoder_bwd(hs_ctx* ctx, const void* w, const void* acts, const int
 // ---- building blocks ----------------------------------------------------------------------------
 hs_status hs_op_gemm(int32_t dtype, int32_t a_kmajor, int32_t b_kmajor, int32_t M, int32_t N, int32_t K, const void* A, int64_t lda,
                      const void* B, int64_t ldb, void* C, int64_t ldc, int32_t c_f32, float beta, const void* bias, int32_t epi,
-                     const void* aux, int64_t ldaux, void* C2, void* stream) {
+                     const void* aux, int64_t ldaux, void* C2, void* scratch, size_t scratch_bytes, void* stream) {
   if (dtype != HS_FP32 && dtype != HS_BF16) return hs_fail(nullptr, HS_ERR_INVALID_ARG, "hs_op_gemm: bad dtype");
   if (M < 0 || N < 0 || K < 0) return hs_fail(nullptr, HS_ERR_INVALID_ARG, "hs_op_gemm: negative size");
   GemmArgs g = gemm_args(dtype, a_kmajor ? 1 : 0, b_kmajor ? 1 : 0, M, N, K, A, lda, B, ldb, C, ldc);
   g.c_f32 = c_f32 ? 1 : 0; g.beta = beta; g.bias = bias; g.epi = epi; g.aux = aux; g.ldaux = ldaux; g.C2 = C2;
+  g.ws = scratch; g.ws_bytes = scratch ? scratch_bytes : 0;
   return launch_gemm(nullptr, g, (hipStream_t)stream);
 }
 

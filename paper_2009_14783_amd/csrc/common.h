@@ -110,6 +110,7 @@ struct GemmArgs {
   int c_f32; float beta;
   const void* bias;
   int epi; const void* aux; int64_t ldaux; void* C2;
+  void* ws; size_t ws_bytes;   // optional scratch for split-K partial sums
 };
 hs_status launch_gemm(hs_ctx* ctx, const GemmArgs& g, hipStream_t s);
 

@@ -3,6 +3,8 @@
 //         contraction index is NOT the contiguous one are staged in their natural layout and read
 //         with the LDS transpose read of gfx950, so every global and LDS access is 16/8 bytes wide.
 //   fp32: plain tiled SIMT kernel (small reference-precision configurations only).
+#include <cstdlib>
+
 #include "common.h"
 
 namespace {
@@ -13,6 +15,8 @@ struct GemmDev {
   int M, N, K;
   int c_f32, epi;
   float beta;
+  float* partial;      // split-K partial sums [splits][M][N], or null
+  int k_per_split;     // multiple of the k-tile
 };
 
 template <class T>
@@ -34,37 +38,97 @@ __device__ __forceinline__ void epilogue_store(const GemmDev& p, int row, int co
 // ------------------------------------------------------------------------------------------
 // bf16 MFMA kernel
 // ------------------------------------------------------------------------------------------
+enum { EPI_PARTIAL = 0, EPI_F32, EPI_ACT, EPI_ACT_RES, EPI_ACT_GELU, EPI_ACT_DGELU };
+
+// Writes the TI x TJ grid of 32x32 result tiles of one wave.  Register r of lane l of a tile is
+// row 8*(r/4) + 4*(l/32) + r%4, column l%32.
+template <int MODE, int TI, int TJ>
+__device__ __forceinline__ void tile_epilogue(const GemmDev& p, const f32x16 (&acc)[TI][TJ], int rbase, int cbase, int lane, int split) {
+  const bf16* bias = (const bf16*)p.bias;
+  float bv[TJ];
+  bool col_ok[TJ];
+#pragma unroll
+  for (int j = 0; j < TJ; ++j) {
+    const int col = cbase + j * 32 + (lane & 31);
+    col_ok[j] = col < p.N;
+    bv[j] = (MODE != EPI_PARTIAL && bias && col_ok[j]) ? (float)bias[col] : 0.f;
+  }
+  const int col0 = cbase + (lane & 31);
+#pragma unroll
+  for (int i = 0; i < TI; ++i) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int row = rbase + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+      if (row < p.M) {
+        // row offsets are computed once per row and used for the TJ columns of this lane
+        const int64_t oc = (MODE == EPI_PARTIAL) ? ((int64_t)split * p.M + row) * p.N + col0 : (int64_t)row * p.ldc + col0;
+        const int64_t oa = (int64_t)row * p.ldaux + col0;
+#pragma unroll
+        for (int j = 0; j < TJ; ++j) {
+          if (!col_ok[j]) continue;
+          float v = acc[i][j][r] + bv[j];
+          if (MODE == EPI_PARTIAL) {
+            p.partial[oc + j * 32] = v;
+          } else if (MODE == EPI_F32) {
+            float* C = (float*)p.C + oc + j * 32;
+            *C = (p.beta != 0.0f) ? p.beta * *C + v : v;
+          } else {
+            if (MODE == EPI_ACT_RES) v += (float)((const bf16*)p.aux)[oa + j * 32];
+            if (MODE == EPI_ACT_DGELU) v *= gelu_grad_f((float)((const bf16*)p.aux)[oa + j * 32]);
+            ((bf16*)p.C)[oc + j * 32] = (bf16)v;
+            if (MODE == EPI_ACT_GELU) ((bf16*)p.C2)[oc + j * 32] = (bf16)gelu_f(v);
+          }
+        }
+      }
+    }
+    // keep the scheduler from overlapping the loads and address arithmetic of different tile rows:
+    // that would cost more registers than the main loop needs and lower the occupancy
+    __builtin_amdgcn_sched_barrier(0);
+  }
+}
+
 constexpr int KPAD = 8;    // k-major LDS rows: BK + 8 elements  (conflict-free 16-byte reads)
 constexpr int MPAD = 32;   // m-major LDS rows: R + 32 elements  (row stride = 64 B mod 256 B)
 
-template <bool KMAJ, int R, int BK>
+template <bool KMAJ, int R, int BK, int NT>
 struct OperandTile {
   static constexpr int LD = KMAJ ? (BK + KPAD) : (R + MPAD);
   static constexpr int ELEMS = KMAJ ? R * LD : BK * LD;
   static constexpr int CPR = KMAJ ? BK / 8 : R / 8;       // 8-element chunks per stored row
-  static constexpr int NCH = R * BK / 8 / 256;            // chunks per thread
-  static_assert(R * BK / 8 % 256 == 0, "tile must split evenly over 256 threads");
+  static constexpr int NCH = R * BK / 8 / NT;             // chunks per thread
+  static_assert(R * BK / 8 % NT == 0, "tile must split evenly over the threads");
 
-  // global -> registers (zero where out of range)
-  static __device__ __forceinline__ void load(uint4 (&reg)[NCH], const bf16* __restrict__ base, int64_t ld, int row0, int rext,
-                                              int k0, int K, int tid) {
+  // Per-thread state of the global side: one pointer per chunk (advanced every k-tile) and whether the
+  // chunk's position along the non-contraction index is inside the matrix.
+  struct Cursor {
+    const bf16* ptr[NCH];
+    int koff[NCH];        // contraction offset of the chunk inside a k-tile
+    bool ok[NCH];
+  };
+  static __device__ __forceinline__ void init(Cursor& cu, const bf16* __restrict__ base, int64_t ld, int row0, int rext, int kbeg, int tid) {
 #pragma unroll
     for (int i = 0; i < NCH; ++i) {
-      const int c = tid + i * 256;
+      const int c = tid + i * NT;
       const int a = c / CPR, b = (c % CPR) * 8;
-      int64_t off; bool ok;
-      if (KMAJ) { ok = (row0 + a < rext) && (k0 + b < K); off = (int64_t)(row0 + a) * ld + k0 + b; }
-      else      { ok = (k0 + a < K) && (row0 + b < rext); off = (int64_t)(k0 + a) * ld + row0 + b; }
+      if (KMAJ) { cu.ok[i] = row0 + a < rext; cu.koff[i] = b; cu.ptr[i] = base + (int64_t)(row0 + a) * ld + kbeg + b; }
+      else      { cu.ok[i] = row0 + b < rext; cu.koff[i] = a; cu.ptr[i] = base + (int64_t)(kbeg + a) * ld + row0 + b; }
+    }
+  }
+  // global -> registers for the k-tile that starts at k0 (zero where out of range), then advance
+  static __device__ __forceinline__ void load(uint4 (&reg)[NCH], Cursor& cu, int64_t ld, int k0, int kend) {
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
       uint4 v = make_uint4(0, 0, 0, 0);
-      if (ok) v = *(const uint4*)(base + off);
+      if (cu.ok[i] && k0 + cu.koff[i] < kend) v = *(const uint4*)cu.ptr[i];
       reg[i] = v;
+      cu.ptr[i] += KMAJ ? (int64_t)BK : (int64_t)BK * ld;
     }
   }
   // registers -> LDS
   static __device__ __forceinline__ void store(const uint4 (&reg)[NCH], bf16* s, int tid) {
 #pragma unroll
     for (int i = 0; i < NCH; ++i) {
-      const int c = tid + i * 256;
+      const int c = tid + i * NT;
       const int a = c / CPR, b = (c % CPR) * 8;
       *(uint4*)(s + a * LD + b) = reg[i];
     }
@@ -90,19 +154,32 @@ struct OperandTile {
   }
 };
 
-template <bool AK, bool BKM, int BM, int BN, int BK>
-__global__ __launch_bounds__(256) void gemm_bf16_mfma(GemmDev p) {
-  typedef OperandTile<AK, BM, BK> TA;
-  typedef OperandTile<BKM, BN, BK> TB;
-  constexpr int WM = BM / 2, WN = BN / 2, TI = WM / 32, TJ = WN / 32;
-  __shared__ __attribute__((aligned(16))) bf16 sA[2][TA::ELEMS];
-  __shared__ __attribute__((aligned(16))) bf16 sB[2][TB::ELEMS];
+// Block tile BM x BN x BK, WGM x WGN waves, each wave (BM/WGM) x (BN/WGN) as 32x32x16 MFMA tiles.
+// blockIdx.z selects a contiguous range of k-tiles (split-K); with more than one split the raw fp32
+// sums go to p.partial[z][M][N] and splitk_reduce_kernel applies the epilogue.
+// waves per SIMD the register allocator should leave room for: accumulators take
+// (BM/WGM)*(BN/WGN)/64 registers per lane out of 512
+constexpr int gemm_occupancy(int bm, int bn, int wgm, int wgn) {
+  const int acc = (bm / wgm) * (bn / wgn) / 64;
+  return acc <= 64 ? 3 : (acc <= 128 ? 2 : 1);
+}
+
+template <bool AK, bool BKM, int BM, int BN, int BK, int WGM, int WGN>
+__global__ __launch_bounds__(64 * WGM * WGN) __attribute__((amdgpu_waves_per_eu(gemm_occupancy(BM, BN, WGM, WGN), 8)))
+void gemm_bf16_mfma(GemmDev p) {
+  constexpr int NT = 64 * WGM * WGN;
+  typedef OperandTile<AK, BM, BK, NT> TA;
+  typedef OperandTile<BKM, BN, BK, NT> TB;
+  constexpr int WM = BM / WGM, WN = BN / WGN, TI = WM / 32, TJ = WN / 32;
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+  bf16* const sA0 = (bf16*)lds_raw;                       // two A buffers, then two B buffers
+  bf16* const sB0 = (bf16*)lds_raw + 2 * TA::ELEMS;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
+  const int wm = wave / WGN, wn = wave % WGN;
   const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
-  const bf16* A = (const bf16*)p.A;
-  const bf16* B = (const bf16*)p.B;
+  const int kbeg = blockIdx.z * p.k_per_split;
+  const int kend = min(p.K, kbeg + p.k_per_split);
 
   f32x16 acc[TI][TJ];
 #pragma unroll
@@ -112,51 +189,65 @@ __global__ __launch_bounds__(256) void gemm_bf16_mfma(GemmDev p) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
+  typename TA::Cursor ca;
+  typename TB::Cursor cb;
+  TA::init(ca, (const bf16*)p.A, p.lda, m0, p.M, kbeg, tid);
+  TB::init(cb, (const bf16*)p.B, p.ldb, n0, p.N, kbeg, tid);
   uint4 ra[TA::NCH], rb[TB::NCH];
-  const int nk = (p.K + BK - 1) / BK;
-  TA::load(ra, A, p.lda, m0, p.M, 0, p.K, tid);
-  TB::load(rb, B, p.ldb, n0, p.N, 0, p.K, tid);
-  TA::store(ra, sA[0], tid);
-  TB::store(rb, sB[0], tid);
+  const int nk = (kend - kbeg + BK - 1) / BK;
+  TA::load(ra, ca, p.lda, kbeg, kend);
+  TB::load(rb, cb, p.ldb, kbeg, kend);
+  TA::store(ra, sA0, tid);
+  TB::store(rb, sB0, tid);
   __syncthreads();
 
   for (int kt = 0; kt < nk; ++kt) {
     const int cur = kt & 1;
     const bool more = kt + 1 < nk;
+    const bf16* sAc = sA0 + cur * TA::ELEMS;
+    const bf16* sBc = sB0 + cur * TB::ELEMS;
     if (more) {
-      TA::load(ra, A, p.lda, m0, p.M, (kt + 1) * BK, p.K, tid);
-      TB::load(rb, B, p.ldb, n0, p.N, (kt + 1) * BK, p.K, tid);
+      TA::load(ra, ca, p.lda, kbeg + (kt + 1) * BK, kend);
+      TB::load(rb, cb, p.ldb, kbeg + (kt + 1) * BK, kend);
     }
 #pragma unroll
     for (int ks = 0; ks < BK / 16; ++ks) {
       bf16x8 fa[TI], fb[TJ];
 #pragma unroll
-      for (int i = 0; i < TI; ++i) fa[i] = TA::frag(sA[cur], wm * WM + i * 32, ks, lane);
+      for (int i = 0; i < TI; ++i) fa[i] = TA::frag(sAc, wm * WM + i * 32, ks, lane);
 #pragma unroll
-      for (int j = 0; j < TJ; ++j) fb[j] = TB::frag(sB[cur], wn * WN + j * 32, ks, lane);
+      for (int j = 0; j < TJ; ++j) fb[j] = TB::frag(sBc, wn * WN + j * 32, ks, lane);
 #pragma unroll
       for (int i = 0; i < TI; ++i)
 #pragma unroll
         for (int j = 0; j < TJ; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
     }
     if (more) {
-      TA::store(ra, sA[cur ^ 1], tid);
-      TB::store(rb, sB[cur ^ 1], tid);
+      TA::store(ra, sA0 + (cur ^ 1) * TA::ELEMS, tid);
+      TB::store(rb, sB0 + (cur ^ 1) * TB::ELEMS, tid);
     }
     __syncthreads();
   }
 
-  // result layout of the 32x32 tile: register r of lane l is row 8*(r/4) + 4*(l/32) + r%4, column l%32
-#pragma unroll
-  for (int i = 0; i < TI; ++i)
-#pragma unroll
-    for (int j = 0; j < TJ; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int row = m0 + wm * WM + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-        const int col = n0 + wn * WN + j * 32 + (lane & 31);
-        epilogue_store<bf16>(p, row, col, acc[i][j][r]);
-      }
+  // The epilogue is selected once per block; each variant is a fully unrolled, branch-light loop
+  // over the accumulator registers (which therefore stay in registers).
+  const int rbase = m0 + wm * WM, cbase = n0 + wn * WN;
+  if (p.partial) tile_epilogue<EPI_PARTIAL, TI, TJ>(p, acc, rbase, cbase, lane, blockIdx.z);
+  else if (p.c_f32) tile_epilogue<EPI_F32, TI, TJ>(p, acc, rbase, cbase, lane, 0);
+  else if (p.epi == 0) tile_epilogue<EPI_ACT, TI, TJ>(p, acc, rbase, cbase, lane, 0);
+  else if (p.epi == 1) tile_epilogue<EPI_ACT_RES, TI, TJ>(p, acc, rbase, cbase, lane, 0);
+  else if (p.epi == 2) tile_epilogue<EPI_ACT_GELU, TI, TJ>(p, acc, rbase, cbase, lane, 0);
+  else tile_epilogue<EPI_ACT_DGELU, TI, TJ>(p, acc, rbase, cbase, lane, 0);
+}
+
+// sums the split-K partials in split order and applies the epilogue
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(GemmDev p, int splits) {
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int64_t mn = (int64_t)p.M * p.N;
+  if (idx >= mn) return;
+  float s = 0.f;
+  for (int z = 0; z < splits; ++z) s += p.partial[z * mn + idx];
+  epilogue_store<bf16>(p, (int)(idx / p.N), (int)(idx % p.N), s);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -213,6 +304,51 @@ __global__ __launch_bounds__(256) void gemm_simt(GemmDev p, int a_kmajor, int b_
 
 }  // namespace
 
+namespace {
+
+template <bool AK, bool BKM, int BM, int BN, int BK, int WGM, int WGN>
+hipError_t launch_one(const GemmDev& p, dim3 grid, hipStream_t s) {
+  constexpr int NT = 64 * WGM * WGN;
+  constexpr size_t lds = 2 * sizeof(bf16) * (OperandTile<AK, BM, BK, NT>::ELEMS + OperandTile<BKM, BN, BK, NT>::ELEMS);
+  auto kern = gemm_bf16_mfma<AK, BKM, BM, BN, BK, WGM, WGN>;
+  static bool configured = false;          // per instantiation; the attribute is per process and device-wide
+  if (!configured && lds > 48 * 1024) {
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+  }
+  configured = true;
+  hipLaunchKernelGGL(kern, grid, dim3(NT), lds, s, p);
+  return hipSuccess;
+}
+
+template <int BM, int BN, int BK, int WGM, int WGN>
+hipError_t launch_cfg(const GemmArgs& g, const GemmDev& p, int splits, hipStream_t s) {
+  dim3 grid((g.N + BN - 1) / BN, (g.M + BM - 1) / BM, splits);
+  if (g.a_kmajor && g.b_kmajor) return launch_one<true, true, BM, BN, BK, WGM, WGN>(p, grid, s);
+  if (g.a_kmajor) return launch_one<true, false, BM, BN, BK, WGM, WGN>(p, grid, s);
+  return launch_one<false, false, BM, BN, BK, WGM, WGN>(p, grid, s);
+}
+
+struct TileCfg { int bm, bn, bk; };
+const TileCfg kCfgs[] = {{128, 128, 32}, {128, 128, 64}, {256, 128, 32}, {256, 128, 64}, {256, 256, 32}, {128, 256, 32},
+                         {256, 128, 32}, {256, 256, 32}, {256, 256, 64}};
+
+hipError_t launch_by_id(int id, const GemmArgs& g, const GemmDev& p, int splits, hipStream_t s) {
+  switch (id) {
+    case 1: return launch_cfg<128, 128, 64, 2, 2>(g, p, splits, s);
+    case 2: return launch_cfg<256, 128, 32, 2, 2>(g, p, splits, s);
+    case 3: return launch_cfg<256, 128, 64, 2, 2>(g, p, splits, s);
+    case 4: return launch_cfg<256, 256, 32, 2, 2>(g, p, splits, s);
+    case 5: return launch_cfg<128, 256, 32, 2, 2>(g, p, splits, s);
+    case 6: return launch_cfg<256, 128, 32, 4, 2>(g, p, splits, s);
+    case 7: return launch_cfg<256, 256, 32, 4, 2>(g, p, splits, s);
+    case 8: return launch_cfg<256, 256, 64, 2, 2>(g, p, splits, s);
+    default: return launch_cfg<128, 128, 32, 2, 2>(g, p, splits, s);
+  }
+}
+
+}  // namespace
+
 hs_status launch_gemm(hs_ctx* ctx, const GemmArgs& g, hipStream_t s) {
   if (g.M <= 0 || g.N <= 0) return HS_OK;  // nothing to write
   if (g.K < 0) return hs_fail(ctx, HS_ERR_INVALID_ARG, "gemm: K < 0");
@@ -224,6 +360,7 @@ hs_status launch_gemm(hs_ctx* ctx, const GemmArgs& g, hipStream_t s) {
   p.A = g.A; p.B = g.B; p.C = g.C; p.C2 = g.C2; p.bias = g.bias; p.aux = g.aux;
   p.lda = g.lda; p.ldb = g.ldb; p.ldc = g.ldc; p.ldaux = g.ldaux;
   p.M = g.M; p.N = g.N; p.K = g.K; p.c_f32 = g.c_f32; p.epi = g.epi; p.beta = g.beta;
+  p.partial = nullptr; p.k_per_split = g.K;
   const double flops = 2.0 * g.M * g.N * (double)g.K;
   const double bytes = ((double)g.M * g.K + (double)g.N * g.K) * esize(g.dtype) + (double)g.M * g.N * (g.c_f32 ? 4 : esize(g.dtype));
   const int kc = (g.a_kmajor && g.b_kmajor) ? KC_GEMM_FWD : (g.a_kmajor ? KC_GEMM_DX : KC_GEMM_DW);
@@ -237,11 +374,33 @@ hs_status launch_gemm(hs_ctx* ctx, const GemmArgs& g, hipStream_t s) {
     if (g.a_kmajor && g.b_kmajor && (g.K % 8))
       return hs_fail(ctx, HS_ERR_SHAPE, "gemm(bf16): K must be a multiple of 8 when both operands are k-major");
     if (!g.a_kmajor && g.b_kmajor) return hs_fail(ctx, HS_ERR_UNIMPLEMENTED, "gemm(bf16): A m-major with B k-major is not built");
-    constexpr int BM = 128, BN = 128, BK = 32;
-    dim3 grid((g.N + BN - 1) / BN, (g.M + BM - 1) / BM);
-    if (g.a_kmajor && g.b_kmajor) hipLaunchKernelGGL((gemm_bf16_mfma<true, true, BM, BN, BK>), grid, dim3(256), 0, s, p);
-    else if (g.a_kmajor) hipLaunchKernelGGL((gemm_bf16_mfma<true, false, BM, BN, BK>), grid, dim3(256), 0, s, p);
-    else hipLaunchKernelGGL((gemm_bf16_mfma<false, false, BM, BN, BK>), grid, dim3(256), 0, s, p);
+    int id = 0;
+    if (const char* e = getenv("HS_GEMM_CFG")) id = atoi(e);
+    if (id < 0 || id > 8) id = 0;
+    const TileCfg tc = kCfgs[id];
+    // split-K when the output has too few tiles to fill the chip and a scratch buffer was given
+    const int64_t tiles = (int64_t)((g.M + tc.bm - 1) / tc.bm) * ((g.N + tc.bn - 1) / tc.bn);
+    int splits = 1;
+    if (g.ws && tiles < 256) {
+      int64_t want = (512 + tiles - 1) / tiles;
+      const int64_t by_k = g.K / (4 * tc.bk), by_ws = (int64_t)(g.ws_bytes / ((size_t)g.M * g.N * sizeof(float)));
+      if (want > by_k) want = by_k;
+      if (want > by_ws) want = by_ws;
+      if (want > 32) want = 32;
+      if (want > 1) splits = (int)want;
+    }
+    if (const char* e = getenv("HS_GEMM_SPLITS")) { int v = atoi(e); if (v >= 1 && g.ws && (size_t)v * g.M * g.N * 4 <= g.ws_bytes) splits = v; }
+    if (splits > 1) {
+      p.partial = (float*)g.ws;
+      p.k_per_split = (int)(((g.K + splits - 1) / splits + tc.bk - 1) / tc.bk * tc.bk);
+      splits = (g.K + p.k_per_split - 1) / p.k_per_split;
+    }
+    hipError_t e = launch_by_id(id, g, p, splits, s);
+    if (e != hipSuccess) return hs_fail(ctx, HS_ERR_HIP, std::string("gemm launch: ") + hipGetErrorString(e));
+    if (splits > 1) {
+      const int64_t mn = (int64_t)g.M * g.N;
+      hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((mn + 255) / 256)), dim3(256), 0, s, p, splits);
+    }
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return hs_fail(ctx, HS_ERR_HIP, std::string("gemm launch: ") + hipGetErrorString(e));

@@ -288,3 +288,31 @@ def test_error_paths_launch_nothing(hs):
         hs.hs_op_layernorm_fwd(0, c, c, c, c, c, 4, 96, 1e-12)
     torch.cuda.synchronize()
     assert float(c.abs().sum()) == 0.0
+
+
+@pytest.mark.parametrize("ak,bk,M,N,K,cf", [(0, 0, 768, 264, 4104, 1), (1, 0, 200, 136, 30522, 0), (1, 1, 130, 72, 2048, 1)])
+def test_gemm_split_k_with_scratch(hs, ak, bk, M, N, K, cf):
+    """Few output tiles and a long contraction: the contraction is split over workgroups and the fp32
+    partial sums are added in a fixed order; the result must not depend on that (beyond fp32 rounding)
+    and must be bit-identical from run to run."""
+    rng = np.random.default_rng(K)
+    A = (rng.standard_normal((M, K) if ak else (K, M)) * 0.1).astype(np.float32)
+    B = (rng.standard_normal((N, K) if bk else (K, N)) * 0.1).astype(np.float32)
+    pad = lambda X: np.pad(X, ((0, 0), (0, (-X.shape[1]) % 8 + 8)))
+    Ap, Bp = pad(A), pad(B)
+    dA, dB = dev(Ap, torch.bfloat16), dev(Bp, torch.bfloat16)
+    bias = rng.standard_normal(N).astype(np.float32)
+    scratch = torch.empty(32 << 20, dtype=torch.uint8, device="cuda")
+    outs = []
+    for _ in range(2):
+        C0 = rng.standard_normal((M, N)).astype(np.float32) if cf else np.zeros((M, N), np.float32)
+        dC = dev(C0, torch.float32 if cf else torch.bfloat16)
+        hs.hs_op_gemm(1, ak, bk, M, N, K, dA, Ap.shape[1], dB, Bp.shape[1], dC, N, c_f32=cf, beta=1.0 if cf else 0.0,
+                      bias=dev(bias, torch.bfloat16), scratch=scratch, scratch_bytes=scratch.numel())
+        torch.cuda.synchronize()
+        Ar, Br = rounded(A, 1), rounded(B, 1)
+        want = (Ar if ak else Ar.T) @ (Br if bk else Br.T).T + rounded(bias, 1) + (C0 if cf else 0.0)
+        assert rel(host(dC), want) < (3e-6 if cf else 4e-3)
+        outs.append(host(dC) - (C0 if cf else 0.0))
+    if not cf:
+        assert np.array_equal(outs[0], outs[1])
