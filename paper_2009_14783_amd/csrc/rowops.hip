@@ -5,27 +5,57 @@
 
 namespace {
 
-constexpr int MAXC = 16;  // columns per lane: hidden <= 1024
+constexpr int MAXC = 16;   // columns per lane (scalar access): hidden <= 1024
+constexpr int MAXCH = 4;   // 4-element chunks per lane (vector access): hidden <= 1024
+
+// 4 consecutive elements as float4 (8-byte access for bfloat16, 16-byte for float)
+template <class T> struct Vec4;
+template <> struct Vec4<float> {
+  static __device__ __forceinline__ float4 ld(const float* p) { return *(const float4*)p; }
+  static __device__ __forceinline__ void st(float* p, float4 v) { *(float4*)p = v; }
+  static __device__ __forceinline__ float4 round(float4 v) { return v; }
+};
+template <> struct Vec4<bf16> {
+  static __device__ __forceinline__ float4 ld(const bf16* p) {
+    const bf16x4 v = *(const bf16x4*)p;
+    return make_float4((float)v[0], (float)v[1], (float)v[2], (float)v[3]);
+  }
+  static __device__ __forceinline__ void st(bf16* p, float4 v) {
+    bf16x4 o;
+    o[0] = (bf16)v.x; o[1] = (bf16)v.y; o[2] = (bf16)v.z; o[3] = (bf16)v.w;
+    *(bf16x4*)p = o;
+  }
+  static __device__ __forceinline__ float4 round(float4 v) {   // what a store followed by a load gives
+    return make_float4((float)(bf16)v.x, (float)(bf16)v.y, (float)(bf16)v.z, (float)(bf16)v.w);
+  }
+};
 
 // ------------------------------------------------------------------------------------------
-// LayerNorm forward: one wave per row
+// LayerNorm forward: one wave per row; lane owns the 4-element chunks lane, lane+64, ...
 // ------------------------------------------------------------------------------------------
 template <class T>
-__device__ __forceinline__ void ln_row(float (&v)[MAXC], int nc, int H, int lane, const T* gain, const T* bias, float eps,
-                                       T* y, float* mean_out, float* rstd_out) {
+__device__ __forceinline__ void ln_row(float4 (&v)[MAXCH], int nch, int H, int lane, const T* __restrict__ gain,
+                                       const T* __restrict__ bias, float eps, T* __restrict__ y, float* mean_out, float* rstd_out) {
   float s = 0.f;
 #pragma unroll
-  for (int c = 0; c < MAXC; ++c) if (c < nc) s += v[c];
+  for (int c = 0; c < MAXCH; ++c) if (c * 64 + lane < nch) s += (v[c].x + v[c].y) + (v[c].z + v[c].w);
   const float mu = wave_sum(s) / (float)H;
   float q = 0.f;
 #pragma unroll
-  for (int c = 0; c < MAXC; ++c) if (c < nc) { const float d = v[c] - mu; q += d * d; }
+  for (int c = 0; c < MAXCH; ++c) if (c * 64 + lane < nch) {
+    const float a = v[c].x - mu, b = v[c].y - mu, d = v[c].z - mu, e = v[c].w - mu;
+    q += (a * a + b * b) + (d * d + e * e);
+  }
   const float var = wave_sum(q) / (float)H;
   const float rstd = 1.0f / sqrtf(var + eps);
 #pragma unroll
-  for (int c = 0; c < MAXC; ++c) if (c < nc) {
-    const int col = c * 64 + lane;
-    y[col] = from_f<T>((v[c] - mu) * rstd * to_f(gain[col]) + to_f(bias[col]));
+  for (int c = 0; c < MAXCH; ++c) if (c * 64 + lane < nch) {
+    const int col = 4 * (c * 64 + lane);
+    const float4 g = Vec4<T>::ld(gain + col), b = Vec4<T>::ld(bias + col);
+    float4 o;
+    o.x = (v[c].x - mu) * rstd * g.x + b.x; o.y = (v[c].y - mu) * rstd * g.y + b.y;
+    o.z = (v[c].z - mu) * rstd * g.z + b.z; o.w = (v[c].w - mu) * rstd * g.w + b.w;
+    Vec4<T>::st(y + col, o);
   }
   if (lane == 0) { *mean_out = mu; *rstd_out = rstd; }
 }
@@ -36,11 +66,11 @@ __global__ __launch_bounds__(256) void ln_fwd_kernel(const T* __restrict__ x, co
   const int lane = threadIdx.x & 63;
   const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= R) return;
-  const int nc = H / 64;
-  float v[MAXC];
+  const int nch = H / 4;
+  float4 v[MAXCH];
 #pragma unroll
-  for (int c = 0; c < MAXC; ++c) if (c < nc) v[c] = to_f(x[(int64_t)row * H + c * 64 + lane]);
-  ln_row<T>(v, nc, H, lane, gain, bias, eps, y + (int64_t)row * H, stats + row, stats + R + row);
+  for (int c = 0; c < MAXCH; ++c) if (c * 64 + lane < nch) v[c] = Vec4<T>::ld(x + (int64_t)row * H + 4 * (c * 64 + lane));
+  ln_row<T>(v, nch, H, lane, gain, bias, eps, y + (int64_t)row * H, stats + row, stats + R + row);
 }
 
 template <class T>
@@ -54,17 +84,18 @@ __global__ __launch_bounds__(256) void embed_ln_fwd_kernel(const T* __restrict__
   int id = ids[row];
   id = id < 0 ? 0 : (id >= V ? V - 1 : id);  // ids are validated by contract; clamp keeps reads in bounds
   const int l = row % L;
-  const int nc = H / 64;
-  float v[MAXC];
+  const int nch = H / 4;
+  float4 v[MAXCH];
 #pragma unroll
-  for (int c = 0; c < MAXC; ++c) if (c < nc) {
-    const int col = c * 64 + lane;
+  for (int c = 0; c < MAXCH; ++c) if (c * 64 + lane < nch) {
+    const int col = 4 * (c * 64 + lane);
+    const float4 a = Vec4<T>::ld(word + (int64_t)id * H + col), b = Vec4<T>::ld(pos + (int64_t)l * H + col);
     // the sum is rounded to the activation type because that is what the backward pass re-reads
-    const T e = from_f<T>(to_f(word[(int64_t)id * H + col]) + to_f(pos[(int64_t)l * H + col]));
-    e_pre[(int64_t)row * H + col] = e;
-    v[c] = to_f(e);
+    const float4 e = Vec4<T>::round(make_float4(a.x + b.x, a.y + b.y, a.z + b.z, a.w + b.w));
+    Vec4<T>::st(e_pre + (int64_t)row * H + col, e);
+    v[c] = e;
   }
-  ln_row<T>(v, nc, H, lane, gain, bias, eps, x0 + (int64_t)row * H, stats + row, stats + R + row);
+  ln_row<T>(v, nch, H, lane, gain, bias, eps, x0 + (int64_t)row * H, stats + row, stats + R + row);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -75,41 +106,57 @@ template <class T>
 __global__ __launch_bounds__(256) void ln_bwd_kernel(const T* __restrict__ dy, const T* __restrict__ x, const float* __restrict__ stats,
                                                      const T* __restrict__ gain, T* __restrict__ dx, float* __restrict__ partials,
                                                      int R, int H) {
-  __shared__ float red[4][MAXC * 64];
+  __shared__ float4 red[4][MAXCH * 64];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int nc = H / 64;
-  float g[MAXC], ag[MAXC], ab[MAXC], as[MAXC];
+  const int nch = H / 4;
+  const float inv_h = 1.0f / (float)H;
+  float4 g[MAXCH], ag[MAXCH], ab[MAXCH], as[MAXCH];
 #pragma unroll
-  for (int c = 0; c < MAXC; ++c) { ag[c] = ab[c] = as[c] = 0.f; g[c] = (c < nc) ? to_f(gain[c * 64 + lane]) : 0.f; }
+  for (int c = 0; c < MAXCH; ++c) {
+    ag[c] = ab[c] = as[c] = make_float4(0.f, 0.f, 0.f, 0.f);
+    g[c] = (c * 64 + lane < nch) ? Vec4<T>::ld(gain + 4 * (c * 64 + lane)) : make_float4(0.f, 0.f, 0.f, 0.f);
+  }
   for (int row = blockIdx.x * 4 + wave; row < R; row += gridDim.x * 4) {
     const float mu = stats[row], rstd = stats[R + row];
-    float xh[MAXC], dyv[MAXC];
+    float4 xh[MAXCH], dyv[MAXCH];
     float s1 = 0.f, s2 = 0.f;
 #pragma unroll
-    for (int c = 0; c < MAXC; ++c) if (c < nc) {
-      const int64_t o = (int64_t)row * H + c * 64 + lane;
-      xh[c] = (to_f(x[o]) - mu) * rstd;
-      dyv[c] = to_f(dy[o]);
-      const float dxh = dyv[c] * g[c];
-      s1 += dxh; s2 += dxh * xh[c];
+    for (int c = 0; c < MAXCH; ++c) if (c * 64 + lane < nch) {
+      const int64_t o = (int64_t)row * H + 4 * (c * 64 + lane);
+      const float4 xv = Vec4<T>::ld(x + o);
+      dyv[c] = Vec4<T>::ld(dy + o);
+      xh[c] = make_float4((xv.x - mu) * rstd, (xv.y - mu) * rstd, (xv.z - mu) * rstd, (xv.w - mu) * rstd);
+      const float4 d = make_float4(dyv[c].x * g[c].x, dyv[c].y * g[c].y, dyv[c].z * g[c].z, dyv[c].w * g[c].w);
+      s1 += (d.x + d.y) + (d.z + d.w);
+      s2 += (d.x * xh[c].x + d.y * xh[c].y) + (d.z * xh[c].z + d.w * xh[c].w);
     }
-    s1 = wave_sum(s1) / (float)H;
-    s2 = wave_sum(s2) / (float)H;
+    s1 = wave_sum(s1) * inv_h;
+    s2 = wave_sum(s2) * inv_h;
 #pragma unroll
-    for (int c = 0; c < MAXC; ++c) if (c < nc) {
-      const float d = rstd * (dyv[c] * g[c] - s1 - xh[c] * s2);
-      const T dr = from_f<T>(d);
-      dx[(int64_t)row * H + c * 64 + lane] = dr;
-      ag[c] += dyv[c] * xh[c]; ab[c] += dyv[c]; as[c] += to_f(dr);
+    for (int c = 0; c < MAXCH; ++c) if (c * 64 + lane < nch) {
+      float4 d;
+      d.x = rstd * (dyv[c].x * g[c].x - s1 - xh[c].x * s2); d.y = rstd * (dyv[c].y * g[c].y - s1 - xh[c].y * s2);
+      d.z = rstd * (dyv[c].z * g[c].z - s1 - xh[c].z * s2); d.w = rstd * (dyv[c].w * g[c].w - s1 - xh[c].w * s2);
+      d = Vec4<T>::round(d);
+      Vec4<T>::st(dx + (int64_t)row * H + 4 * (c * 64 + lane), d);
+      ag[c].x += dyv[c].x * xh[c].x; ag[c].y += dyv[c].y * xh[c].y; ag[c].z += dyv[c].z * xh[c].z; ag[c].w += dyv[c].w * xh[c].w;
+      ab[c].x += dyv[c].x; ab[c].y += dyv[c].y; ab[c].z += dyv[c].z; ab[c].w += dyv[c].w;
+      as[c].x += d.x; as[c].y += d.y; as[c].z += d.z; as[c].w += d.w;
     }
   }
   // combine the four waves of the block in wave order, one quantity at a time
   float* out = partials + (int64_t)blockIdx.x * 3 * H;
   for (int q = 0; q < 3; ++q) {
 #pragma unroll
-    for (int c = 0; c < MAXC; ++c) if (c < nc) red[wave][c * 64 + lane] = (q == 0) ? ag[c] : (q == 1 ? ab[c] : as[c]);
+    for (int c = 0; c < MAXCH; ++c) if (c * 64 + lane < nch) red[wave][c * 64 + lane] = (q == 0) ? ag[c] : (q == 1 ? ab[c] : as[c]);
     __syncthreads();
-    for (int col = threadIdx.x; col < H; col += 256) out[q * H + col] = ((red[0][col] + red[1][col]) + red[2][col]) + red[3][col];
+    for (int ch = threadIdx.x; ch < nch; ch += 256) {
+      const float4 a = red[0][ch], b = red[1][ch], c2 = red[2][ch], d = red[3][ch];
+      float4 t;
+      t.x = ((a.x + b.x) + c2.x) + d.x; t.y = ((a.y + b.y) + c2.y) + d.y;
+      t.z = ((a.z + b.z) + c2.z) + d.z; t.w = ((a.w + b.w) + c2.w) + d.w;
+      *(float4*)(out + q * H + 4 * ch) = t;
+    }
     __syncthreads();
   }
 }
@@ -319,7 +366,8 @@ __global__ __launch_bounds__(512) void sort_ids_kernel(const int32_t* __restrict
 // Runs that lie wholly inside a chunk are added to g_word directly (no other wave touches that
 // row).  A run that continues into a neighbouring chunk is written to carry[chunk][0] (run open
 // to the left, or spanning the whole chunk) or carry[chunk][1] (run open to the right only).
-constexpr int CH = 16;
+// All CH gradient rows of a chunk are fetched before any is used, so the loads overlap.
+constexpr int CH = 8;
 template <class T>
 __global__ __launch_bounds__(256) void word_grad_chunks_kernel(const T* __restrict__ de, const int32_t* __restrict__ skey,
                                                                const int32_t* __restrict__ sval, int Ttok, int H,
@@ -328,40 +376,57 @@ __global__ __launch_bounds__(256) void word_grad_chunks_kernel(const T* __restri
   const int chunk = blockIdx.x * 4 + (threadIdx.x >> 6);
   const int i0 = chunk * CH;
   if (i0 >= Ttok) return;
-  const int i1 = min(Ttok, i0 + CH);
-  const int nc = H / 64;
-  float acc[MAXC];
+  const int n = min(CH, Ttok - i0);
+  const int nch = H / 4;
+  int key[CH];
+  float4 rowv[CH][MAXCH];
 #pragma unroll
-  for (int c = 0; c < MAXC; ++c) acc[c] = 0.f;
-  int run_start = i0;
-  for (int i = i0; i < i1; ++i) {
-    const int key = skey[i];
-    const int64_t t = sval[i];
+  for (int e = 0; e < CH; ++e) {
+    key[e] = (e < n) ? skey[i0 + e] : -1;
+    const int64_t t = (e < n) ? sval[i0 + e] : 0;
 #pragma unroll
-    for (int c = 0; c < MAXC; ++c) if (c < nc) acc[c] += to_f(de[t * H + c * 64 + lane]);
-    const bool last_of_chunk = (i + 1 == i1);
-    const bool run_ends = last_of_chunk || skey[i + 1] != key;
-    if (run_ends) {
-      const bool open_left = (run_start == i0) && (i0 > 0) && (skey[i0 - 1] == key);
-      const bool open_right = last_of_chunk && (i1 < Ttok) && (skey[i1] == key);
-      float* dst;
-      bool add;
-      if (open_left) { dst = carry + ((int64_t)chunk * 2 + 0) * H; add = false; }
-      else if (open_right) { dst = carry + ((int64_t)chunk * 2 + 1) * H; add = false; }
-      else { dst = g_word + (int64_t)key * H; add = true; }
+    for (int c = 0; c < MAXCH; ++c)
+      rowv[e][c] = (e < n && c * 64 + lane < nch) ? Vec4<T>::ld(de + t * H + 4 * (c * 64 + lane)) : make_float4(0.f, 0.f, 0.f, 0.f);
+  }
+  const int key_left = (i0 > 0) ? skey[i0 - 1] : -1;
+  const int key_right = (i0 + n < Ttok) ? skey[i0 + n] : -1;
+  float4 acc[MAXCH];
 #pragma unroll
-      for (int c = 0; c < MAXC; ++c) if (c < nc) {
-        const int col = c * 64 + lane;
-        dst[col] = add ? dst[col] + acc[c] : acc[c];
-        acc[c] = 0.f;
+  for (int c = 0; c < MAXCH; ++c) acc[c] = make_float4(0.f, 0.f, 0.f, 0.f);
+  bool run_from_start = true;
+#pragma unroll
+  for (int e = 0; e < CH; ++e) {
+    if (e < n) {
+#pragma unroll
+      for (int c = 0; c < MAXCH; ++c) { acc[c].x += rowv[e][c].x; acc[c].y += rowv[e][c].y; acc[c].z += rowv[e][c].z; acc[c].w += rowv[e][c].w; }
+      const bool last = (e + 1 == n);
+      const bool run_ends = last || key[(e + 1) % CH] != key[e];
+      if (run_ends) {
+        const bool open_left = run_from_start && key_left == key[e];
+        const bool open_right = last && key_right == key[e];
+        float* dst;
+        bool add;
+        if (open_left) { dst = carry + ((int64_t)chunk * 2 + 0) * H; add = false; }
+        else if (open_right) { dst = carry + ((int64_t)chunk * 2 + 1) * H; add = false; }
+        else { dst = g_word + (int64_t)key[e] * H; add = true; }
+#pragma unroll
+        for (int c = 0; c < MAXCH; ++c) if (c * 64 + lane < nch) {
+          float4* d4 = (float4*)(dst + 4 * (c * 64 + lane));
+          float4 o = acc[c];
+          if (add) { const float4 old = *d4; o.x += old.x; o.y += old.y; o.z += old.z; o.w += old.w; }
+          *d4 = o;
+          acc[c] = make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+        run_from_start = false;
       }
-      run_start = i + 1;
     }
   }
 }
 
 // Joins the runs that cross chunk borders: the wave of the chunk in which such a run STARTS adds
 // its right-open piece and every following left-open piece, in chunk order, then updates g_word.
+// The end of the run is found by bisection in the sorted keys, after which the pieces are fetched
+// eight at a time.
 __global__ __launch_bounds__(256) void word_grad_join_kernel(const int32_t* __restrict__ skey, int Ttok, int H,
                                                              float* __restrict__ g_word, const float* __restrict__ carry) {
   const int lane = threadIdx.x & 63;
@@ -372,24 +437,40 @@ __global__ __launch_bounds__(256) void word_grad_join_kernel(const int32_t* __re
   if (i1 >= Ttok) return;                       // nothing to the right
   const int key = skey[i1 - 1];
   if (skey[i1] != key) return;                  // last run is not open to the right
-  // is the last run of this chunk also open to the left (i.e. it started in an earlier chunk)?
-  const bool whole_chunk = (skey[i0] == key);
-  if (whole_chunk && i0 > 0 && skey[i0 - 1] == key) return;   // a continuation: the starting chunk handles it
-  const int nc = H / 64;
-  float acc[MAXC];
-  // A run that spans this whole chunk but starts here was stored by the chunk kernel in slot 1
-  // (open to the right only), exactly like a run that starts mid-chunk.
+  // a run that also reaches back into the previous chunk is a continuation: its starting chunk handles it
+  if (skey[i0] == key && i0 > 0 && skey[i0 - 1] == key) return;
+  // last index of the run: largest j with skey[j] == key (keys ascend)
+  int lo = i1, hi = Ttok - 1;
+  while (lo < hi) {
+    const int mid = (lo + hi + 1) >> 1;
+    if (skey[mid] == key) lo = mid; else hi = mid - 1;
+  }
+  const int last_chunk = lo / CH;               // every chunk in (chunk, last_chunk] starts with this key
+  const int nch = H / 4;
+  float4 acc[MAXCH];
 #pragma unroll
-  for (int c = 0; c < MAXC; ++c) acc[c] = (c < nc) ? carry[((int64_t)chunk * 2 + 1) * H + c * 64 + lane] : 0.f;
-  for (int ch = chunk + 1; ch * CH < Ttok; ++ch) {
-    if (skey[ch * CH] != key) break;
+  for (int c = 0; c < MAXCH; ++c)
+    acc[c] = (c * 64 + lane < nch) ? *(const float4*)(carry + ((int64_t)chunk * 2 + 1) * H + 4 * (c * 64 + lane)) : make_float4(0.f, 0.f, 0.f, 0.f);
+  for (int ch = chunk + 1; ch <= last_chunk; ch += 8) {
+    float4 v[8][MAXCH];
 #pragma unroll
-    for (int c = 0; c < MAXC; ++c) if (c < nc) acc[c] += carry[((int64_t)ch * 2 + 0) * H + c * 64 + lane];
-    const int e = min(Ttok, ch * CH + CH);
-    if (skey[e - 1] != key) break;              // the run ended inside chunk ch
+    for (int u = 0; u < 8; ++u)
+#pragma unroll
+      for (int c = 0; c < MAXCH; ++c)
+        v[u][c] = (ch + u <= last_chunk && c * 64 + lane < nch)
+                      ? *(const float4*)(carry + ((int64_t)(ch + u) * 2 + 0) * H + 4 * (c * 64 + lane)) : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+#pragma unroll
+      for (int c = 0; c < MAXCH; ++c) { acc[c].x += v[u][c].x; acc[c].y += v[u][c].y; acc[c].z += v[u][c].z; acc[c].w += v[u][c].w; }
   }
 #pragma unroll
-  for (int c = 0; c < MAXC; ++c) if (c < nc) g_word[(int64_t)key * H + c * 64 + lane] += acc[c];
+  for (int c = 0; c < MAXCH; ++c) if (c * 64 + lane < nch) {
+    float4* d4 = (float4*)(g_word + (int64_t)key * H + 4 * (c * 64 + lane));
+    float4 o = *d4;
+    o.x += acc[c].x; o.y += acc[c].y; o.z += acc[c].z; o.w += acc[c].w;
+    *d4 = o;
+  }
 }
 
 }  // namespace
@@ -416,7 +497,7 @@ hs_status launch_layernorm_fwd(hs_ctx* ctx, int dtype, const void* x, const void
   return HS_OK;
 }
 
-static int ln_bwd_blocks(int R) { int nb = (R + 15) / 16; return nb < 1 ? 1 : (nb > 256 ? 256 : nb); }
+static int ln_bwd_blocks(int R) { int nb = (R + 7) / 8; return nb < 1 ? 1 : (nb > 768 ? 768 : nb); }
 size_t layernorm_bwd_scratch(int R, int H) { return align_up((size_t)ln_bwd_blocks(R) * 3 * H * sizeof(float), 256); }
 
 hs_status launch_layernorm_bwd(hs_ctx* ctx, int dtype, const void* dy, const void* x, const float* stats, const void* gain, void* dx,
