@@ -40,8 +40,75 @@ __device__ __forceinline__ void epilogue_store(const GemmDev& p, int row, int co
 // ------------------------------------------------------------------------------------------
 enum { EPI_PARTIAL = 0, EPI_F32, EPI_ACT, EPI_ACT_RES, EPI_ACT_GELU, EPI_ACT_DGELU };
 
+// One group of four consecutive output columns of one row: bias, epilogue, store.  `vec` says that
+// all four columns exist and every pointer involved is aligned for a 4-element access.
+template <int MODE>
+__device__ __forceinline__ void store_quad(const GemmDev& p, int row, int col, float4 v, bool vec, int split) {
+  const bf16* bias = (const bf16*)p.bias;
+  const bf16* aux = (const bf16*)p.aux;
+  if (vec) {
+    if (MODE != EPI_PARTIAL && bias) {
+      const bf16x4 b = *(const bf16x4*)(bias + col);
+      v.x += (float)b[0]; v.y += (float)b[1]; v.z += (float)b[2]; v.w += (float)b[3];
+    }
+    if (MODE == EPI_PARTIAL) {
+      *(float4*)(p.partial + ((int64_t)split * p.M + row) * p.N + col) = v;
+    } else if (MODE == EPI_F32) {
+      float4* C = (float4*)((float*)p.C + (int64_t)row * p.ldc + col);
+      if (p.beta != 0.0f) { const float4 o = *C; v.x += p.beta * o.x; v.y += p.beta * o.y; v.z += p.beta * o.z; v.w += p.beta * o.w; }
+      *C = v;
+    } else {
+      const int64_t o = (int64_t)row * p.ldc + col;
+      if (MODE == EPI_ACT_RES || MODE == EPI_ACT_DGELU) {
+        const bf16x4 a = *(const bf16x4*)(aux + (int64_t)row * p.ldaux + col);
+        if (MODE == EPI_ACT_RES) { v.x += (float)a[0]; v.y += (float)a[1]; v.z += (float)a[2]; v.w += (float)a[3]; }
+        else { v.x *= gelu_grad_f((float)a[0]); v.y *= gelu_grad_f((float)a[1]); v.z *= gelu_grad_f((float)a[2]); v.w *= gelu_grad_f((float)a[3]); }
+      }
+      bf16x4 c;
+      c[0] = (bf16)v.x; c[1] = (bf16)v.y; c[2] = (bf16)v.z; c[3] = (bf16)v.w;
+      *(bf16x4*)((bf16*)p.C + o) = c;
+      if (MODE == EPI_ACT_GELU) {
+        bf16x4 g;
+        g[0] = (bf16)gelu_f(v.x); g[1] = (bf16)gelu_f(v.y); g[2] = (bf16)gelu_f(v.z); g[3] = (bf16)gelu_f(v.w);
+        *(bf16x4*)((bf16*)p.C2 + o) = g;
+      }
+    }
+  } else {
+    const float e[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      if (col + t >= p.N) break;
+      float x = e[t];
+      if (MODE == EPI_PARTIAL) { p.partial[((int64_t)split * p.M + row) * p.N + col + t] = x; continue; }
+      if (bias) x += (float)bias[col + t];
+      if (MODE == EPI_F32) {
+        float* C = (float*)p.C + (int64_t)row * p.ldc + col + t;
+        *C = (p.beta != 0.0f) ? p.beta * *C + x : x;
+      } else {
+        const int64_t o = (int64_t)row * p.ldc + col + t;
+        if (MODE == EPI_ACT_RES) x += (float)aux[(int64_t)row * p.ldaux + col + t];
+        if (MODE == EPI_ACT_DGELU) x *= gelu_grad_f((float)aux[(int64_t)row * p.ldaux + col + t]);
+        ((bf16*)p.C)[o] = (bf16)x;
+        if (MODE == EPI_ACT_GELU) ((bf16*)p.C2)[o] = (bf16)gelu_f(x);
+      }
+    }
+  }
+}
+
+// whether 4-element accesses are aligned for everything this mode touches
+template <int MODE>
+__device__ __forceinline__ bool quad_aligned(const GemmDev& p) {
+  if (MODE == EPI_PARTIAL) return (p.N & 3) == 0;
+  bool ok = (p.ldc & 3) == 0 && ((uintptr_t)p.C & 15) == 0;
+  if (p.bias) ok = ok && ((uintptr_t)p.bias & 7) == 0;
+  if (MODE == EPI_ACT_RES || MODE == EPI_ACT_DGELU) ok = ok && (p.ldaux & 3) == 0 && ((uintptr_t)p.aux & 7) == 0;
+  if (MODE == EPI_ACT_GELU) ok = ok && ((uintptr_t)p.C2 & 7) == 0;
+  return ok;
+}
+
 // Writes the TI x TJ grid of 32x32 result tiles of one wave.  Register r of lane l of a tile is
-// row 8*(r/4) + 4*(l/32) + r%4, column l%32.
+// row 8*(r/4) + 4*(l/32) + r%4, column l%32: one store instruction covers 64 contiguous bytes of two
+// rows (measured faster than 8-byte pieces of 32 rows from transposed tiles).
 template <int MODE, int TI, int TJ>
 __device__ __forceinline__ void tile_epilogue(const GemmDev& p, const f32x16 (&acc)[TI][TJ], int rbase, int cbase, int lane, int split) {
   const bf16* bias = (const bf16*)p.bias;
@@ -102,10 +169,14 @@ struct OperandTile {
   // chunk's position along the non-contraction index is inside the matrix.
   struct Cursor {
     const bf16* ptr[NCH];
+    const bf16* safe;     // an always-readable address (start of the matrix) for masked-out chunks
     int koff[NCH];        // contraction offset of the chunk inside a k-tile
     bool ok[NCH];
+    bool edge;            // some chunk of this block lies outside the matrix along the non-contraction index
   };
   static __device__ __forceinline__ void init(Cursor& cu, const bf16* __restrict__ base, int64_t ld, int row0, int rext, int kbeg, int tid) {
+    cu.safe = base;
+    cu.edge = row0 + R > rext;
 #pragma unroll
     for (int i = 0; i < NCH; ++i) {
       const int c = tid + i * NT;
@@ -114,23 +185,28 @@ struct OperandTile {
       else      { cu.ok[i] = row0 + b < rext; cu.koff[i] = a; cu.ptr[i] = base + (int64_t)(kbeg + a) * ld + row0 + b; }
     }
   }
-  // global -> registers for the k-tile that starts at k0 (zero where out of range), then advance
+  // global -> registers for the k-tile that starts at k0, then advance.  The loads are unconditional
+  // (no branch, so the hardware load counter can be waited on exactly): a chunk outside the matrix or
+  // beyond kend reads the safe address instead and is zeroed when it is written to LDS.
   static __device__ __forceinline__ void load(uint4 (&reg)[NCH], Cursor& cu, int64_t ld, int k0, int kend) {
 #pragma unroll
     for (int i = 0; i < NCH; ++i) {
-      uint4 v = make_uint4(0, 0, 0, 0);
-      if (cu.ok[i] && k0 + cu.koff[i] < kend) v = *(const uint4*)cu.ptr[i];
-      reg[i] = v;
+      const bool ok = cu.ok[i] && k0 + cu.koff[i] < kend;
+      const bf16* q = ok ? cu.ptr[i] : cu.safe;
+      reg[i] = *(const uint4*)q;
       cu.ptr[i] += KMAJ ? (int64_t)BK : (int64_t)BK * ld;
     }
   }
-  // registers -> LDS
-  static __device__ __forceinline__ void store(const uint4 (&reg)[NCH], bf16* s, int tid) {
+  // registers -> LDS for the k-tile that started at k0 (chunks that were masked out become zeros)
+  static __device__ __forceinline__ void store(const uint4 (&reg)[NCH], bf16* s, int tid, const Cursor& cu, int k0, int kend) {
+    const bool mask = cu.edge || k0 + BK > kend;      // uniform over the block
 #pragma unroll
     for (int i = 0; i < NCH; ++i) {
       const int c = tid + i * NT;
       const int a = c / CPR, b = (c % CPR) * 8;
-      *(uint4*)(s + a * LD + b) = reg[i];
+      uint4 v = reg[i];
+      if (mask && !(cu.ok[i] && k0 + cu.koff[i] < kend)) v = make_uint4(0, 0, 0, 0);
+      *(uint4*)(s + a * LD + b) = v;
     }
   }
   // LDS -> MFMA operand: lane gets elements (row = rbase + lane%32, k = ks*16 + 8*(lane/32) + 0..7)
@@ -193,23 +269,23 @@ void gemm_bf16_mfma(GemmDev p) {
   typename TB::Cursor cb;
   TA::init(ca, (const bf16*)p.A, p.lda, m0, p.M, kbeg, tid);
   TB::init(cb, (const bf16*)p.B, p.ldb, n0, p.N, kbeg, tid);
-  uint4 ra[TA::NCH], rb[TB::NCH];
-  const int nk = (kend - kbeg + BK - 1) / BK;
-  TA::load(ra, ca, p.lda, kbeg, kend);
-  TB::load(rb, cb, p.ldb, kbeg, kend);
-  TA::store(ra, sA0, tid);
-  TB::store(rb, sB0, tid);
+  // Software pipeline with a prefetch distance of two k-tiles: tile t is fetched from global memory
+  // into register set t%2 during iteration t-2, moved to LDS buffer t%2 during iteration t-1 and
+  // consumed during iteration t, so a global load has two iterations of MFMA work to hide behind.
+  // The tile count is rounded up to even; a tile beyond the range loads nothing real and is all zeros.
+  uint4 ra0[TA::NCH], rb0[TB::NCH], ra1[TA::NCH], rb1[TB::NCH];
+  const int nk = ((kend - kbeg + BK - 1) / BK + 1) & ~1;
+  TA::load(ra0, ca, p.lda, kbeg, kend);
+  TB::load(rb0, cb, p.ldb, kbeg, kend);
+  TA::load(ra1, ca, p.lda, kbeg + BK, kend);
+  TB::load(rb1, cb, p.ldb, kbeg + BK, kend);
+  TA::store(ra0, sA0, tid, ca, kbeg, kend);
+  TB::store(rb0, sB0, tid, cb, kbeg, kend);
   __syncthreads();
 
-  for (int kt = 0; kt < nk; ++kt) {
-    const int cur = kt & 1;
-    const bool more = kt + 1 < nk;
+  auto compute = [&](int cur) {
     const bf16* sAc = sA0 + cur * TA::ELEMS;
     const bf16* sBc = sB0 + cur * TB::ELEMS;
-    if (more) {
-      TA::load(ra, ca, p.lda, kbeg + (kt + 1) * BK, kend);
-      TB::load(rb, cb, p.ldb, kbeg + (kt + 1) * BK, kend);
-    }
 #pragma unroll
     for (int ks = 0; ks < BK / 16; ++ks) {
       bf16x8 fa[TI], fb[TJ];
@@ -222,9 +298,24 @@ void gemm_bf16_mfma(GemmDev p) {
 #pragma unroll
         for (int j = 0; j < TJ; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
     }
-    if (more) {
-      TA::store(ra, sA0 + (cur ^ 1) * TA::ELEMS, tid);
-      TB::store(rb, sB0 + (cur ^ 1) * TB::ELEMS, tid);
+  };
+
+  for (int kt = 0; kt < nk; kt += 2) {
+    const int k0 = kbeg + kt * BK;
+    // even tile kt: in LDS buffer 0; register set 0 is free, set 1 holds tile kt+1
+    TA::load(ra0, ca, p.lda, k0 + 2 * BK, kend);
+    TB::load(rb0, cb, p.ldb, k0 + 2 * BK, kend);
+    compute(0);
+    TA::store(ra1, sA0 + TA::ELEMS, tid, ca, k0 + BK, kend);
+    TB::store(rb1, sB0 + TB::ELEMS, tid, cb, k0 + BK, kend);
+    __syncthreads();
+    // odd tile kt+1: in LDS buffer 1; register set 1 is free, set 0 holds tile kt+2
+    TA::load(ra1, ca, p.lda, k0 + 3 * BK, kend);
+    TB::load(rb1, cb, p.ldb, k0 + 3 * BK, kend);
+    compute(1);
+    if (kt + 2 < nk) {
+      TA::store(ra0, sA0, tid, ca, k0 + 2 * BK, kend);
+      TB::store(rb0, sB0, tid, cb, k0 + 2 * BK, kend);
     }
     __syncthreads();
   }
@@ -240,14 +331,34 @@ void gemm_bf16_mfma(GemmDev p) {
   else tile_epilogue<EPI_ACT_DGELU, TI, TJ>(p, acc, rbase, cbase, lane, 0);
 }
 
-// sums the split-K partials in split order and applies the epilogue
+// sums the split-K partials in split order and applies the epilogue (four columns per thread)
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(GemmDev p, int splits) {
-  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
   const int64_t mn = (int64_t)p.M * p.N;
-  if (idx >= mn) return;
-  float s = 0.f;
-  for (int z = 0; z < splits; ++z) s += p.partial[z * mn + idx];
-  epilogue_store<bf16>(p, (int)(idx / p.N), (int)(idx % p.N), s);
+  if ((p.N & 3) == 0) {
+    const int64_t idx = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
+    if (idx >= mn) return;
+    float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int z = 0; z < splits; ++z) {
+      const float4 t = *(const float4*)(p.partial + z * mn + idx);
+      s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
+    }
+    const int row = (int)(idx / p.N), col = (int)(idx % p.N);
+    GemmDev q = p;
+    q.partial = nullptr;
+    if (p.c_f32) store_quad<EPI_F32>(q, row, col, s, quad_aligned<EPI_F32>(q), 0);
+    else if (p.epi == 0) store_quad<EPI_ACT>(q, row, col, s, quad_aligned<EPI_ACT>(q), 0);
+    else if (p.epi == 1) store_quad<EPI_ACT_RES>(q, row, col, s, quad_aligned<EPI_ACT_RES>(q), 0);
+    else if (p.epi == 2) store_quad<EPI_ACT_GELU>(q, row, col, s, quad_aligned<EPI_ACT_GELU>(q), 0);
+    else store_quad<EPI_ACT_DGELU>(q, row, col, s, quad_aligned<EPI_ACT_DGELU>(q), 0);
+  } else {
+    for (int t = 0; t < 4; ++t) {
+      const int64_t idx = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4 + t;
+      if (idx >= mn) return;
+      float s = 0.f;
+      for (int z = 0; z < splits; ++z) s += p.partial[z * mn + idx];
+      epilogue_store<bf16>(p, (int)(idx / p.N), (int)(idx % p.N), s);
+    }
+  }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -399,7 +510,7 @@ hs_status launch_gemm(hs_ctx* ctx, const GemmArgs& g, hipStream_t s) {
     if (e != hipSuccess) return hs_fail(ctx, HS_ERR_HIP, std::string("gemm launch: ") + hipGetErrorString(e));
     if (splits > 1) {
       const int64_t mn = (int64_t)g.M * g.N;
-      hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((mn + 255) / 256)), dim3(256), 0, s, p, splits);
+      hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((mn + 1023) / 1024)), dim3(256), 0, s, p, splits);
     }
   }
   hipError_t e = hipGetLastError();
