@@ -69,7 +69,9 @@ HeadWs carve_head(const hs_model_cfg& c, int M, void* base) {
 }
 
 struct BwdWs {
-  void *dxa, *dxb, *dy, *dh, *dctx, *dqkv, *ln_part, *cs_part, *emb, *gemm_ws;
+  // dy2, dy1, dh and dqkv exist twice (by layer parity): the weight-gradient GEMMs that read them run
+  // on a second stream and may still be in flight while the next layer produces its own
+  void *dxa, *dxb, *dy2[2], *dy1[2], *dh[2], *dqkv[2], *dctx, *ln_part, *cs_part, *emb, *gemm_ws, *gemm_ws_side;
   float* dvec;
   size_t total, gemm_ws_bytes;
 };
@@ -77,16 +79,31 @@ BwdWs carve_bwd(const hs_model_cfg& c, int B, int L, void* base) {
   const size_t T = (size_t)B * L, H = c.hidden, F = c.ffn, es = esize(c.compute);
   Carver cv(base);
   BwdWs w;
-  w.dxa = cv.take(T * H * es); w.dxb = cv.take(T * H * es); w.dy = cv.take(T * H * es);
-  w.dh = cv.take(T * F * es); w.dctx = cv.take(T * H * es); w.dqkv = cv.take(T * 3 * H * es);
+  w.dxa = cv.take(T * H * es); w.dxb = cv.take(T * H * es); w.dctx = cv.take(T * H * es);
+  for (int k = 0; k < 2; ++k) {
+    w.dy2[k] = cv.take(T * H * es); w.dy1[k] = cv.take(T * H * es);
+    w.dh[k] = cv.take(T * F * es); w.dqkv[k] = cv.take(T * 3 * H * es);
+  }
   w.dvec = (float*)cv.take((size_t)B * c.n_heads * L * sizeof(float));
   w.ln_part = cv.take(layernorm_bwd_scratch((int)T, (int)H));
   w.cs_part = cv.take(colsum_scratch((int)T, (int)std::max(F, 3 * H)));
   w.emb = cv.take(embed_bwd_scratch((int)T, (int)H));
   w.gemm_ws_bytes = gemm_scratch_bytes(c);
   w.gemm_ws = cv.take(w.gemm_ws_bytes);
+  w.gemm_ws_side = cv.take(w.gemm_ws_bytes);
   w.total = cv.off;
   return w;
+}
+
+// second stream + ordering events of a context, created on first use
+hs_status ensure_side_stream(hs_ctx* ctx, size_t n_events) {
+  if (!ctx->side) HS_HIP_CHECK(ctx, hipStreamCreateWithFlags(&ctx->side, hipStreamNonBlocking));
+  while (ctx->events.size() < n_events) {
+    hipEvent_t e;
+    HS_HIP_CHECK(ctx, hipEventCreateWithFlags(&e, hipEventDisableTiming));
+    ctx->events.push_back(e);
+  }
+  return HS_OK;
 }
 
 bool shape_ok(hs_ctx* ctx, int B, int L, std::string* why) {
@@ -252,55 +269,79 @@ hs_status hs_encoder_bwd(hs_ctx* ctx, const void* w, const void* acts, const int
   const float beta = accumulate ? 1.f : 0.f;
   auto run_gemm = [&](GemmArgs& a) { a.ws = ws.gemm_ws; a.ws_bytes = ws.gemm_ws_bytes; return launch_gemm(ctx, a, s); };
 
+  // The weight-gradient GEMMs only consume; they run on a second stream so that their ramp-up and tail
+  // overlap the activation-gradient chain.  Per layer: four "operand ready" events (main -> side) and
+  // one "layer done" event (side -> main, waited on before the operand buffers of that parity are
+  // reused two layers later and at the end of the call).  With per-launch timing enabled everything
+  // stays on the caller's stream so that the timings do not overlap.
+  const bool overlap = ctx->prof == nullptr;
+  const int NL = c.n_layers;
+  if (overlap) HS_TRY(ensure_side_stream(ctx, (size_t)5 * NL));
+  hipStream_t sd = overlap ? ctx->side : s;
+  auto ev = [&](int layer, int k) { return ctx->events[(size_t)layer * 5 + k]; };
+  auto hand_over = [&](int layer, int k) -> hs_status {      // main has produced operand k of this layer
+    if (!overlap) return HS_OK;
+    HS_HIP_CHECK(ctx, hipEventRecord(ev(layer, k), s));
+    HS_HIP_CHECK(ctx, hipStreamWaitEvent(sd, ev(layer, k), 0));
+    return HS_OK;
+  };
+  auto side_gemm = [&](GemmArgs& a) { a.ws = ws.gemm_ws_side; a.ws_bytes = ws.gemm_ws_bytes; a.c_f32 = 1; a.beta = beta; return launch_gemm(ctx, a, sd); };
+
   const void* dcur = d_hidden;
-  for (int i = c.n_layers - 1; i >= 0; --i) {
+  for (int i = NL - 1; i >= 0; --i) {
     const LayerOff& lo = o.layer[i];
     LayerActs& la = a.layer[i];
     const void* x_in = (i == 0) ? a.x0 : a.layer[i - 1].x2;
+    const int par = i & 1;
+    void *dy2 = ws.dy2[par], *dy1 = ws.dy1[par], *dh = ws.dh[par], *dqkv = ws.dqkv[par];
+    if (overlap && i + 2 < NL) HS_HIP_CHECK(ctx, hipStreamWaitEvent(s, ev(i + 2, 4), 0));   // buffers of this parity are free again
     // LN2 backward: dy2, d gain/bias, and colsum(dy2) = d b2
-    HS_TRY(launch_layernorm_bwd(ctx, dt, dcur, la.y2, la.st2, W(ctx, w, lo.ln2_g), ws.dy, g + lo.ln2_g, g + lo.ln2_b, g + lo.ffn2_b, beta,
+    HS_TRY(launch_layernorm_bwd(ctx, dt, dcur, la.y2, la.st2, W(ctx, w, lo.ln2_g), dy2, g + lo.ln2_g, g + lo.ln2_b, g + lo.ffn2_b, beta,
                                 T, H, ws.ln_part, s));
+    HS_TRY(hand_over(i, 0));
     // dW2 [H,F] = dy2^T h
-    GemmArgs ga = gemm_args(dt, 0, 0, H, F, T, ws.dy, H, la.h, F, g + lo.ffn2_w, F);
-    ga.c_f32 = 1; ga.beta = beta;
-    HS_TRY(run_gemm(ga));
+    GemmArgs ga = gemm_args(dt, 0, 0, H, F, T, dy2, H, la.h, F, g + lo.ffn2_w, F);
+    HS_TRY(side_gemm(ga));
     // dhpre [T,F] = (dy2 W2) * GELU'(hpre)
-    ga = gemm_args(dt, 1, 0, T, F, H, ws.dy, H, W(ctx, w, lo.ffn2_w), F, ws.dh, F);
+    ga = gemm_args(dt, 1, 0, T, F, H, dy2, H, W(ctx, w, lo.ffn2_w), F, dh, F);
     ga.epi = 3; ga.aux = la.hpre; ga.ldaux = F;
     HS_TRY(run_gemm(ga));
-    HS_TRY(launch_colsum(ctx, dt, ws.dh, F, T, F, g + lo.ffn1_b, beta, ws.cs_part, s));
+    HS_TRY(launch_colsum(ctx, dt, dh, F, T, F, g + lo.ffn1_b, beta, ws.cs_part, s));
+    HS_TRY(hand_over(i, 1));
     // dW1 [F,H] = dhpre^T x1
-    ga = gemm_args(dt, 0, 0, F, H, T, ws.dh, F, la.x1, H, g + lo.ffn1_w, H);
-    ga.c_f32 = 1; ga.beta = beta;
-    HS_TRY(run_gemm(ga));
+    ga = gemm_args(dt, 0, 0, F, H, T, dh, F, la.x1, H, g + lo.ffn1_w, H);
+    HS_TRY(side_gemm(ga));
     // dx1 [T,H] = dhpre W1 + dy2
-    ga = gemm_args(dt, 1, 0, T, H, F, ws.dh, F, W(ctx, w, lo.ffn1_w), H, ws.dxa, H);
-    ga.epi = 1; ga.aux = ws.dy; ga.ldaux = H;
+    ga = gemm_args(dt, 1, 0, T, H, F, dh, F, W(ctx, w, lo.ffn1_w), H, ws.dxa, H);
+    ga.epi = 1; ga.aux = dy2; ga.ldaux = H;
     HS_TRY(run_gemm(ga));
     // LN1 backward: dy1, d gain/bias, colsum(dy1) = d bo
-    HS_TRY(launch_layernorm_bwd(ctx, dt, ws.dxa, la.y1, la.st1, W(ctx, w, lo.ln1_g), ws.dy, g + lo.ln1_g, g + lo.ln1_b, g + lo.o_b, beta, T,
+    HS_TRY(launch_layernorm_bwd(ctx, dt, ws.dxa, la.y1, la.st1, W(ctx, w, lo.ln1_g), dy1, g + lo.ln1_g, g + lo.ln1_b, g + lo.o_b, beta, T,
                                 H, ws.ln_part, s));
+    HS_TRY(hand_over(i, 2));
     // dWo [H,H] = dy1^T ctx ; dctx = dy1 Wo
-    ga = gemm_args(dt, 0, 0, H, H, T, ws.dy, H, la.ctx, H, g + lo.o_w, H);
-    ga.c_f32 = 1; ga.beta = beta;
+    ga = gemm_args(dt, 0, 0, H, H, T, dy1, H, la.ctx, H, g + lo.o_w, H);
+    HS_TRY(side_gemm(ga));
+    ga = gemm_args(dt, 1, 0, T, H, H, dy1, H, W(ctx, w, lo.o_w), H, ws.dctx, H);
     HS_TRY(run_gemm(ga));
-    ga = gemm_args(dt, 1, 0, T, H, H, ws.dy, H, W(ctx, w, lo.o_w), H, ws.dctx, H);
-    HS_TRY(run_gemm(ga));
-    HS_TRY(launch_attention_bwd(ctx, dt, la.qkv, la.ctx, la.lse, ws.dctx, lens, B, L, c.n_heads, ws.dqkv, ws.dvec, s));
-    HS_TRY(launch_colsum(ctx, dt, ws.dqkv, 3 * H, T, 3 * H, g + lo.qkv_b, beta, ws.cs_part, s));
+    HS_TRY(launch_attention_bwd(ctx, dt, la.qkv, la.ctx, la.lse, ws.dctx, lens, B, L, c.n_heads, dqkv, ws.dvec, s));
+    HS_TRY(launch_colsum(ctx, dt, dqkv, 3 * H, T, 3 * H, g + lo.qkv_b, beta, ws.cs_part, s));
+    HS_TRY(hand_over(i, 3));
     // dWqkv [3H,H] = dqkv^T x_in ; dx_in = dqkv Wqkv + dy1
-    ga = gemm_args(dt, 0, 0, 3 * H, H, T, ws.dqkv, 3 * H, x_in, H, g + lo.qkv_w, H);
-    ga.c_f32 = 1; ga.beta = beta;
-    HS_TRY(run_gemm(ga));
-    ga = gemm_args(dt, 1, 0, T, H, 3 * H, ws.dqkv, 3 * H, W(ctx, w, lo.qkv_w), H, ws.dxb, H);
-    ga.epi = 1; ga.aux = ws.dy; ga.ldaux = H;
+    ga = gemm_args(dt, 0, 0, 3 * H, H, T, dqkv, 3 * H, x_in, H, g + lo.qkv_w, H);
+    HS_TRY(side_gemm(ga));
+    if (overlap) HS_HIP_CHECK(ctx, hipEventRecord(ev(i, 4), sd));
+    ga = gemm_args(dt, 1, 0, T, H, 3 * H, dqkv, 3 * H, W(ctx, w, lo.qkv_w), H, ws.dxb, H);
+    ga.epi = 1; ga.aux = dy1; ga.ldaux = H;
     HS_TRY(run_gemm(ga));
     dcur = ws.dxb;
   }
   // embedding LayerNorm, then the two embedding tables
-  HS_TRY(launch_layernorm_bwd(ctx, dt, dcur, a.e_pre, a.emb_stats, W(ctx, w, o.emb_ln_g), ws.dy, g + o.emb_ln_g, g + o.emb_ln_b, nullptr, beta,
-                              T, H, ws.ln_part, s));
-  HS_TRY(launch_embed_bwd(ctx, dt, ws.dy, ids, B, L, H, c.vocab, c.max_pos, g + o.emb_word, g + o.emb_pos, beta, ws.emb, s));
+  HS_TRY(launch_layernorm_bwd(ctx, dt, dcur, a.e_pre, a.emb_stats, W(ctx, w, o.emb_ln_g), ws.dxa, g + o.emb_ln_g,
+                              g + o.emb_ln_b, nullptr, beta, T, H, ws.ln_part, s));
+  HS_TRY(launch_embed_bwd(ctx, dt, ws.dxa, ids, B, L, H, c.vocab, c.max_pos, g + o.emb_word, g + o.emb_pos, beta, ws.emb, s));
+  // everything the second stream did is ordered before whatever the caller enqueues next
+  if (overlap) HS_HIP_CHECK(ctx, hipStreamWaitEvent(s, ev(0, 4), 0));
   return HS_OK;
 }
 

@@ -87,6 +87,10 @@ struct hs_ctx {
   ModelOff off;
   std::string err;
   Profiler* prof;  // null unless enabled
+  // a second stream on which the weight-gradient GEMMs of the backward pass run beside the
+  // activation-gradient chain, with the events that order the two (created on first use)
+  hipStream_t side;
+  std::vector<hipEvent_t> events;
 };
 
 hs_status hs_fail(hs_ctx* ctx, hs_status st, const std::string& msg);  // records msg, returns st

@@ -116,6 +116,7 @@ hs_status hs_ctx_create(const hs_model_cfg* cfg, hs_ctx** out) {
   c->cfg = *cfg;
   hs_model_offsets(*cfg, &c->off);
   c->prof = nullptr;
+  c->side = nullptr;
   *out = c;
   return HS_OK;
 }
@@ -123,6 +124,8 @@ hs_status hs_ctx_create(const hs_model_cfg* cfg, hs_ctx** out) {
 hs_status hs_ctx_destroy(hs_ctx* ctx) {
   if (!ctx) return HS_ERR_INVALID_ARG;
   delete ctx->prof;
+  for (hipEvent_t e : ctx->events) (void)hipEventDestroy(e);
+  if (ctx->side) (void)hipStreamDestroy(ctx->side);
   delete ctx;
   return HS_OK;
 }

@@ -253,7 +253,17 @@ void gemm_bf16_mfma(GemmDev p) {
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WGN, wn = wave % WGN;
-  const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+  // Tile order.  Workgroups are handed to the 8 XCDs round-robin by linear id, and each XCD has its own
+  // L2: give every XCD a contiguous range of tiles, and walk the tiles in groups of 8 tile rows so that
+  // the tiles in flight on one XCD share operand panels.
+  int b = blockIdx.y * gridDim.x + blockIdx.x;
+  const int nbx = gridDim.x, nby = gridDim.y, nb = nbx * nby;
+  if ((nb & 7) == 0) b = (b & 7) * (nb >> 3) + (b >> 3);
+  constexpr int GM = 8;
+  const int group = b / (GM * nbx), first_m = group * GM;
+  const int gm = min(GM, nby - first_m);
+  const int in_group = b - group * GM * nbx;
+  const int m0 = (first_m + in_group % gm) * BM, n0 = (in_group / gm) * BN;
   const int kbeg = blockIdx.z * p.k_per_split;
   const int kend = min(p.K, kbeg + p.k_per_split);
 
