@@ -71,7 +71,7 @@ HeadWs carve_head(const hs_model_cfg& c, int M, void* base) {
 struct BwdWs {
   // dy2, dy1, dh and dqkv exist twice (by layer parity): the weight-gradient GEMMs that read them run
   // on a second stream and may still be in flight while the next layer produces its own
-  void *dxa, *dxb, *dy2[2], *dy1[2], *dh[2], *dqkv[2], *dctx, *ln_part, *cs_part, *emb, *gemm_ws, *gemm_ws_side;
+  void *dxa, *dxb, *dy2[2], *dy1[2], *dh[2], *dqkv[2], *dctx, *ln_part, *ln_part2[2], *ln_part1[2], *cs_part, *emb, *gemm_ws, *gemm_ws_side;
   float* dvec;
   size_t total, gemm_ws_bytes;
 };
@@ -86,6 +86,10 @@ BwdWs carve_bwd(const hs_model_cfg& c, int B, int L, void* base) {
   }
   w.dvec = (float*)cv.take((size_t)B * c.n_heads * L * sizeof(float));
   w.ln_part = cv.take(layernorm_bwd_scratch((int)T, (int)H));
+  for (int k = 0; k < 2; ++k) {
+    w.ln_part2[k] = cv.take(layernorm_bwd_scratch((int)T, (int)H));
+    w.ln_part1[k] = cv.take(layernorm_bwd_scratch((int)T, (int)H));
+  }
   w.cs_part = cv.take(colsum_scratch((int)T, (int)std::max(F, 3 * H)));
   w.emb = cv.take(embed_bwd_scratch((int)T, (int)H));
   w.gemm_ws_bytes = gemm_scratch_bytes(c);
@@ -295,10 +299,10 @@ hs_status hs_encoder_bwd(hs_ctx* ctx, const void* w, const void* acts, const int
     const int par = i & 1;
     void *dy2 = ws.dy2[par], *dy1 = ws.dy1[par], *dh = ws.dh[par], *dqkv = ws.dqkv[par];
     if (overlap && i + 2 < NL) HS_HIP_CHECK(ctx, hipStreamWaitEvent(s, ev(i + 2, 4), 0));   // buffers of this parity are free again
-    // LN2 backward: dy2, d gain/bias, and colsum(dy2) = d b2
-    HS_TRY(launch_layernorm_bwd(ctx, dt, dcur, la.y2, la.st2, W(ctx, w, lo.ln2_g), dy2, g + lo.ln2_g, g + lo.ln2_b, g + lo.ffn2_b, beta,
-                                T, H, ws.ln_part, s));
+    // LN2 backward: dy2 on the main chain; d gain/bias and colsum(dy2) = d b2 from its partials beside it
+    HS_TRY(launch_layernorm_bwd_rows(ctx, dt, dcur, la.y2, la.st2, W(ctx, w, lo.ln2_g), dy2, T, H, ws.ln_part2[par], s));
     HS_TRY(hand_over(i, 0));
+    HS_TRY(launch_layernorm_bwd_cols(ctx, ws.ln_part2[par], g + lo.ln2_g, g + lo.ln2_b, g + lo.ffn2_b, beta, T, H, sd));
     // dW2 [H,F] = dy2^T h
     GemmArgs ga = gemm_args(dt, 0, 0, H, F, T, dy2, H, la.h, F, g + lo.ffn2_w, F);
     HS_TRY(side_gemm(ga));
@@ -306,8 +310,8 @@ hs_status hs_encoder_bwd(hs_ctx* ctx, const void* w, const void* acts, const int
     ga = gemm_args(dt, 1, 0, T, F, H, dy2, H, W(ctx, w, lo.ffn2_w), F, dh, F);
     ga.epi = 3; ga.aux = la.hpre; ga.ldaux = F;
     HS_TRY(run_gemm(ga));
-    HS_TRY(launch_colsum(ctx, dt, dh, F, T, F, g + lo.ffn1_b, beta, ws.cs_part, s));
     HS_TRY(hand_over(i, 1));
+    HS_TRY(launch_colsum(ctx, dt, dh, F, T, F, g + lo.ffn1_b, beta, ws.cs_part, sd));
     // dW1 [F,H] = dhpre^T x1
     ga = gemm_args(dt, 0, 0, F, H, T, dh, F, la.x1, H, g + lo.ffn1_w, H);
     HS_TRY(side_gemm(ga));
@@ -316,17 +320,17 @@ hs_status hs_encoder_bwd(hs_ctx* ctx, const void* w, const void* acts, const int
     ga.epi = 1; ga.aux = dy2; ga.ldaux = H;
     HS_TRY(run_gemm(ga));
     // LN1 backward: dy1, d gain/bias, colsum(dy1) = d bo
-    HS_TRY(launch_layernorm_bwd(ctx, dt, ws.dxa, la.y1, la.st1, W(ctx, w, lo.ln1_g), dy1, g + lo.ln1_g, g + lo.ln1_b, g + lo.o_b, beta, T,
-                                H, ws.ln_part, s));
+    HS_TRY(launch_layernorm_bwd_rows(ctx, dt, ws.dxa, la.y1, la.st1, W(ctx, w, lo.ln1_g), dy1, T, H, ws.ln_part1[par], s));
     HS_TRY(hand_over(i, 2));
+    HS_TRY(launch_layernorm_bwd_cols(ctx, ws.ln_part1[par], g + lo.ln1_g, g + lo.ln1_b, g + lo.o_b, beta, T, H, sd));
     // dWo [H,H] = dy1^T ctx ; dctx = dy1 Wo
     ga = gemm_args(dt, 0, 0, H, H, T, dy1, H, la.ctx, H, g + lo.o_w, H);
     HS_TRY(side_gemm(ga));
     ga = gemm_args(dt, 1, 0, T, H, H, dy1, H, W(ctx, w, lo.o_w), H, ws.dctx, H);
     HS_TRY(run_gemm(ga));
     HS_TRY(launch_attention_bwd(ctx, dt, la.qkv, la.ctx, la.lse, ws.dctx, lens, B, L, c.n_heads, dqkv, ws.dvec, s));
-    HS_TRY(launch_colsum(ctx, dt, dqkv, 3 * H, T, 3 * H, g + lo.qkv_b, beta, ws.cs_part, s));
     HS_TRY(hand_over(i, 3));
+    HS_TRY(launch_colsum(ctx, dt, dqkv, 3 * H, T, 3 * H, g + lo.qkv_b, beta, ws.cs_part, sd));
     // dWqkv [3H,H] = dqkv^T x_in ; dx_in = dqkv Wqkv + dy1
     ga = gemm_args(dt, 0, 0, 3 * H, H, T, dqkv, 3 * H, x_in, H, g + lo.qkv_w, H);
     HS_TRY(side_gemm(ga));

@@ -124,6 +124,10 @@ size_t layernorm_bwd_scratch(int R, int H);
 hs_status launch_layernorm_bwd(hs_ctx* ctx, int dtype, const void* dy, const void* x, const float* stats, const void* gain,
                                void* dx, float* d_gain, float* d_bias, float* d_colsum, float beta, int R, int H,
                                void* partials, hipStream_t s);
+hs_status launch_layernorm_bwd_rows(hs_ctx* ctx, int dtype, const void* dy, const void* x, const float* stats, const void* gain, void* dx,
+                                    int R, int H, void* partials, hipStream_t s);
+hs_status launch_layernorm_bwd_cols(hs_ctx* ctx, const void* partials, float* d_gain, float* d_bias, float* d_colsum, float beta, int R, int H,
+                                    hipStream_t s);
 hs_status launch_embed_ln_fwd(hs_ctx* ctx, int dtype, const void* word, const void* pos, const void* gain, const void* bias,
                               const int32_t* ids, void* e_pre, void* x0, float* stats, int B, int L, int H, int V, float eps,
                               hipStream_t s);

@@ -500,20 +500,32 @@ hs_status launch_layernorm_fwd(hs_ctx* ctx, int dtype, const void* x, const void
 static int ln_bwd_blocks(int R) { int nb = (R + 7) / 8; return nb < 1 ? 1 : (nb > 768 ? 768 : nb); }
 size_t layernorm_bwd_scratch(int R, int H) { return align_up((size_t)ln_bwd_blocks(R) * 3 * H * sizeof(float), 256); }
 
-hs_status launch_layernorm_bwd(hs_ctx* ctx, int dtype, const void* dy, const void* x, const float* stats, const void* gain, void* dx,
-                               float* d_gain, float* d_bias, float* d_colsum, float beta, int R, int H, void* partials, hipStream_t s) {
+// main kernel: dx and the per-block partial column sums
+hs_status launch_layernorm_bwd_rows(hs_ctx* ctx, int dtype, const void* dy, const void* x, const float* stats, const void* gain, void* dx,
+                                    int R, int H, void* partials, hipStream_t s) {
   if (R <= 0) return HS_OK;
   const int nb = ln_bwd_blocks(R);
   KScope scope(prof_of(ctx), KC_LN_BWD, 14.0 * R * H, 3.0 * R * H * esize(dtype), s);
   if (dtype == HS_BF16) hipLaunchKernelGGL(ln_bwd_kernel<bf16>, dim3(nb), dim3(256), 0, s, (const bf16*)dy, (const bf16*)x, stats, (const bf16*)gain, (bf16*)dx, (float*)partials, R, H);
   else hipLaunchKernelGGL(ln_bwd_kernel<float>, dim3(nb), dim3(256), 0, s, (const float*)dy, (const float*)x, stats, (const float*)gain, (float*)dx, (float*)partials, R, H);
   LAUNCH_CHECK(ctx, "layernorm_bwd");
-  if (d_gain || d_bias || d_colsum) {
-    hipLaunchKernelGGL(sum_partials_kernel, dim3((H + 63) / 64, 3), dim3(256), 0, s, (const float*)partials, nb, (int64_t)3 * H, (int64_t)H, H,
-                       d_gain, d_bias, d_colsum, beta);
-    LAUNCH_CHECK(ctx, "layernorm_bwd finalize");
-  }
   return HS_OK;
+}
+// fixed-order sum of the partials into the three gradient vectors (may run on another stream)
+hs_status launch_layernorm_bwd_cols(hs_ctx* ctx, const void* partials, float* d_gain, float* d_bias, float* d_colsum, float beta, int R, int H,
+                                    hipStream_t s) {
+  if (R <= 0 || !(d_gain || d_bias || d_colsum)) return HS_OK;
+  KScope scope(prof_of(ctx), KC_LN_BWD, 0.0, 0.0, s);
+  hipLaunchKernelGGL(sum_partials_kernel, dim3((H + 63) / 64, 3), dim3(256), 0, s, (const float*)partials, ln_bwd_blocks(R), (int64_t)3 * H,
+                     (int64_t)H, H, d_gain, d_bias, d_colsum, beta);
+  LAUNCH_CHECK(ctx, "layernorm_bwd finalize");
+  return HS_OK;
+}
+hs_status launch_layernorm_bwd(hs_ctx* ctx, int dtype, const void* dy, const void* x, const float* stats, const void* gain, void* dx,
+                               float* d_gain, float* d_bias, float* d_colsum, float beta, int R, int H, void* partials, hipStream_t s) {
+  hs_status st = launch_layernorm_bwd_rows(ctx, dtype, dy, x, stats, gain, dx, R, H, partials, s);
+  if (st != HS_OK) return st;
+  return launch_layernorm_bwd_cols(ctx, partials, d_gain, d_bias, d_colsum, beta, R, H, s);
 }
 
 hs_status launch_embed_ln_fwd(hs_ctx* ctx, int dtype, const void* word, const void* pos, const void* gain, const void* bias,
