@@ -40,6 +40,21 @@ __device__ __forceinline__ float gelu_grad_f(float x) {
   return 0.5f * (1.0f + erff(x * 0.70710678118654752440f)) + x * 0.39894228040143267794f * __expf(-0.5f * x * x);
 }
 
+// Cheaper forms for the bf16 GEMM epilogues: erf by the rational-exponential fit 7.1.26 of Abramowitz &
+// Stegun (absolute error below 1.5e-7, far under bf16 resolution).  The Gaussian e^{-x^2/2} it needs is
+// the same one GELU' needs, so both cost one exponential and one reciprocal.
+__device__ __forceinline__ void normal_cdf_pdf(float x, float& cdf, float& pdf) {
+  const float ax = fabsf(x) * 0.70710678118654752440f;
+  const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, ax, 1.0f));
+  const float e = __expf(-ax * ax);
+  const float poly = t * (0.254829592f + t * (-0.284496736f + t * (1.421413741f + t * (-1.453152027f + t * 1.061405429f))));
+  const float erf_abs = fmaf(-poly, e, 1.0f);
+  cdf = 0.5f * (1.0f + copysignf(erf_abs, x));
+  pdf = 0.39894228040143267794f * e;
+}
+__device__ __forceinline__ float gelu_fast(float x) { float c, d; normal_cdf_pdf(x, c, d); return x * c; }
+__device__ __forceinline__ float gelu_grad_fast(float x) { float c, d; normal_cdf_pdf(x, c, d); return fmaf(x, d, c); }
+
 // ---- kernel classes for the optional per-launch timing ---------------------------------
 enum KClass {
   KC_GEMM_FWD = 0,   // A k-major, B k-major   (y = x W^T)

@@ -62,14 +62,14 @@ __device__ __forceinline__ void store_quad(const GemmDev& p, int row, int col, f
       if (MODE == EPI_ACT_RES || MODE == EPI_ACT_DGELU) {
         const bf16x4 a = *(const bf16x4*)(aux + (int64_t)row * p.ldaux + col);
         if (MODE == EPI_ACT_RES) { v.x += (float)a[0]; v.y += (float)a[1]; v.z += (float)a[2]; v.w += (float)a[3]; }
-        else { v.x *= gelu_grad_f((float)a[0]); v.y *= gelu_grad_f((float)a[1]); v.z *= gelu_grad_f((float)a[2]); v.w *= gelu_grad_f((float)a[3]); }
+        else { v.x *= gelu_grad_fast((float)a[0]); v.y *= gelu_grad_fast((float)a[1]); v.z *= gelu_grad_fast((float)a[2]); v.w *= gelu_grad_fast((float)a[3]); }
       }
       bf16x4 c;
       c[0] = (bf16)v.x; c[1] = (bf16)v.y; c[2] = (bf16)v.z; c[3] = (bf16)v.w;
       *(bf16x4*)((bf16*)p.C + o) = c;
       if (MODE == EPI_ACT_GELU) {
         bf16x4 g;
-        g[0] = (bf16)gelu_f(v.x); g[1] = (bf16)gelu_f(v.y); g[2] = (bf16)gelu_f(v.z); g[3] = (bf16)gelu_f(v.w);
+        g[0] = (bf16)gelu_fast(v.x); g[1] = (bf16)gelu_fast(v.y); g[2] = (bf16)gelu_fast(v.z); g[3] = (bf16)gelu_fast(v.w);
         *(bf16x4*)((bf16*)p.C2 + o) = g;
       }
     }
@@ -87,9 +87,9 @@ __device__ __forceinline__ void store_quad(const GemmDev& p, int row, int col, f
       } else {
         const int64_t o = (int64_t)row * p.ldc + col + t;
         if (MODE == EPI_ACT_RES) x += (float)aux[(int64_t)row * p.ldaux + col + t];
-        if (MODE == EPI_ACT_DGELU) x *= gelu_grad_f((float)aux[(int64_t)row * p.ldaux + col + t]);
+        if (MODE == EPI_ACT_DGELU) x *= gelu_grad_fast((float)aux[(int64_t)row * p.ldaux + col + t]);
         ((bf16*)p.C)[o] = (bf16)x;
-        if (MODE == EPI_ACT_GELU) ((bf16*)p.C2)[o] = (bf16)gelu_f(x);
+        if (MODE == EPI_ACT_GELU) ((bf16*)p.C2)[o] = (bf16)gelu_fast(x);
       }
     }
   }
@@ -141,15 +141,119 @@ __device__ __forceinline__ void tile_epilogue(const GemmDev& p, const f32x16 (&a
             *C = (p.beta != 0.0f) ? p.beta * *C + v : v;
           } else {
             if (MODE == EPI_ACT_RES) v += (float)((const bf16*)p.aux)[oa + j * 32];
-            if (MODE == EPI_ACT_DGELU) v *= gelu_grad_f((float)((const bf16*)p.aux)[oa + j * 32]);
+            if (MODE == EPI_ACT_DGELU) v *= gelu_grad_fast((float)((const bf16*)p.aux)[oa + j * 32]);
             ((bf16*)p.C)[oc + j * 32] = (bf16)v;
-            if (MODE == EPI_ACT_GELU) ((bf16*)p.C2)[oc + j * 32] = (bf16)gelu_f(v);
+            if (MODE == EPI_ACT_GELU) ((bf16*)p.C2)[oc + j * 32] = (bf16)gelu_fast(v);
           }
         }
       }
     }
     // keep the scheduler from overlapping the loads and address arithmetic of different tile rows:
     // that would cost more registers than the main loop needs and lower the occupancy
+    __builtin_amdgcn_sched_barrier(0);
+  }
+}
+
+// Eight consecutive output columns of one row (as two float4): bias, epilogue, store.  `vec` says
+// that all eight columns exist and every pointer involved is aligned for 16-byte accesses.
+template <int MODE>
+__device__ __forceinline__ void store_octet(const GemmDev& p, int row, int col, float4 lo, float4 hi, bool vec, int split) {
+  const bf16* bias = (const bf16*)p.bias;
+  const bf16* aux = (const bf16*)p.aux;
+  float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+  if (vec) {
+    if (MODE == EPI_PARTIAL) {
+      float* dst = p.partial + ((int64_t)split * p.M + row) * p.N + col;
+      *(float4*)dst = lo; *(float4*)(dst + 4) = hi;
+      return;
+    }
+    if (bias) {
+      const bf16x8 b = *(const bf16x8*)(bias + col);
+#pragma unroll
+      for (int t = 0; t < 8; ++t) v[t] += (float)b[t];
+    }
+    if (MODE == EPI_F32) {
+      float* C = (float*)p.C + (int64_t)row * p.ldc + col;
+      if (p.beta != 0.0f) {
+        const float4 o0 = *(const float4*)C, o1 = *(const float4*)(C + 4);
+        v[0] += p.beta * o0.x; v[1] += p.beta * o0.y; v[2] += p.beta * o0.z; v[3] += p.beta * o0.w;
+        v[4] += p.beta * o1.x; v[5] += p.beta * o1.y; v[6] += p.beta * o1.z; v[7] += p.beta * o1.w;
+      }
+      *(float4*)C = make_float4(v[0], v[1], v[2], v[3]);
+      *(float4*)(C + 4) = make_float4(v[4], v[5], v[6], v[7]);
+    } else {
+      const int64_t o = (int64_t)row * p.ldc + col;
+      if (MODE == EPI_ACT_RES || MODE == EPI_ACT_DGELU) {
+        const bf16x8 a = *(const bf16x8*)(aux + (int64_t)row * p.ldaux + col);
+#pragma unroll
+        for (int t = 0; t < 8; ++t) v[t] = (MODE == EPI_ACT_RES) ? v[t] + (float)a[t] : v[t] * gelu_grad_fast((float)a[t]);
+      }
+      bf16x8 c;
+#pragma unroll
+      for (int t = 0; t < 8; ++t) c[t] = (bf16)v[t];
+      *(bf16x8*)((bf16*)p.C + o) = c;
+      if (MODE == EPI_ACT_GELU) {
+        bf16x8 g;
+#pragma unroll
+        for (int t = 0; t < 8; ++t) g[t] = (bf16)gelu_fast(v[t]);
+        *(bf16x8*)((bf16*)p.C2 + o) = g;
+      }
+    }
+  } else {
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+      if (col + t >= p.N) break;
+      float x = v[t];
+      if (MODE == EPI_PARTIAL) { p.partial[((int64_t)split * p.M + row) * p.N + col + t] = x; continue; }
+      if (bias) x += (float)bias[col + t];
+      if (MODE == EPI_F32) {
+        float* C = (float*)p.C + (int64_t)row * p.ldc + col + t;
+        *C = (p.beta != 0.0f) ? p.beta * *C + x : x;
+      } else {
+        const int64_t o = (int64_t)row * p.ldc + col + t;
+        if (MODE == EPI_ACT_RES) x += (float)aux[(int64_t)row * p.ldaux + col + t];
+        if (MODE == EPI_ACT_DGELU) x *= gelu_grad_fast((float)aux[(int64_t)row * p.ldaux + col + t]);
+        ((bf16*)p.C)[o] = (bf16)x;
+        if (MODE == EPI_ACT_GELU) ((bf16*)p.C2)[o] = (bf16)gelu_fast(x);
+      }
+    }
+  }
+}
+
+template <int MODE>
+__device__ __forceinline__ bool octet_aligned(const GemmDev& p) {
+  if (MODE == EPI_PARTIAL) return (p.N & 3) == 0;
+  if (MODE == EPI_F32) return (p.ldc & 3) == 0 && ((uintptr_t)p.C & 15) == 0 && (!p.bias || ((uintptr_t)p.bias & 15) == 0);
+  bool ok = (p.ldc & 7) == 0 && ((uintptr_t)p.C & 15) == 0 && (!p.bias || ((uintptr_t)p.bias & 15) == 0);
+  if (MODE == EPI_ACT_RES || MODE == EPI_ACT_DGELU) ok = ok && (p.ldaux & 7) == 0 && ((uintptr_t)p.aux & 15) == 0;
+  if (MODE == EPI_ACT_GELU) ok = ok && ((uintptr_t)p.C2 & 15) == 0;
+  return ok;
+}
+
+// Epilogue through LDS: each wave writes one 32-row slab of its result tile to its own LDS region in
+// row-major order and reads it back so that a lane holds 8 consecutive columns of one row; global
+// accesses are then 16 bytes per lane and whole 128-byte lines per row.  LDS operations of one wave
+// execute in order, so no barrier is needed inside a wave's region.
+template <int MODE, int TI, int TJ>
+__device__ __forceinline__ void tile_epilogue_lds(const GemmDev& p, const f32x16 (&acc)[TI][TJ], int rbase, int cbase, int lane, int split,
+                                                  float* stage) {
+  constexpr int WN = 32 * TJ, LDW = WN + 4;
+  constexpr int LPR = WN / 8;           // lanes per row
+  constexpr int RPI = 64 / LPR;         // rows per read step
+  const bool vec = octet_aligned<MODE>(p);
+#pragma unroll
+  for (int i = 0; i < TI; ++i) {
+#pragma unroll
+    for (int j = 0; j < TJ; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) stage[(8 * (r >> 2) + 4 * (lane >> 5) + (r & 3)) * LDW + j * 32 + (lane & 31)] = acc[i][j][r];
+#pragma unroll
+    for (int it = 0; it < 32 / RPI; ++it) {
+      const int lr = it * RPI + lane / LPR, lc = (lane % LPR) * 8;
+      const float4 lo = *(const float4*)(stage + lr * LDW + lc), hi = *(const float4*)(stage + lr * LDW + lc + 4);
+      const int row = rbase + i * 32 + lr, col = cbase + lc;
+      if (row < p.M && col < p.N) store_octet<MODE>(p, row, col, lo, hi, vec && col + 7 < p.N, split);
+    }
     __builtin_amdgcn_sched_barrier(0);
   }
 }
@@ -330,15 +434,27 @@ void gemm_bf16_mfma(GemmDev p) {
     __syncthreads();
   }
 
-  // The epilogue is selected once per block; each variant is a fully unrolled, branch-light loop
-  // over the accumulator registers (which therefore stay in registers).
+  // The epilogue is selected once per block.  When the staging area fits into the LDS the main loop
+  // used, results go out through LDS in whole lines; otherwise straight from the registers.
   const int rbase = m0 + wm * WM, cbase = n0 + wn * WN;
-  if (p.partial) tile_epilogue<EPI_PARTIAL, TI, TJ>(p, acc, rbase, cbase, lane, blockIdx.z);
-  else if (p.c_f32) tile_epilogue<EPI_F32, TI, TJ>(p, acc, rbase, cbase, lane, 0);
-  else if (p.epi == 0) tile_epilogue<EPI_ACT, TI, TJ>(p, acc, rbase, cbase, lane, 0);
-  else if (p.epi == 1) tile_epilogue<EPI_ACT_RES, TI, TJ>(p, acc, rbase, cbase, lane, 0);
-  else if (p.epi == 2) tile_epilogue<EPI_ACT_GELU, TI, TJ>(p, acc, rbase, cbase, lane, 0);
-  else tile_epilogue<EPI_ACT_DGELU, TI, TJ>(p, acc, rbase, cbase, lane, 0);
+  constexpr int STAGE_FLOATS = 32 * (WN + 4);
+  constexpr bool kStage = (size_t)WGM * WGN * STAGE_FLOATS * sizeof(float) <= 2 * sizeof(bf16) * (size_t)(TA::ELEMS + TB::ELEMS);
+  if constexpr (kStage) {
+    float* stage = (float*)lds_raw + wave * STAGE_FLOATS;     // the last loop iteration ended with a barrier
+    if (p.partial) tile_epilogue_lds<EPI_PARTIAL, TI, TJ>(p, acc, rbase, cbase, lane, blockIdx.z, stage);
+    else if (p.c_f32) tile_epilogue_lds<EPI_F32, TI, TJ>(p, acc, rbase, cbase, lane, 0, stage);
+    else if (p.epi == 0) tile_epilogue_lds<EPI_ACT, TI, TJ>(p, acc, rbase, cbase, lane, 0, stage);
+    else if (p.epi == 1) tile_epilogue_lds<EPI_ACT_RES, TI, TJ>(p, acc, rbase, cbase, lane, 0, stage);
+    else if (p.epi == 2) tile_epilogue_lds<EPI_ACT_GELU, TI, TJ>(p, acc, rbase, cbase, lane, 0, stage);
+    else tile_epilogue_lds<EPI_ACT_DGELU, TI, TJ>(p, acc, rbase, cbase, lane, 0, stage);
+  } else {
+    if (p.partial) tile_epilogue<EPI_PARTIAL, TI, TJ>(p, acc, rbase, cbase, lane, blockIdx.z);
+    else if (p.c_f32) tile_epilogue<EPI_F32, TI, TJ>(p, acc, rbase, cbase, lane, 0);
+    else if (p.epi == 0) tile_epilogue<EPI_ACT, TI, TJ>(p, acc, rbase, cbase, lane, 0);
+    else if (p.epi == 1) tile_epilogue<EPI_ACT_RES, TI, TJ>(p, acc, rbase, cbase, lane, 0);
+    else if (p.epi == 2) tile_epilogue<EPI_ACT_GELU, TI, TJ>(p, acc, rbase, cbase, lane, 0);
+    else tile_epilogue<EPI_ACT_DGELU, TI, TJ>(p, acc, rbase, cbase, lane, 0);
+  }
 }
 
 // sums the split-K partials in split order and applies the epilogue (four columns per thread)
