@@ -320,6 +320,152 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma(const bf16* __restrict_
   }
 }
 
+// ------------------------------------------------------------------------------------------
+// backward for sequences of at most 128 positions: one block per (sequence, head) keeps Q, K, V
+// and dO in LDS; every wave first owns 32 queries (dq), then 32 keys (dk, dv).  One staging phase,
+// one barrier, no second launch and no re-reading of the operands.
+// ------------------------------------------------------------------------------------------
+__device__ __forceinline__ void stage128(bf16* tile, const bf16* __restrict__ src, int64_t ld, int row_limit, int tid) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int c = tid + i * 256;
+    const int r = c >> 3, col = (c & 7) * 8;
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (r < row_limit) v = *(const uint4*)(src + (int64_t)r * ld + col);
+    *(uint4*)(tile + r * LDT + col) = v;
+  }
+}
+
+__global__ __launch_bounds__(256) void attn_bwd_fused128_mfma(const bf16* __restrict__ qkv, const bf16* __restrict__ out,
+                                                              const float* __restrict__ lse, const bf16* __restrict__ d_out,
+                                                              const int32_t* __restrict__ lens, int L, int A, bf16* __restrict__ dqkv) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+  bf16* Qs = (bf16*)lds_raw;
+  bf16* Ks = Qs + 128 * LDT;
+  bf16* Vs = Ks + 128 * LDT;
+  bf16* Gs = Vs + 128 * LDT;
+  float* lse2_s = (float*)(Gs + 128 * LDT);
+  float* dvec_s = lse2_s + 128;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int b = blockIdx.y, h = blockIdx.x;
+  const int H = A * DH;
+  const int64_t ld = 3 * (int64_t)H;
+  int len = lens[b];
+  len = len < 1 ? 1 : (len > L ? L : len);
+  const bf16* base = qkv + (int64_t)b * L * ld + h * DH;
+  const bf16* go = d_out + (int64_t)b * L * H + h * DH;
+  const bf16* oo = out + (int64_t)b * L * H + h * DH;
+
+  stage128(Qs, base, ld, len, tid);
+  stage128(Ks, base + H, ld, len, tid);
+  stage128(Vs, base + 2 * H, ld, len, tid);
+  stage128(Gs, go, H, len, tid);
+  {
+    // row dot products sum_d dO*O: two threads per row, 32 columns each
+    const int r = tid >> 1, c0 = (tid & 1) * 32;
+    float part = 0.f;
+    if (r < len) {
+#pragma unroll
+      for (int c = 0; c < 32; c += 8) {
+        const bf16x8 g = *(const bf16x8*)(go + (int64_t)r * H + c0 + c), o = *(const bf16x8*)(oo + (int64_t)r * H + c0 + c);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) part = fmaf((float)g[e], (float)o[e], part);
+      }
+    }
+    part += __shfl_xor(part, 1);
+    if ((tid & 1) == 0) {
+      dvec_s[r] = part;
+      lse2_s[r] = (r < len) ? lse[((int64_t)b * A + h) * L + r] * LOG2E : 0.f;
+    }
+  }
+  __syncthreads();
+
+  const int own = wave * 32 + (lane & 31);       // the query, then the key, this lane owns
+  const bool wave_active = wave * 32 < len;      // wave-uniform
+  f32x16 acc[2], acc2[2];
+  // ---- queries owned: dq ----
+  if (wave_active) {
+    bf16x8 qf[4], gf[4];
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) { qf[ks] = frag_rows(Qs, wave * 32, ks, lane); gf[ks] = frag_rows(Gs, wave * 32, ks, lane); }
+    const float lse2 = lse2_s[own], drow = dvec_s[own];
+#pragma unroll
+    for (int db = 0; db < 2; ++db)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[db][r] = 0.f;
+    for (int kb = 0; kb < len; kb += 32) {
+      f32x16 st, dp;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) { st[r] = 0.f; dp[r] = 0.f; }
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) {
+        st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(Ks, kb, ks, lane), qf[ks], st, 0, 0, 0);
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(Vs, kb, ks, lane), gf[ks], dp, 0, 0, 0);
+      }
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const bool ok = (kb + tile_row(r, lane) < len) && (own < len);
+        const float pr = ok ? fast_exp2(st[r] * SCALE2 - lse2) : 0.f;
+        st[r] = pr * (dp[r] - drow);
+      }
+      const bf16x8 s0 = pack8(st, 0), s1 = pack8(st, 1);
+#pragma unroll
+      for (int db = 0; db < 2; ++db) {
+        acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols_t(Ks, kb, 0, 32 * db, lane), s0, acc[db], 0, 0, 0);
+        acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols_t(Ks, kb, 1, 32 * db, lane), s1, acc[db], 0, 0, 0);
+      }
+    }
+  } else {
+#pragma unroll
+    for (int db = 0; db < 2; ++db)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[db][r] = 0.f;
+  }
+  if (own < L) store_owned_rows(dqkv + ((int64_t)b * L + own) * ld + h * DH, acc, 0.125f, lane);
+
+  // ---- keys owned: dk, dv ----
+#pragma unroll
+  for (int db = 0; db < 2; ++db)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { acc[db][r] = 0.f; acc2[db][r] = 0.f; }
+  if (wave_active) {
+    bf16x8 kf[4], vf[4];
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) { kf[ks] = frag_rows(Ks, wave * 32, ks, lane); vf[ks] = frag_rows(Vs, wave * 32, ks, lane); }
+    for (int qb = 0; qb < len; qb += 32) {
+      f32x16 st, dp;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) { st[r] = 0.f; dp[r] = 0.f; }
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) {
+        st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(Qs, qb, ks, lane), kf[ks], st, 0, 0, 0);
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(Gs, qb, ks, lane), vf[ks], dp, 0, 0, 0);
+      }
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int qi = qb + tile_row(r, lane);
+        const bool ok = (qi < len) && (own < len);
+        const float pr = ok ? fast_exp2(st[r] * SCALE2 - lse2_s[qi]) : 0.f;
+        st[r] = pr;
+        dp[r] = pr * (dp[r] - dvec_s[qi]);
+      }
+      const bf16x8 p0 = pack8(st, 0), p1 = pack8(st, 1), s0 = pack8(dp, 0), s1 = pack8(dp, 1);
+#pragma unroll
+      for (int db = 0; db < 2; ++db) {
+        acc2[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols_t(Gs, qb, 0, 32 * db, lane), p0, acc2[db], 0, 0, 0);
+        acc2[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols_t(Gs, qb, 1, 32 * db, lane), p1, acc2[db], 0, 0, 0);
+        acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols_t(Qs, qb, 0, 32 * db, lane), s0, acc[db], 0, 0, 0);
+        acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols_t(Qs, qb, 1, 32 * db, lane), s1, acc[db], 0, 0, 0);
+      }
+    }
+  }
+  if (own < L) {
+    bf16* row = dqkv + ((int64_t)b * L + own) * ld + h * DH;
+    store_owned_rows(row + H, acc, 0.125f, lane);
+    store_owned_rows(row + 2 * H, acc2, 1.0f, lane);
+  }
+}
+
 }  // namespace
 
 void launch_attention_fwd_mfma(const void* qkv, const int32_t* lens, int B, int L, int A, void* out, float* lse, hipStream_t s) {
@@ -329,6 +475,14 @@ void launch_attention_fwd_mfma(const void* qkv, const int32_t* lens, int B, int 
 
 void launch_attention_bwd_mfma(const void* qkv, const void* out, const float* lse, const void* d_out, const int32_t* lens, int B, int L,
                                int A, void* dqkv, float* dvec, hipStream_t s) {
+  if (L <= 128) {
+    constexpr size_t lds = 4 * 128 * LDT * sizeof(bf16) + 2 * 128 * sizeof(float);
+    static bool configured = false;
+    if (!configured) { (void)hipFuncSetAttribute((const void*)attn_bwd_fused128_mfma, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); configured = true; }
+    hipLaunchKernelGGL(attn_bwd_fused128_mfma, dim3(A, B), dim3(256), lds, s, (const bf16*)qkv, (const bf16*)out, lse, (const bf16*)d_out, lens,
+                       L, A, (bf16*)dqkv);
+    return;
+  }
   dim3 grid((L + 127) / 128, A, B);
   hipLaunchKernelGGL(attn_bwd_dq_mfma, grid, dim3(256), 0, s, (const bf16*)qkv, (const bf16*)out, lse, (const bf16*)d_out, lens, L, A,
                      (bf16*)dqkv, dvec);

@@ -180,7 +180,7 @@ def attention_reference(qkv, lens, B, L, A):
 
 @pytest.mark.parametrize("mode", [0, 1])
 @pytest.mark.parametrize("B,L,A,lens", [(3, 64, 2, [64, 1, 37]), (2, 136, 3, [136, 70]), (1, 8, 1, [5]),
-                                        (3, 512, 2, [512, 300, 33]), (2, 256, 1, [129, 256])])
+                                        (3, 512, 2, [512, 300, 33]), (2, 256, 1, [129, 256]), (3, 128, 2, [128, 77, 31]), (2, 104, 1, [104, 97])])
 def test_attention_fwd_bwd(hs, mode, B, L, A, lens):
     rng = np.random.default_rng(B * L + A)
     H = A * 64
