@@ -3,8 +3,6 @@
 //         contraction index is NOT the contiguous one are staged in their natural layout and read
 //         with the LDS transpose read of gfx950, so every global and LDS access is 16/8 bytes wide.
 //   fp32: plain tiled SIMT kernel (small reference-precision configurations only).
-#include <cstdlib>
-
 #include "common.h"
 
 namespace {
@@ -566,23 +564,10 @@ hipError_t launch_cfg(const GemmArgs& g, const GemmDev& p, int splits, hipStream
   return launch_one<false, false, BM, BN, BK, WGM, WGN>(p, grid, s);
 }
 
-struct TileCfg { int bm, bn, bk; };
-const TileCfg kCfgs[] = {{128, 128, 32}, {128, 128, 64}, {256, 128, 32}, {256, 128, 64}, {256, 256, 32}, {128, 256, 32},
-                         {256, 128, 32}, {256, 256, 32}, {256, 256, 64}};
-
-hipError_t launch_by_id(int id, const GemmArgs& g, const GemmDev& p, int splits, hipStream_t s) {
-  switch (id) {
-    case 1: return launch_cfg<128, 128, 64, 2, 2>(g, p, splits, s);
-    case 2: return launch_cfg<256, 128, 32, 2, 2>(g, p, splits, s);
-    case 3: return launch_cfg<256, 128, 64, 2, 2>(g, p, splits, s);
-    case 4: return launch_cfg<256, 256, 32, 2, 2>(g, p, splits, s);
-    case 5: return launch_cfg<128, 256, 32, 2, 2>(g, p, splits, s);
-    case 6: return launch_cfg<256, 128, 32, 4, 2>(g, p, splits, s);
-    case 7: return launch_cfg<256, 256, 32, 4, 2>(g, p, splits, s);
-    case 8: return launch_cfg<256, 256, 64, 2, 2>(g, p, splits, s);
-    default: return launch_cfg<128, 128, 32, 2, 2>(g, p, splits, s);
-  }
-}
+// The one tile shape in use: 128 x 128 x 32 with 2 x 2 waves.  Measured alternatives (256 x 128 and
+// 256 x 256 block tiles, 8-wave blocks, 64-deep k-tiles, asynchronous global->LDS rings with 4
+// stages) were equal or slower on every shape of the training step and are not built.
+constexpr int kBM = 128, kBN = 128, kBK = 32;
 
 }  // namespace
 
@@ -611,28 +596,23 @@ hs_status launch_gemm(hs_ctx* ctx, const GemmArgs& g, hipStream_t s) {
     if (g.a_kmajor && g.b_kmajor && (g.K % 8))
       return hs_fail(ctx, HS_ERR_SHAPE, "gemm(bf16): K must be a multiple of 8 when both operands are k-major");
     if (!g.a_kmajor && g.b_kmajor) return hs_fail(ctx, HS_ERR_UNIMPLEMENTED, "gemm(bf16): A m-major with B k-major is not built");
-    int id = 0;
-    if (const char* e = getenv("HS_GEMM_CFG")) id = atoi(e);
-    if (id < 0 || id > 8) id = 0;
-    const TileCfg tc = kCfgs[id];
     // split-K when the output has too few tiles to fill the chip and a scratch buffer was given
-    const int64_t tiles = (int64_t)((g.M + tc.bm - 1) / tc.bm) * ((g.N + tc.bn - 1) / tc.bn);
+    const int64_t tiles = (int64_t)((g.M + kBM - 1) / kBM) * ((g.N + kBN - 1) / kBN);
     int splits = 1;
     if (g.ws && tiles < 256) {
       int64_t want = (512 + tiles - 1) / tiles;
-      const int64_t by_k = g.K / (4 * tc.bk), by_ws = (int64_t)(g.ws_bytes / ((size_t)g.M * g.N * sizeof(float)));
+      const int64_t by_k = g.K / (4 * kBK), by_ws = (int64_t)(g.ws_bytes / ((size_t)g.M * g.N * sizeof(float)));
       if (want > by_k) want = by_k;
       if (want > by_ws) want = by_ws;
       if (want > 32) want = 32;
       if (want > 1) splits = (int)want;
     }
-    if (const char* e = getenv("HS_GEMM_SPLITS")) { int v = atoi(e); if (v >= 1 && g.ws && (size_t)v * g.M * g.N * 4 <= g.ws_bytes) splits = v; }
     if (splits > 1) {
       p.partial = (float*)g.ws;
-      p.k_per_split = (int)(((g.K + splits - 1) / splits + tc.bk - 1) / tc.bk * tc.bk);
+      p.k_per_split = (int)(((g.K + splits - 1) / splits + kBK - 1) / kBK * kBK);
       splits = (g.K + p.k_per_split - 1) / p.k_per_split;
     }
-    hipError_t e = launch_by_id(id, g, p, splits, s);
+    hipError_t e = launch_cfg<kBM, kBN, kBK, 2, 2>(g, p, splits, s);
     if (e != hipSuccess) return hs_fail(ctx, HS_ERR_HIP, std::string("gemm launch: ") + hipGetErrorString(e));
     if (splits > 1) {
       const int64_t mn = (int64_t)g.M * g.N;
