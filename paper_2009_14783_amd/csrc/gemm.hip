@@ -236,8 +236,7 @@ template <int MODE, int TI, int TJ>
 __device__ __forceinline__ void tile_epilogue_lds(const GemmDev& p, const f32x16 (&acc)[TI][TJ], int rbase, int cbase, int lane, int split,
                                                   float* stage) {
   constexpr int WN = 32 * TJ, LDW = WN + 4;
-  constexpr int LPR = WN / 8;           // lanes per row
-  constexpr int RPI = 64 / LPR;         // rows per read step
+  constexpr int LPR = WN / 8;           // 8-column pieces per row
   const bool vec = octet_aligned<MODE>(p);
 #pragma unroll
   for (int i = 0; i < TI; ++i) {
@@ -246,8 +245,9 @@ __device__ __forceinline__ void tile_epilogue_lds(const GemmDev& p, const f32x16
 #pragma unroll
       for (int r = 0; r < 16; ++r) stage[(8 * (r >> 2) + 4 * (lane >> 5) + (r & 3)) * LDW + j * 32 + (lane & 31)] = acc[i][j][r];
 #pragma unroll
-    for (int it = 0; it < 32 / RPI; ++it) {
-      const int lr = it * RPI + lane / LPR, lc = (lane % LPR) * 8;
+    for (int it = 0; it < 32 * LPR / 64; ++it) {
+      const int piece = it * 64 + lane;
+      const int lr = piece / LPR, lc = (piece % LPR) * 8;
       const float4 lo = *(const float4*)(stage + lr * LDW + lc), hi = *(const float4*)(stage + lr * LDW + lc + 4);
       const int row = rbase + i * 32 + lr, col = cbase + lc;
       if (row < p.M && col < p.N) store_octet<MODE>(p, row, col, lo, hi, vec && col + 7 < p.N, split);
@@ -256,65 +256,71 @@ __device__ __forceinline__ void tile_epilogue_lds(const GemmDev& p, const f32x16
   }
 }
 
-constexpr int KPAD = 8;    // k-major LDS rows: BK + 8 elements  (conflict-free 16-byte reads)
 constexpr int MPAD = 32;   // m-major LDS rows: R + 32 elements  (row stride = 64 B mod 256 B)
 
 template <bool KMAJ, int R, int BK, int NT>
 struct OperandTile {
-  static constexpr int LD = KMAJ ? (BK + KPAD) : (R + MPAD);
+  // k-major rows are stored without padding and with their 16-byte chunks permuted: chunk j of row r sits
+  // at position j ^ ((r / 4) % 4).  Sixteen rows read at one k-offset then fall into sixteen different
+  // 16-byte bank groups, and so do the four 64-byte rows that sixteen lanes write at once.
+  static_assert(!KMAJ || BK == 32, "the chunk permutation is written for four chunks per row");
+  static constexpr int LD = KMAJ ? BK : (R + MPAD);
+  static __device__ __forceinline__ int swz(int row, int chunk) { return (chunk ^ ((row >> 2) & 3)) * 8; }
   static constexpr int ELEMS = KMAJ ? R * LD : BK * LD;
   static constexpr int CPR = KMAJ ? BK / 8 : R / 8;       // 8-element chunks per stored row
   static constexpr int NCH = R * BK / 8 / NT;             // chunks per thread
   static_assert(R * BK / 8 % NT == 0, "tile must split evenly over the threads");
 
-  // Per-thread state of the global side: one pointer per chunk (advanced every k-tile) and whether the
-  // chunk's position along the non-contraction index is inside the matrix.
+  // Per-thread state of the global side: one 32-bit byte offset per chunk from the start of the matrix
+  // (advanced every k-tile; the matrix start is uniform, so a load needs one address register) and whether
+  // the chunk's position along the non-contraction index is inside the matrix.
   struct Cursor {
-    const bf16* ptr[NCH];
-    const bf16* safe;     // an always-readable address (start of the matrix) for masked-out chunks
+    const char* base;     // start of the matrix: always readable, also the address of masked-out chunks
+    unsigned off[NCH];
+    unsigned step;        // bytes from one k-tile to the next
     int koff[NCH];        // contraction offset of the chunk inside a k-tile
     bool ok[NCH];
-    bool edge;            // some chunk of this block lies outside the matrix along the non-contraction index
   };
   static __device__ __forceinline__ void init(Cursor& cu, const bf16* __restrict__ base, int64_t ld, int row0, int rext, int kbeg, int tid) {
-    cu.safe = base;
-    cu.edge = row0 + R > rext;
+    cu.base = (const char*)base;
+    cu.step = (unsigned)(KMAJ ? (int64_t)BK * 2 : (int64_t)BK * ld * 2);
 #pragma unroll
     for (int i = 0; i < NCH; ++i) {
       const int c = tid + i * NT;
       const int a = c / CPR, b = (c % CPR) * 8;
-      if (KMAJ) { cu.ok[i] = row0 + a < rext; cu.koff[i] = b; cu.ptr[i] = base + (int64_t)(row0 + a) * ld + kbeg + b; }
-      else      { cu.ok[i] = row0 + b < rext; cu.koff[i] = a; cu.ptr[i] = base + (int64_t)(kbeg + a) * ld + row0 + b; }
+      if (KMAJ) { cu.ok[i] = row0 + a < rext; cu.koff[i] = b; cu.off[i] = (unsigned)(((int64_t)(row0 + a) * ld + kbeg + b) * 2); }
+      else      { cu.ok[i] = row0 + b < rext; cu.koff[i] = a; cu.off[i] = (unsigned)(((int64_t)(kbeg + a) * ld + row0 + b) * 2); }
     }
   }
   // global -> registers for the k-tile that starts at k0, then advance.  The loads are unconditional
   // (no branch, so the hardware load counter can be waited on exactly): a chunk outside the matrix or
-  // beyond kend reads the safe address instead and is zeroed when it is written to LDS.
-  static __device__ __forceinline__ void load(uint4 (&reg)[NCH], Cursor& cu, int64_t ld, int k0, int kend) {
+  // beyond kend reads the start of the matrix instead and is zeroed when it is written to LDS.
+  static __device__ __forceinline__ void load(uint4 (&reg)[NCH], Cursor& cu, int k0, int kend) {
 #pragma unroll
     for (int i = 0; i < NCH; ++i) {
       const bool ok = cu.ok[i] && k0 + cu.koff[i] < kend;
-      const bf16* q = ok ? cu.ptr[i] : cu.safe;
-      reg[i] = *(const uint4*)q;
-      cu.ptr[i] += KMAJ ? (int64_t)BK : (int64_t)BK * ld;
+      reg[i] = *(const uint4*)(cu.base + (ok ? cu.off[i] : 0u));
+      cu.off[i] += cu.step;
     }
   }
   // registers -> LDS for the k-tile that started at k0 (chunks that were masked out become zeros)
   static __device__ __forceinline__ void store(const uint4 (&reg)[NCH], bf16* s, int tid, const Cursor& cu, int k0, int kend) {
-    const bool mask = cu.edge || k0 + BK > kend;      // uniform over the block
 #pragma unroll
     for (int i = 0; i < NCH; ++i) {
       const int c = tid + i * NT;
       const int a = c / CPR, b = (c % CPR) * 8;
+      // branch-free select: an all-ones or all-zeros word per chunk
+      const unsigned keep = (cu.ok[i] && k0 + cu.koff[i] < kend) ? 0xffffffffu : 0u;
       uint4 v = reg[i];
-      if (mask && !(cu.ok[i] && k0 + cu.koff[i] < kend)) v = make_uint4(0, 0, 0, 0);
-      *(uint4*)(s + a * LD + b) = v;
+      v.x &= keep; v.y &= keep; v.z &= keep; v.w &= keep;
+      *(uint4*)(s + a * LD + (KMAJ ? swz(a, b >> 3) : b)) = v;
     }
   }
   // LDS -> MFMA operand: lane gets elements (row = rbase + lane%32, k = ks*16 + 8*(lane/32) + 0..7)
   static __device__ __forceinline__ bf16x8 frag(const bf16* s, int rbase, int ks, int lane) {
     if (KMAJ) {
-      return *(const bf16x8*)(s + (rbase + (lane & 31)) * LD + ks * 16 + (lane >> 5) * 8);
+      const int row = rbase + (lane & 31);
+      return *(const bf16x8*)(s + row * LD + swz(row, ks * 2 + (lane >> 5)));
     } else {
       // Transpose read: within each group of 16 lanes, lane i receives, as element e, the (i%4)-th
       // 16-bit value of the 8 bytes addressed by lane 4*e + i/4 of the group.  With lane s of a
@@ -333,13 +339,23 @@ struct OperandTile {
 };
 
 // Block tile BM x BN x BK, WGM x WGN waves, each wave (BM/WGM) x (BN/WGN) as 32x32x16 MFMA tiles.
-// blockIdx.z selects a contiguous range of k-tiles (split-K); with more than one split the raw fp32
+// A block's split index selects a contiguous range of k-tiles (split-K); with more than one split the raw fp32
 // sums go to p.partial[z][M][N] and splitk_reduce_kernel applies the epilogue.
 // waves per SIMD the register allocator should leave room for: accumulators take
 // (BM/WGM)*(BN/WGN)/64 registers per lane out of 512
 constexpr int gemm_occupancy(int bm, int bn, int wgm, int wgn) {
   const int acc = (bm / wgm) * (bn / wgn) / 64;
   return acc <= 64 ? 3 : (acc <= 128 ? 2 : 1);
+}
+
+// dynamic LDS of a block: the two pipeline stages of both operands, and at least the staging area of
+// the epilogue (one 32-row slab of fp32 results per wave) when that is not much larger
+template <bool AK, bool BKM, int BM, int BN, int BK, int WGM, int WGN>
+constexpr size_t gemm_lds_bytes() {
+  constexpr int NT = 64 * WGM * WGN;
+  const size_t pipe = 2 * sizeof(bf16) * (size_t)(OperandTile<AK, BM, BK, NT>::ELEMS + OperandTile<BKM, BN, BK, NT>::ELEMS);
+  const size_t stage = (size_t)WGM * WGN * 32 * (BN / WGN + 4) * sizeof(float);
+  return (stage > pipe && stage <= pipe + pipe / 4) ? stage : pipe;
 }
 
 template <bool AK, bool BKM, int BM, int BN, int BK, int WGM, int WGN>
@@ -358,15 +374,21 @@ void gemm_bf16_mfma(GemmDev p) {
   // Tile order.  Workgroups are handed to the 8 XCDs round-robin by linear id, and each XCD has its own
   // L2: give every XCD a contiguous range of tiles, and walk the tiles in groups of 8 tile rows so that
   // the tiles in flight on one XCD share operand panels.
-  int b = blockIdx.y * gridDim.x + blockIdx.x;
+  // The same holds across the k-splits (blockIdx.z): an XCD then works on one or two splits
+  // instead of all of them, and fetches only their share of the operands.  Blocks beyond the last
+  // multiple of 8 keep their place.
   const int nbx = gridDim.x, nby = gridDim.y, nb = nbx * nby;
-  if ((nb & 7) == 0) b = (b & 7) * (nb >> 3) + (b >> 3);
+  int v = (blockIdx.z * nby + blockIdx.y) * nbx + blockIdx.x;
+  const int per_xcd = (nb * (int)gridDim.z) >> 3;
+  if (v < 8 * per_xcd) v = (v & 7) * per_xcd + (v >> 3);
+  const int split = v / nb;
+  const int b = v - split * nb;
   constexpr int GM = 8;
   const int group = b / (GM * nbx), first_m = group * GM;
   const int gm = min(GM, nby - first_m);
   const int in_group = b - group * GM * nbx;
   const int m0 = (first_m + in_group % gm) * BM, n0 = (in_group / gm) * BN;
-  const int kbeg = blockIdx.z * p.k_per_split;
+  const int kbeg = split * p.k_per_split;
   const int kend = min(p.K, kbeg + p.k_per_split);
 
   f32x16 acc[TI][TJ];
@@ -387,48 +409,58 @@ void gemm_bf16_mfma(GemmDev p) {
   // The tile count is rounded up to even; a tile beyond the range loads nothing real and is all zeros.
   uint4 ra0[TA::NCH], rb0[TB::NCH], ra1[TA::NCH], rb1[TB::NCH];
   const int nk = ((kend - kbeg + BK - 1) / BK + 1) & ~1;
-  TA::load(ra0, ca, p.lda, kbeg, kend);
-  TB::load(rb0, cb, p.ldb, kbeg, kend);
-  TA::load(ra1, ca, p.lda, kbeg + BK, kend);
-  TB::load(rb1, cb, p.ldb, kbeg + BK, kend);
+  TA::load(ra0, ca, kbeg, kend);
+  TB::load(rb0, cb, kbeg, kend);
+  TA::load(ra1, ca, kbeg + BK, kend);
+  TB::load(rb1, cb, kbeg + BK, kend);
   TA::store(ra0, sA0, tid, ca, kbeg, kend);
   TB::store(rb0, sB0, tid, cb, kbeg, kend);
   __syncthreads();
 
-  auto compute = [&](int cur) {
+  // One k-tile of work, in the order the hardware queues like it: all fragment reads of the tile, the
+  // MFMAs of its first half, then the LDS writes of the next tile (they need the global loads issued one
+  // iteration ago and complete behind the second half's MFMAs), then the second half.
+  static_assert(BK == 32, "the main loop is written for two 16-deep MFMA steps per k-tile");
+  bf16x8 fa[2][TI], fb[2][TJ];
+  auto frags = [&](int cur) {
     const bf16* sAc = sA0 + cur * TA::ELEMS;
     const bf16* sBc = sB0 + cur * TB::ELEMS;
 #pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks) {
-      bf16x8 fa[TI], fb[TJ];
+    for (int ks = 0; ks < 2; ++ks) {
 #pragma unroll
-      for (int i = 0; i < TI; ++i) fa[i] = TA::frag(sAc, wm * WM + i * 32, ks, lane);
+      for (int i = 0; i < TI; ++i) fa[ks][i] = TA::frag(sAc, wm * WM + i * 32, ks, lane);
 #pragma unroll
-      for (int j = 0; j < TJ; ++j) fb[j] = TB::frag(sBc, wn * WN + j * 32, ks, lane);
-#pragma unroll
-      for (int i = 0; i < TI; ++i)
-#pragma unroll
-        for (int j = 0; j < TJ; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+      for (int j = 0; j < TJ; ++j) fb[ks][j] = TB::frag(sBc, wn * WN + j * 32, ks, lane);
     }
+  };
+  auto mfmas = [&](int ks) {
+#pragma unroll
+    for (int i = 0; i < TI; ++i)
+#pragma unroll
+      for (int j = 0; j < TJ; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks][i], fb[ks][j], acc[i][j], 0, 0, 0);
   };
 
   for (int kt = 0; kt < nk; kt += 2) {
     const int k0 = kbeg + kt * BK;
     // even tile kt: in LDS buffer 0; register set 0 is free, set 1 holds tile kt+1
-    TA::load(ra0, ca, p.lda, k0 + 2 * BK, kend);
-    TB::load(rb0, cb, p.ldb, k0 + 2 * BK, kend);
-    compute(0);
+    TA::load(ra0, ca, k0 + 2 * BK, kend);
+    TB::load(rb0, cb, k0 + 2 * BK, kend);
+    frags(0);
+    mfmas(0);
     TA::store(ra1, sA0 + TA::ELEMS, tid, ca, k0 + BK, kend);
     TB::store(rb1, sB0 + TB::ELEMS, tid, cb, k0 + BK, kend);
+    mfmas(1);
     __syncthreads();
     // odd tile kt+1: in LDS buffer 1; register set 1 is free, set 0 holds tile kt+2
-    TA::load(ra1, ca, p.lda, k0 + 3 * BK, kend);
-    TB::load(rb1, cb, p.ldb, k0 + 3 * BK, kend);
-    compute(1);
+    TA::load(ra1, ca, k0 + 3 * BK, kend);
+    TB::load(rb1, cb, k0 + 3 * BK, kend);
+    frags(1);
+    mfmas(0);
     if (kt + 2 < nk) {
       TA::store(ra0, sA0, tid, ca, k0 + 2 * BK, kend);
       TB::store(rb0, sB0, tid, cb, k0 + 2 * BK, kend);
     }
+    mfmas(1);
     __syncthreads();
   }
 
@@ -436,17 +468,17 @@ void gemm_bf16_mfma(GemmDev p) {
   // used, results go out through LDS in whole lines; otherwise straight from the registers.
   const int rbase = m0 + wm * WM, cbase = n0 + wn * WN;
   constexpr int STAGE_FLOATS = 32 * (WN + 4);
-  constexpr bool kStage = (size_t)WGM * WGN * STAGE_FLOATS * sizeof(float) <= 2 * sizeof(bf16) * (size_t)(TA::ELEMS + TB::ELEMS);
+  constexpr bool kStage = (size_t)WGM * WGN * STAGE_FLOATS * sizeof(float) <= gemm_lds_bytes<AK, BKM, BM, BN, BK, WGM, WGN>();
   if constexpr (kStage) {
     float* stage = (float*)lds_raw + wave * STAGE_FLOATS;     // the last loop iteration ended with a barrier
-    if (p.partial) tile_epilogue_lds<EPI_PARTIAL, TI, TJ>(p, acc, rbase, cbase, lane, blockIdx.z, stage);
+    if (p.partial) tile_epilogue_lds<EPI_PARTIAL, TI, TJ>(p, acc, rbase, cbase, lane, split, stage);
     else if (p.c_f32) tile_epilogue_lds<EPI_F32, TI, TJ>(p, acc, rbase, cbase, lane, 0, stage);
     else if (p.epi == 0) tile_epilogue_lds<EPI_ACT, TI, TJ>(p, acc, rbase, cbase, lane, 0, stage);
     else if (p.epi == 1) tile_epilogue_lds<EPI_ACT_RES, TI, TJ>(p, acc, rbase, cbase, lane, 0, stage);
     else if (p.epi == 2) tile_epilogue_lds<EPI_ACT_GELU, TI, TJ>(p, acc, rbase, cbase, lane, 0, stage);
     else tile_epilogue_lds<EPI_ACT_DGELU, TI, TJ>(p, acc, rbase, cbase, lane, 0, stage);
   } else {
-    if (p.partial) tile_epilogue<EPI_PARTIAL, TI, TJ>(p, acc, rbase, cbase, lane, blockIdx.z);
+    if (p.partial) tile_epilogue<EPI_PARTIAL, TI, TJ>(p, acc, rbase, cbase, lane, split);
     else if (p.c_f32) tile_epilogue<EPI_F32, TI, TJ>(p, acc, rbase, cbase, lane, 0);
     else if (p.epi == 0) tile_epilogue<EPI_ACT, TI, TJ>(p, acc, rbase, cbase, lane, 0);
     else if (p.epi == 1) tile_epilogue<EPI_ACT_RES, TI, TJ>(p, acc, rbase, cbase, lane, 0);
@@ -544,7 +576,7 @@ namespace {
 template <bool AK, bool BKM, int BM, int BN, int BK, int WGM, int WGN>
 hipError_t launch_one(const GemmDev& p, dim3 grid, hipStream_t s) {
   constexpr int NT = 64 * WGM * WGN;
-  constexpr size_t lds = 2 * sizeof(bf16) * (OperandTile<AK, BM, BK, NT>::ELEMS + OperandTile<BKM, BN, BK, NT>::ELEMS);
+  constexpr size_t lds = gemm_lds_bytes<AK, BKM, BM, BN, BK, WGM, WGN>();
   auto kern = gemm_bf16_mfma<AK, BKM, BM, BN, BK, WGM, WGN>;
   static bool configured = false;          // per instantiation; the attribute is per process and device-wide
   if (!configured && lds > 48 * 1024) {
@@ -564,9 +596,12 @@ hipError_t launch_cfg(const GemmArgs& g, const GemmDev& p, int splits, hipStream
   return launch_one<false, false, BM, BN, BK, WGM, WGN>(p, grid, s);
 }
 
-// The one tile shape in use: 128 x 128 x 32 with 2 x 2 waves.  Measured alternatives (256 x 128 and
-// 256 x 256 block tiles, 8-wave blocks, 64-deep k-tiles, asynchronous global->LDS rings with 4
-// stages) were equal or slower on every shape of the training step and are not built.
+// The one tile shape in use: 128 x 128 x 32 with 2 x 2 waves, three blocks per CU.  Measured alternatives
+// were equal or slower over the shapes of the training step and are not built: 256 x 128 and 256 x 256
+// block tiles, 8-wave blocks, 64-deep k-tiles, asynchronous global->LDS rings with 4 stages, and a
+// three-stage LDS pipeline with two fragment sets and a prescribed MFMA/LDS/global issue order (faster
+// only with a single block per CU: 128 x 192 tiles gained 5-15 % on the N = 768 shapes and lost on the
+// weight-gradient shapes).
 constexpr int kBM = 128, kBN = 128, kBK = 32;
 
 }  // namespace
@@ -596,6 +631,11 @@ hs_status launch_gemm(hs_ctx* ctx, const GemmArgs& g, hipStream_t s) {
     if (g.a_kmajor && g.b_kmajor && (g.K % 8))
       return hs_fail(ctx, HS_ERR_SHAPE, "gemm(bf16): K must be a multiple of 8 when both operands are k-major");
     if (!g.a_kmajor && g.b_kmajor) return hs_fail(ctx, HS_ERR_UNIMPLEMENTED, "gemm(bf16): A m-major with B k-major is not built");
+    // the kernel addresses each operand with 32-bit byte offsets from its start (one k-tile of slack)
+    const int64_t a_rows = g.a_kmajor ? g.M : g.K, b_rows = g.b_kmajor ? g.N : g.K;
+    const int64_t lim = ((int64_t)1 << 32) - 1;
+    if ((a_rows + 2 * kBK) * g.lda * 2 + 4 * kBK > lim || (b_rows + 2 * kBK) * g.ldb * 2 + 4 * kBK > lim)
+      return hs_fail(ctx, HS_ERR_SHAPE, "gemm(bf16): an operand exceeds 4 GiB");
     // split-K when the output has too few tiles to fill the chip and a scratch buffer was given
     const int64_t tiles = (int64_t)((g.M + kBM - 1) / kBM) * ((g.N + kBN - 1) / kBN);
     int splits = 1;

@@ -116,15 +116,40 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(const T* __restrict__ dy, c
     ag[c] = ab[c] = as[c] = make_float4(0.f, 0.f, 0.f, 0.f);
     g[c] = (c * 64 + lane < nch) ? Vec4<T>::ld(gain + 4 * (c * 64 + lane)) : make_float4(0.f, 0.f, 0.f, 0.f);
   }
-  for (int row = blockIdx.x * 4 + wave; row < R; row += gridDim.x * 4) {
-    const float mu = stats[row], rstd = stats[R + row];
-    float4 xh[MAXCH], dyv[MAXCH];
-    float s1 = 0.f, s2 = 0.f;
+  // Rows of one wave are software-pipelined: the loads of the wave's next row are issued before the
+  // reductions of the current one, so two rows are in flight per wave.
+  const int stride = gridDim.x * 4;
+  int row = blockIdx.x * 4 + wave;
+  float4 nx[MAXCH], ndy[MAXCH];
+  float nmu = 0.f, nrstd = 0.f;
+  if (row < R) {
+    nmu = stats[row]; nrstd = stats[R + row];
 #pragma unroll
     for (int c = 0; c < MAXCH; ++c) if (c * 64 + lane < nch) {
       const int64_t o = (int64_t)row * H + 4 * (c * 64 + lane);
-      const float4 xv = Vec4<T>::ld(x + o);
-      dyv[c] = Vec4<T>::ld(dy + o);
+      nx[c] = Vec4<T>::ld(x + o);
+      ndy[c] = Vec4<T>::ld(dy + o);
+    }
+  }
+  for (; row < R; row += stride) {
+    const float mu = nmu, rstd = nrstd;
+    float4 xh[MAXCH], dyv[MAXCH];
+#pragma unroll
+    for (int c = 0; c < MAXCH; ++c) { xh[c] = nx[c]; dyv[c] = ndy[c]; }
+    const int next = row + stride;
+    if (next < R) {
+      nmu = stats[next]; nrstd = stats[R + next];
+#pragma unroll
+      for (int c = 0; c < MAXCH; ++c) if (c * 64 + lane < nch) {
+        const int64_t o = (int64_t)next * H + 4 * (c * 64 + lane);
+        nx[c] = Vec4<T>::ld(x + o);
+        ndy[c] = Vec4<T>::ld(dy + o);
+      }
+    }
+    float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+    for (int c = 0; c < MAXCH; ++c) if (c * 64 + lane < nch) {
+      const float4 xv = xh[c];
       xh[c] = make_float4((xv.x - mu) * rstd, (xv.y - mu) * rstd, (xv.z - mu) * rstd, (xv.w - mu) * rstd);
       const float4 d = make_float4(dyv[c].x * g[c].x, dyv[c].y * g[c].y, dyv[c].z * g[c].z, dyv[c].w * g[c].w);
       s1 += (d.x + d.y) + (d.z + d.w);
