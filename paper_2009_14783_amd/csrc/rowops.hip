@@ -187,12 +187,13 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(const T* __restrict__ dy, c
 }
 
 // out_q[col] = beta*out_q[col] + sum_p partials[p*pstride + q*qstride + col] for up to three quantities q
-// (blockIdx.y).  Fixed summation tree: wave w of the block adds p = w, w+4, w+8, ... in ascending order,
-// then the four wave sums are added in wave order.
-__global__ __launch_bounds__(256) void sum_partials_kernel(const float* __restrict__ partials, int np, int64_t pstride, int64_t qstride,
-                                                           int C, float* __restrict__ out0, float* __restrict__ out1,
-                                                           float* __restrict__ out2, float beta) {
-  __shared__ float red[4][64];
+// (blockIdx.y).  Fixed summation tree: wave w of the block's 16 waves adds p = w, w+16, w+32, ... in
+// ascending order, then the wave sums are added in wave order.
+constexpr int SP_WAVES = 16;
+__global__ __launch_bounds__(64 * SP_WAVES) void sum_partials_kernel(const float* __restrict__ partials, int np, int64_t pstride,
+                                                                    int64_t qstride, int C, float* __restrict__ out0,
+                                                                    float* __restrict__ out1, float* __restrict__ out2, float beta) {
+  __shared__ float red[SP_WAVES][64];
   const int q = blockIdx.y;
   float* out = q == 0 ? out0 : (q == 1 ? out1 : out2);
   if (!out) return;                                   // uniform over the block
@@ -202,19 +203,21 @@ __global__ __launch_bounds__(256) void sum_partials_kernel(const float* __restri
   if (col < C) {
     const float* src = partials + q * qstride + col;
     int p = wave;
-    for (; p + 28 < np; p += 32) {
+    for (; p + 7 * SP_WAVES < np; p += 8 * SP_WAVES) {
       float a[8];
 #pragma unroll
-      for (int u = 0; u < 8; ++u) a[u] = src[(int64_t)(p + 4 * u) * pstride];
+      for (int u = 0; u < 8; ++u) a[u] = src[(int64_t)(p + SP_WAVES * u) * pstride];
 #pragma unroll
       for (int u = 0; u < 8; ++u) s += a[u];
     }
-    for (; p < np; p += 4) s += src[(int64_t)p * pstride];
+    for (; p < np; p += SP_WAVES) s += src[(int64_t)p * pstride];
   }
   red[wave][lane] = s;
   __syncthreads();
   if (wave == 0 && col < C) {
-    const float t = ((red[0][lane] + red[1][lane]) + red[2][lane]) + red[3][lane];
+    float t = red[0][lane];
+#pragma unroll
+    for (int w = 1; w < SP_WAVES; ++w) t += red[w][lane];
     out[col] = (beta != 0.f) ? beta * out[col] + t : t;
   }
 }
@@ -541,7 +544,7 @@ hs_status launch_layernorm_bwd_cols(hs_ctx* ctx, const void* partials, float* d_
                                     hipStream_t s) {
   if (R <= 0 || !(d_gain || d_bias || d_colsum)) return HS_OK;
   KScope scope(prof_of(ctx), KC_LN_BWD, 0.0, 0.0, s);
-  hipLaunchKernelGGL(sum_partials_kernel, dim3((H + 63) / 64, 3), dim3(256), 0, s, (const float*)partials, ln_bwd_blocks(R), (int64_t)3 * H,
+  hipLaunchKernelGGL(sum_partials_kernel, dim3((H + 63) / 64, 3), dim3(64 * SP_WAVES), 0, s, (const float*)partials, ln_bwd_blocks(R), (int64_t)3 * H,
                      (int64_t)H, H, d_gain, d_bias, d_colsum, beta);
   LAUNCH_CHECK(ctx, "layernorm_bwd finalize");
   return HS_OK;
@@ -614,7 +617,7 @@ hs_status launch_colsum(hs_ctx* ctx, int dtype, const void* x, int64_t ldx, int 
   if (dtype == HS_BF16) hipLaunchKernelGGL(colsum_kernel<bf16>, grid, dim3(256), 0, s, (const bf16*)x, ldx, R, C, rpc, (float*)partials);
   else hipLaunchKernelGGL(colsum_kernel<float>, grid, dim3(256), 0, s, (const float*)x, ldx, R, C, rpc, (float*)partials);
   LAUNCH_CHECK(ctx, "colsum");
-  hipLaunchKernelGGL(sum_partials_kernel, dim3((C + 63) / 64, 1), dim3(256), 0, s, (const float*)partials, nch, (int64_t)C, (int64_t)0, C, out,
+  hipLaunchKernelGGL(sum_partials_kernel, dim3((C + 63) / 64, 1), dim3(64 * SP_WAVES), 0, s, (const float*)partials, nch, (int64_t)C, (int64_t)0, C, out,
                      (float*)nullptr, (float*)nullptr, beta);
   LAUNCH_CHECK(ctx, "colsum finalize");
   return HS_OK;
