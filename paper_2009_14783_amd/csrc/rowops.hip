@@ -319,6 +319,58 @@ __global__ __launch_bounds__(256) void ce_loss_kernel(const float* __restrict__ 
   }
 }
 
+// The same with the whole row held in registers (one read of the logits): 1024 threads, up to eight
+// 4-element chunks per thread, so rows of up to 32768 padded columns; row stride a multiple of 4.
+// The padding columns of the logits buffer are never read; those of dlogits are written as zeros.
+constexpr int CE_NT = 1024, CE_MAXCH = 8;
+template <class T>
+__global__ __launch_bounds__(CE_NT) void ce_loss_row_kernel(const float* __restrict__ logits, int64_t ldl, const int32_t* __restrict__ labels,
+                                                           int V, T* __restrict__ dlogits, float* __restrict__ row_loss) {
+  __shared__ float sh[CE_NT / 64];
+  const int m = blockIdx.x;
+  const float* z = logits + (int64_t)m * ldl;
+  const int nch = (int)(ldl / 4);
+  float4 x[CE_MAXCH];
+  float mx = -3.0e38f;
+#pragma unroll
+  for (int c = 0; c < CE_MAXCH; ++c) {
+    const int ch = threadIdx.x + c * CE_NT, v = ch * 4;
+    x[c] = make_float4(-3.0e38f, -3.0e38f, -3.0e38f, -3.0e38f);
+    if (ch < nch) {
+      if (v + 3 < V) x[c] = *(const float4*)(z + v);
+      else {
+        if (v < V) x[c].x = z[v];
+        if (v + 1 < V) x[c].y = z[v + 1];
+        if (v + 2 < V) x[c].z = z[v + 2];
+      }
+    }
+    mx = fmaxf(mx, fmaxf(fmaxf(x[c].x, x[c].y), fmaxf(x[c].z, x[c].w)));
+  }
+  mx = block_reduce(mx, true, sh);
+  float se = 0.f;
+#pragma unroll
+  for (int c = 0; c < CE_MAXCH; ++c)     // excluded positions hold -3e38: their exponential is exactly 0
+    se += (__expf(x[c].x - mx) + __expf(x[c].y - mx)) + (__expf(x[c].z - mx) + __expf(x[c].w - mx));
+  se = block_reduce(se, false, sh);
+  const float lse = mx + logf(se);
+  int lab = labels[m];
+  lab = lab < 0 ? 0 : (lab >= V ? V - 1 : lab);
+  if (threadIdx.x == 0) row_loss[m] = lse - z[lab];
+  T* d = dlogits + (int64_t)m * ldl;
+#pragma unroll
+  for (int c = 0; c < CE_MAXCH; ++c) {
+    const int ch = threadIdx.x + c * CE_NT, v = ch * 4;
+    if (ch < nch) {
+      float4 p;
+      p.x = __expf(x[c].x - lse) - (v == lab ? 1.0f : 0.0f);
+      p.y = __expf(x[c].y - lse) - (v + 1 == lab ? 1.0f : 0.0f);
+      p.z = __expf(x[c].z - lse) - (v + 2 == lab ? 1.0f : 0.0f);
+      p.w = __expf(x[c].w - lse) - (v + 3 == lab ? 1.0f : 0.0f);
+      Vec4<T>::st(d + v, p);
+    }
+  }
+}
+
 // fixed-order sum of n floats by one block
 __global__ __launch_bounds__(256) void sum_vector_kernel(const float* __restrict__ x, int n, float* __restrict__ out) {
   __shared__ float sh[8];
@@ -679,7 +731,12 @@ hs_status launch_ce_loss(hs_ctx* ctx, int dtype, const float* logits, int64_t ld
                          float* row_loss, float* loss_sum, hipStream_t s) {
   if (M <= 0) return HS_OK;
   KScope scope(prof_of(ctx), KC_LOSS, 4.0 * M * V, (double)M * V * (4.0 + esize(dtype)), s);
-  if (dtype == HS_BF16) hipLaunchKernelGGL(ce_loss_kernel<bf16>, dim3(M), dim3(256), 0, s, logits, ldl, labels, V, (bf16*)dlogits, row_loss);
+  const bool in_regs = (ldl % 4) == 0 && ldl <= (int64_t)4 * CE_NT * CE_MAXCH && ((uintptr_t)logits % 16) == 0 &&
+                       ((uintptr_t)dlogits % 16) == 0;
+  if (in_regs) {
+    if (dtype == HS_BF16) hipLaunchKernelGGL(ce_loss_row_kernel<bf16>, dim3(M), dim3(CE_NT), 0, s, logits, ldl, labels, V, (bf16*)dlogits, row_loss);
+    else hipLaunchKernelGGL(ce_loss_row_kernel<float>, dim3(M), dim3(CE_NT), 0, s, logits, ldl, labels, V, (float*)dlogits, row_loss);
+  } else if (dtype == HS_BF16) hipLaunchKernelGGL(ce_loss_kernel<bf16>, dim3(M), dim3(256), 0, s, logits, ldl, labels, V, (bf16*)dlogits, row_loss);
   else hipLaunchKernelGGL(ce_loss_kernel<float>, dim3(M), dim3(256), 0, s, logits, ldl, labels, V, (float*)dlogits, row_loss);
   LAUNCH_CHECK(ctx, "ce_loss");
   hipLaunchKernelGGL(sum_vector_kernel, dim3(1), dim3(256), 0, s, (const float*)row_loss, M, loss_sum);
