@@ -40,6 +40,28 @@ def algorithmic_flops(model, mbs):
     return total
 
 
+def recorded_traffic(kernel_class):
+    """HBM-side bytes per launch of a GEMM class from the committed counter summary (two profiler
+    runs, FETCH_SIZE and WRITE_SIZE, scaled by the calibration copy), or None when the summary is
+    missing or was taken with a different GEMM source than the one in the tree."""
+    import hashlib
+    try:
+        text = open(os.path.join(ROOT, "profiles", "bench_bert_base_L128_hbm_traffic.md")).read()
+        src = open(os.path.join(ROOT, "paper_2009_14783_amd", "csrc", "gemm.hip"), "rb").read()
+    except OSError:
+        return None
+    sha, value = None, None
+    for line in text.splitlines():
+        f = line.split()
+        if len(f) == 2 and f[0] == "gemm_source_sha256:":
+            sha = f[1]
+        if len(f) == 3 and f[0] == "traffic_bytes_per_launch" and f[1] == kernel_class:
+            value = float(f[2])
+    if sha != hashlib.sha256(src).hexdigest():
+        return None
+    return value
+
+
 def cpu_baseline(model, wl, theta, mbs, n_seq_sample=16):
     """The oracle, as it stands, on a bounded sample of the same workload: the first
     n_seq_sample sequences of the batch through the identical step (forward, loss, backward,
@@ -168,7 +190,8 @@ def main():
         gemm_flops = sum(prof[k]["flops"] for k in gemm_classes)
         gemm_ms = sum(prof[k]["ms"] for k in gemm_classes)
         roofline = dict(bound="mfma", kernel=dominant, achieved=achieved, peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
-                        frac=achieved / PEAK_BF16_TFLOPS, traffic=None,
+                        frac=achieved / PEAK_BF16_TFLOPS, traffic=recorded_traffic(dominant),
+                        algorithmic_bytes_per_launch=dp["bytes"] / dp["launches"],
                         avg_launch_us=1e3 * dp["ms"] / dp["launches"],
                         launches_per_step=dp["launches"] / args.profile_steps,
                         all_gemms_tflops=gemm_flops / (gemm_ms * 1e-3) / 1e12,
