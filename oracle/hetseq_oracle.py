@@ -20,7 +20,11 @@ fixes, and where:
 * Section "Forward Pass": batches are formed under a max-instances or max-tokens
   criterion (see `oracle/batcher.py`).
 * Section "BERT Language Model": Adam with beta1 0.9, beta2 0.999, eps 1e-8,
-  maximum learning rate 1e-4 (`adam_step`).
+  maximum learning rate 1e-4 (`adam_step`); linear-decay schedule with 10K warm-up updates of
+  1M (`lr_linear`).
+* Section "Checkpointing": a snapshot holds the parameters, the completed steps, the optimizer
+  status with the scheduler's and the seed; training continues from it exactly (`train_loop`
+  works on such a state).
 
 The transformer encoder itself is only cited by the paper (BERT); the textbook
 definition is written out below: post-LN encoder layers, softmax attention that
@@ -34,7 +38,8 @@ Pins (tests/test_oracle_*.py): central finite differences in float64 for every
 parameter tensor; a pure-Python loop re-implementation of the forward pass; SciPy's
 logsumexp/erf; padding invariance; the concatenation invariant
 sum_i grad_i / sum_i n_i == grad(concatenated batch)/D; the paper's worked example
-with local batch sizes 2,2,1,0; Adam closed forms.
+with local batch sizes 2,2,1,0; Adam closed forms; the schedule's closed-form values at the
+paper's settings; a loop interrupted and resumed equals the uninterrupted one bit for bit.
 """
 from __future__ import annotations
 
@@ -350,3 +355,38 @@ def train_step(cfg: ModelCfg, theta, m, v, t, micro_batches, lr=1e-4, beta1=0.9,
     normalize(G, D)
     adam_step(theta, m, v, G, t, lr, beta1, beta2, eps, weight_decay)
     return loss_total / D, G, D
+
+
+# ----------------------------------------------------------------------------------------------
+# Training loop: learning-rate schedule and resumable state
+# ----------------------------------------------------------------------------------------------
+def lr_linear(t: int, max_lr: float, warmup: int, total: int) -> float:
+    """Learning rate of update number t = 1, 2, ... under the linear schedule of section "BERT
+    Language Model" (linear decay, maximum rate, the first `warmup` updates as warm-up, `total`
+    updates in all).  The paper gives the three numbers only; the usual reading is taken: the rate
+    rises linearly from 0 to max_lr over the warm-up (max_lr * t / warmup, reaching max_lr at
+    t = warmup) and then falls linearly to 0 at t = total; it is 0 beyond."""
+    if t < 1 or warmup < 0 or total < max(warmup, 1):
+        raise ValueError("lr_linear: need t >= 1 and 0 <= warmup <= total")
+    if t <= warmup:
+        return max_lr * t / warmup
+    if t >= total:
+        return 0.0
+    return max_lr * (total - t) / (total - warmup)
+
+
+def train_loop(cfg: ModelCfg, state: dict, n_steps: int, micro_batches_of, adam: dict, schedule: dict):
+    """n_steps updates from `state` = dict(theta, m, v, step) (updated in place; `step` counts the
+    completed updates, which is what section "Checkpointing" stores next to the parameters, the
+    optimizer status and the seed).  Update number t = step + 1 takes its micro-batches from
+    micro_batches_of(t) and its rate from lr_linear(t, **schedule).  Returns the reported losses."""
+    losses = []
+    for _ in range(n_steps):
+        t = state["step"] + 1
+        lr = lr_linear(t, schedule["max_lr"], schedule["warmup"], schedule["total"])
+        loss, _, _ = train_step(cfg, state["theta"], state["m"], state["v"], t, micro_batches_of(t), lr=lr,
+                                beta1=adam["beta1"], beta2=adam["beta2"], eps=adam["eps"],
+                                weight_decay=adam.get("weight_decay", 0.0))
+        state["step"] = t
+        losses.append(loss)
+    return losses

@@ -133,3 +133,11 @@ def concat_micro_batches(mbs: list) -> dict:
     return dict(ids=ids, lens=lens, mlm_pos=np.concatenate(pos).astype(np.int32),
                 mlm_label=np.concatenate(lab).astype(np.int32), n_seq=ids.shape[0],
                 n_real_tokens=int(lens.sum()))
+
+
+def step_micro_batches(seed: int, t: int, lens, L: int, vocab: int, dist: str, n_micro: int = 1) -> list:
+    """The micro-batches of update number t of a multi-step run: drawn from a generator seeded with
+    seed + t, so that a run resumed after any number of updates sees the same data as an
+    uninterrupted one (the seed is part of a checkpoint)."""
+    rng = rng_for(seed + t)
+    return [make_micro_batch(rng, lens, L, vocab, dist) for _ in range(n_micro)]

@@ -427,3 +427,79 @@ def test_train_step_reports_weighted_loss_and_updates_once():
     assert abs(loss - lb / 5) < 1e-12 * abs(lb)
     np.testing.assert_allclose(G, gb / 5, rtol=1e-9, atol=1e-13)
     np.testing.assert_allclose(th1 - th, -1e-3 * G / (np.abs(G) + 1e-8), rtol=1e-7, atol=1e-16)
+
+
+# ---------------------------------------------------------------- schedule and loop
+def test_lr_schedule_paper_settings_and_linearity():
+    rows = []
+    par = {}
+    with open(os.path.join(GOLDEN, "paper_lr_schedule.txt")) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            k, v = line.split()
+            if k in ("max_lr", "warmup", "total"):
+                par[k] = float(v) if k == "max_lr" else int(v)
+            else:
+                rows.append((int(k), float(v)))
+    assert par == dict(max_lr=1e-4, warmup=10000, total=1000000)
+    for t, want in rows:
+        got = O.lr_linear(t, **par)
+        assert got == pytest.approx(want, rel=1e-12, abs=1e-20), (t, got, want)
+    # straight lines: constant first differences inside each segment, continuous at the junction,
+    # never above the maximum, zero at and beyond the end
+    lr = np.array([O.lr_linear(t, 3e-4, 7, 40) for t in range(1, 46)])
+    up, down = np.diff(lr[:7]), np.diff(lr[6:40])
+    assert np.allclose(up, 3e-4 / 7, rtol=1e-12) and np.allclose(down, -3e-4 / 33, rtol=1e-12)
+    assert lr[6] == 3e-4 and lr.max() == 3e-4 and np.all(lr[39:] == 0.0)
+    # no warm-up: the first update already decays from the maximum
+    assert O.lr_linear(1, 1.0, 0, 10) == pytest.approx(0.9)
+    with pytest.raises(ValueError):
+        O.lr_linear(0, 1.0, 2, 10)
+
+
+def test_train_loop_wires_schedule_and_update_number():
+    cfg = MICRO
+    adam = dict(beta1=0.9, beta2=0.999, eps=1e-12)
+    sched = dict(max_lr=1e-3, warmup=4, total=12)
+    batches = lambda t: [micro_batch(cfg, [8, 5, 3], 8, 1000 + t)]
+    th0 = micro_theta(cfg, 3)
+    st = dict(theta=th0.copy(), m=np.zeros_like(th0), v=np.zeros_like(th0), step=0)
+    O.train_loop(cfg, st, 1, batches, adam, sched)
+    # First Adam update with bias correction moves every parameter with a non-zero gradient by
+    # exactly the learning rate (m_hat / sqrt(v_hat) = +-1): here lr(1) = max_lr / warmup.
+    step = np.abs(st["theta"] - th0)
+    moved = step > 0
+    assert moved.sum() > 0.9 * th0.size
+    lr1 = 1e-3 / 4
+    assert np.all(step <= lr1 * (1 + 1e-9))                      # (entries with |g| near eps move a little less)
+    assert np.mean(np.abs(step[moved] - lr1) <= 1e-6 * lr1) > 0.99
+    assert st["step"] == 1
+    # a zero maximum rate changes nothing but still counts updates
+    st2 = dict(theta=th0.copy(), m=np.zeros_like(th0), v=np.zeros_like(th0), step=0)
+    O.train_loop(cfg, st2, 3, batches, adam, dict(max_lr=0.0, warmup=4, total=12))
+    assert np.array_equal(st2["theta"], th0) and st2["step"] == 3
+    # the loss on a repeated batch goes down over a few updates
+    st3 = dict(theta=th0.copy(), m=np.zeros_like(th0), v=np.zeros_like(th0), step=0)
+    same = lambda t: [micro_batch(cfg, [8, 5, 3], 8, 77)]
+    losses = O.train_loop(cfg, st3, 8, same, adam, dict(max_lr=3e-2, warmup=2, total=40))
+    assert losses[-1] < losses[0] - 0.1
+
+
+def test_train_loop_resumed_equals_uninterrupted():
+    cfg = MICRO
+    adam = dict(beta1=0.9, beta2=0.999, eps=1e-8)
+    sched = dict(max_lr=2e-3, warmup=3, total=10)
+    batches = lambda t: synth.step_micro_batches(42, t, [8, 6, 2], 8, cfg.vocab, "uniform", n_micro=2)
+    th0 = micro_theta(cfg, 9, dtype=np.float32)
+    full = dict(theta=th0.copy(), m=np.zeros_like(th0), v=np.zeros_like(th0), step=0)
+    l_full = O.train_loop(cfg, full, 7, batches, adam, sched)
+    part = dict(theta=th0.copy(), m=np.zeros_like(th0), v=np.zeros_like(th0), step=0)
+    l_a = O.train_loop(cfg, part, 3, batches, adam, sched)
+    snap = {k: (v.copy() if isinstance(v, np.ndarray) else v) for k, v in part.items()}   # the checkpoint
+    l_b = O.train_loop(cfg, snap, 4, batches, adam, sched)
+    assert l_a + l_b == l_full
+    for k in ("theta", "m", "v"):
+        assert np.array_equal(snap[k], full[k])
+    assert snap["step"] == full["step"] == 7
