@@ -91,6 +91,42 @@ size_t hs_acts_bytes(const hs_model_cfg* cfg, int32_t B, int32_t L, int32_t M);
  * maximum over the three calls, so one buffer serves all. */
 size_t hs_workspace_bytes(const hs_model_cfg* cfg, int32_t B, int32_t L, int32_t M);
 
+/* ---- learning-rate schedule (host) ---------------------------------------------------------
+ * Section "BERT Language Model": linear-decay schedule with a maximum rate, `warmup` warm-up
+ * updates and `total` updates in all.  Returns the rate of update number t (1-based):
+ * max_lr * t / warmup while t <= warmup, then max_lr * (total - t) / (total - warmup), and 0 from
+ * t = total on.  No device work.  Returns NaN (and records an error text) when t < 1, warmup < 0,
+ * total < max(warmup, 1), or max_lr is negative or not finite. */
+double hs_lr_linear(int64_t t, double max_lr, int64_t warmup, int64_t total);
+
+/* ---- checkpoints (host files) -------------------------------------------------------------
+ * Section "Checkpointing": a snapshot holds the model parameters, the completed epochs and steps,
+ * the optimizer status including the scheduler's, and the random seed, so that training continues
+ * exactly where it stopped.  The file is: the magic "HSCKPT01", this header, the three fp32 arrays
+ * w, m, v of n_params elements each, and a 64-bit FNV-1a checksum of everything before it
+ * (little-endian, no padding beyond the struct's own).
+ * All pointers are HOST pointers; the caller copies device state to the host first.  Nothing is
+ * kept after a call returns.  A failed write leaves no file under `path` (it is written under a
+ * temporary name and renamed). */
+typedef struct {
+  hs_model_cfg cfg;        /* the model the state belongs to */
+  int64_t n_params;        /* = hs_param_count(&cfg) */
+  int64_t epoch, step;     /* completed epochs and completed updates (Adam's t of the last update) */
+  uint64_t seed;           /* seed of the run's random processes */
+  double max_lr;           /* scheduler status: the three numbers of hs_lr_linear */
+  int64_t warmup, total;
+  double beta1, beta2, eps, weight_decay;   /* optimizer hyper-parameters (its moments are m and v) */
+} hs_ckpt_header;
+/* HS_ERR_INVALID_ARG: NULL argument, n_params != hs_param_count(&cfg); HS_ERR_STATE: the file
+ * cannot be created or written completely. */
+hs_status hs_checkpoint_write(const char* path, const hs_ckpt_header* header, const float* w, const float* m, const float* v);
+/* Reads and validates magic and header only. */
+hs_status hs_checkpoint_read_header(const char* path, hs_ckpt_header* header_out);
+/* Reads the arrays into w, m, v (each n elements, n must equal the file's n_params) and verifies the
+ * checksum; HS_ERR_STATE on a missing, truncated or corrupted file (the arrays may then be partly
+ * written), HS_ERR_SHAPE when n does not match. */
+hs_status hs_checkpoint_read(const char* path, hs_ckpt_header* header_out, float* w, float* m, float* v, size_t n);
+
 /* ---- batch formation (host, integer) ----------------------------------------------------
  * Section "Forward Pass": batches are formed under a max-instances or max-tokens criterion; the
  * last batch may be partially filled (section "Optimizer and Learning Rate Scheduler").

@@ -30,6 +30,12 @@ class hs_profile_entry(C.Structure):
                 ("bytes", C.c_double)]
 
 
+class hs_ckpt_header(C.Structure):
+    _fields_ = [("cfg", hs_model_cfg), ("n_params", C.c_int64), ("epoch", C.c_int64), ("step", C.c_int64),
+                ("seed", C.c_uint64), ("max_lr", C.c_double), ("warmup", C.c_int64), ("total", C.c_int64),
+                ("beta1", C.c_double), ("beta2", C.c_double), ("eps", C.c_double), ("weight_decay", C.c_double)]
+
+
 class HsError(RuntimeError):
     def __init__(self, status, msg):
         super().__init__(f"{STATUS.get(status, status)}: {msg}")
@@ -55,6 +61,10 @@ _SIGNATURES = {
     "hs_grad_accum_normalize": (_I32, [_P, _P, _SZ, _I32, _D, _P]),
     "hs_adam_step": (_I32, [_P, _P, _P, _P, _P, _SZ, _D, _D, _D, _D, _D, _I64, _P]),
     "hs_cast_params": (_I32, [_P, _P, _SZ, _I32, _P]),
+    "hs_lr_linear": (_D, [_I64, _D, _I64, _I64]),
+    "hs_checkpoint_write": (_I32, [C.c_char_p, C.POINTER(hs_ckpt_header), _P, _P, _P]),
+    "hs_checkpoint_read_header": (_I32, [C.c_char_p, C.POINTER(hs_ckpt_header)]),
+    "hs_checkpoint_read": (_I32, [C.c_char_p, C.POINTER(hs_ckpt_header), _P, _P, _P, _SZ]),
     "hs_profile_enable": (_I32, [_P, _I32]),
     "hs_profile_read": (_I32, [_P, C.POINTER(hs_profile_entry), C.POINTER(_I32)]),
     "hs_op_gemm": (_I32, [_I32, _I32, _I32, _I32, _I32, _I32, _P, _I64, _P, _I64, _P, _I64, _I32, _F, _P, _I32, _P, _I64, _P, _P, _SZ, _P]),
@@ -116,6 +126,36 @@ def make_cfg(n_layers, hidden, n_heads, ffn, vocab, max_pos, ln_eps=1e-12, compu
 
 
 # ---- host-only calls ---------------------------------------------------------------------
+def hs_lr_linear(t, max_lr, warmup, total) -> float:
+    lr = lib().hs_lr_linear(int(t), float(max_lr), int(warmup), int(total))
+    if lr != lr:
+        raise HsError(1, (lib().hs_last_error(None) or b"").decode())
+    return lr
+
+
+def hs_checkpoint_write(path: str, header: hs_ckpt_header, w: np.ndarray, m: np.ndarray, v: np.ndarray):
+    """w, m, v: contiguous float32 HOST arrays of header.n_params elements."""
+    for a in (w, m, v):
+        assert isinstance(a, np.ndarray) and a.dtype == np.float32 and a.flags["C_CONTIGUOUS"] and a.size == header.n_params
+    _check(lib().hs_checkpoint_write(path.encode(), C.byref(header), _ptr(w), _ptr(m), _ptr(v)))
+
+
+def hs_checkpoint_read_header(path: str) -> hs_ckpt_header:
+    h = hs_ckpt_header()
+    _check(lib().hs_checkpoint_read_header(path.encode(), C.byref(h)))
+    return h
+
+
+def hs_checkpoint_read(path: str, w: np.ndarray, m: np.ndarray, v: np.ndarray) -> hs_ckpt_header:
+    """Fills the contiguous float32 HOST arrays w, m, v (same size) and returns the header."""
+    for a in (w, m, v):
+        assert isinstance(a, np.ndarray) and a.dtype == np.float32 and a.flags["C_CONTIGUOUS"] and a.size == w.size
+    h = hs_ckpt_header()
+    _check(lib().hs_checkpoint_read(path.encode(), C.byref(h), _ptr(w), _ptr(m), _ptr(v), w.size))
+    return h
+
+
+
 def hs_ctx_create(cfg: hs_model_cfg):
     out = _P()
     _check(lib().hs_ctx_create(C.byref(cfg), C.byref(out)))

@@ -232,3 +232,104 @@ hs_status hs_make_batches(const int32_t* lengths, int64_t n, int32_t bucket_widt
 }
 
 }  // extern "C"
+
+// ---- learning-rate schedule and checkpoints (host only) ---------------------------------------
+#include <cmath>
+#include <cstdio>
+#include <limits>
+
+extern "C" double hs_lr_linear(int64_t t, double max_lr, int64_t warmup, int64_t total) {
+  if (t < 1 || warmup < 0 || total < 1 || total < warmup || !(max_lr >= 0.0) || !std::isfinite(max_lr)) {
+    hs_fail(nullptr, HS_ERR_INVALID_ARG, "hs_lr_linear: need t >= 1, 0 <= warmup <= total, total >= 1 and a finite max_lr >= 0");
+    return std::numeric_limits<double>::quiet_NaN();
+  }
+  if (t <= warmup) return max_lr * (double)t / (double)warmup;
+  if (t >= total) return 0.0;
+  return max_lr * (double)(total - t) / (double)(total - warmup);
+}
+
+namespace {
+const char kCkptMagic[8] = {'H', 'S', 'C', 'K', 'P', 'T', '0', '1'};
+
+struct Fnv {
+  uint64_t h = 1469598103934665603ull;
+  void add(const void* p, size_t n) {
+    const unsigned char* b = (const unsigned char*)p;
+    for (size_t i = 0; i < n; ++i) { h ^= b[i]; h *= 1099511628211ull; }
+  }
+};
+
+struct File {
+  FILE* f;
+  explicit File(FILE* fp) : f(fp) {}
+  ~File() { if (f) fclose(f); }
+};
+
+bool header_ok(const hs_ckpt_header& h, std::string* why) {
+  if (!hs_cfg_valid(&h.cfg, why)) return false;
+  if (h.n_params != (int64_t)hs_param_count(&h.cfg)) { *why = "n_params does not match the model"; return false; }
+  if (h.epoch < 0 || h.step < 0) { *why = "negative epoch or step"; return false; }
+  return true;
+}
+}  // namespace
+
+extern "C" hs_status hs_checkpoint_write(const char* path, const hs_ckpt_header* header, const float* w, const float* m, const float* v) {
+  if (!path || !header || !w || !m || !v) return hs_fail(nullptr, HS_ERR_INVALID_ARG, "hs_checkpoint_write: NULL argument");
+  std::string why;
+  if (!header_ok(*header, &why)) return hs_fail(nullptr, HS_ERR_INVALID_ARG, "hs_checkpoint_write: " + why);
+  const std::string tmp = std::string(path) + ".tmp";
+  const size_t bytes = (size_t)header->n_params * sizeof(float);
+  Fnv sum;
+  bool ok = false;
+  {
+    File out(fopen(tmp.c_str(), "wb"));
+    if (!out.f) return hs_fail(nullptr, HS_ERR_STATE, "hs_checkpoint_write: cannot create " + tmp);
+    auto put = [&](const void* p, size_t n) { sum.add(p, n); return fwrite(p, 1, n, out.f) == n; };
+    ok = put(kCkptMagic, sizeof(kCkptMagic)) && put(header, sizeof(*header)) && put(w, bytes) && put(m, bytes) && put(v, bytes);
+    const uint64_t h = sum.h;
+    ok = ok && fwrite(&h, 1, sizeof(h), out.f) == sizeof(h) && fflush(out.f) == 0;
+  }
+  if (!ok || rename(tmp.c_str(), path) != 0) {
+    remove(tmp.c_str());
+    return hs_fail(nullptr, HS_ERR_STATE, std::string("hs_checkpoint_write: could not write ") + path);
+  }
+  return HS_OK;
+}
+
+static hs_status read_header(FILE* f, const char* path, hs_ckpt_header* h, Fnv* sum) {
+  char magic[8];
+  if (fread(magic, 1, 8, f) != 8 || memcmp(magic, kCkptMagic, 8) != 0)
+    return hs_fail(nullptr, HS_ERR_STATE, std::string("checkpoint: bad magic in ") + path);
+  if (fread(h, 1, sizeof(*h), f) != sizeof(*h)) return hs_fail(nullptr, HS_ERR_STATE, std::string("checkpoint: truncated header in ") + path);
+  std::string why;
+  if (!header_ok(*h, &why)) return hs_fail(nullptr, HS_ERR_STATE, std::string("checkpoint: ") + why);
+  if (sum) { sum->add(magic, 8); sum->add(h, sizeof(*h)); }
+  return HS_OK;
+}
+
+extern "C" hs_status hs_checkpoint_read_header(const char* path, hs_ckpt_header* header_out) {
+  if (!path || !header_out) return hs_fail(nullptr, HS_ERR_INVALID_ARG, "hs_checkpoint_read_header: NULL argument");
+  File in(fopen(path, "rb"));
+  if (!in.f) return hs_fail(nullptr, HS_ERR_STATE, std::string("checkpoint: cannot open ") + path);
+  return read_header(in.f, path, header_out, nullptr);
+}
+
+extern "C" hs_status hs_checkpoint_read(const char* path, hs_ckpt_header* header_out, float* w, float* m, float* v, size_t n) {
+  if (!path || !header_out || !w || !m || !v) return hs_fail(nullptr, HS_ERR_INVALID_ARG, "hs_checkpoint_read: NULL argument");
+  File in(fopen(path, "rb"));
+  if (!in.f) return hs_fail(nullptr, HS_ERR_STATE, std::string("checkpoint: cannot open ") + path);
+  Fnv sum;
+  hs_status st = read_header(in.f, path, header_out, &sum);
+  if (st != HS_OK) return st;
+  if ((int64_t)n != header_out->n_params) return hs_fail(nullptr, HS_ERR_SHAPE, "hs_checkpoint_read: array size does not match the file");
+  const size_t bytes = n * sizeof(float);
+  float* dst[3] = {w, m, v};
+  for (float* d : dst) {
+    if (fread(d, 1, bytes, in.f) != bytes) return hs_fail(nullptr, HS_ERR_STATE, std::string("checkpoint: truncated file ") + path);
+    sum.add(d, bytes);
+  }
+  uint64_t stored = 0;
+  if (fread(&stored, 1, sizeof(stored), in.f) != sizeof(stored) || stored != sum.h)
+    return hs_fail(nullptr, HS_ERR_STATE, std::string("checkpoint: checksum mismatch in ") + path);
+  return HS_OK;
+}

@@ -135,3 +135,44 @@ class Worker:
 
     def reported_loss(self, D) -> float:
         return float(self.loss_buf.sum().item()) / D
+
+    # ---- multi-step loop: schedule and checkpoints (call order only, like the rest of this class) ----
+    def train(self, n_steps: int, micro_batches_of, adam: dict, schedule: dict) -> list:
+        """n_steps updates; update number t = completed updates + 1 takes its micro-batches (host dicts)
+        from micro_batches_of(t) and its learning rate from hs_lr_linear(t, **schedule).  Returns the
+        reported loss of every update."""
+        losses = []
+        for _ in range(n_steps):
+            t = self.t + 1
+            lr = hs.hs_lr_linear(t, schedule["max_lr"], schedule["warmup"], schedule["total"])
+            batches = [None if (mb is None or mb.get("dummy", False)) else self.upload(mb) for mb in micro_batches_of(t)]
+            D = self.train_step(batches, dict(adam, lr=lr))
+            losses.append(self.reported_loss(D))
+        return losses
+
+    def save_checkpoint(self, path: str, adam: dict, schedule: dict, seed: int, epoch: int = 0):
+        """Everything needed to continue exactly: parameters, Adam moments, completed updates, the
+        scheduler's numbers, the optimizer's hyper-parameters and the seed."""
+        h = hs.hs_ckpt_header()
+        h.cfg = self.cfg
+        h.n_params, h.epoch, h.step, h.seed = self.P, epoch, self.t, seed
+        h.max_lr, h.warmup, h.total = schedule["max_lr"], schedule["warmup"], schedule["total"]
+        h.beta1, h.beta2, h.eps, h.weight_decay = adam["beta1"], adam["beta2"], adam["eps"], adam.get("weight_decay", 0.0)
+        torch.cuda.synchronize(self.device)
+        hs.hs_checkpoint_write(path, h, self.w.cpu().numpy(), self.m.cpu().numpy(), self.v.cpu().numpy())
+
+    def load_checkpoint(self, path: str):
+        """Restores a state written by save_checkpoint; returns (adam, schedule, seed, epoch)."""
+        head = hs.hs_checkpoint_read_header(path)
+        for f, _ in hs.hs_model_cfg._fields_:
+            if f != "compute" and getattr(head.cfg, f) != getattr(self.cfg, f):
+                raise ValueError(f"checkpoint is for another model ({f})")
+        w, m, v = (np.empty(self.P, dtype=np.float32) for _ in range(3))
+        head = hs.hs_checkpoint_read(path, w, m, v)
+        self.w.copy_(torch.from_numpy(w)); self.m.copy_(torch.from_numpy(m)); self.v.copy_(torch.from_numpy(v))
+        if self.w_lowp is not None:
+            hs.hs_cast_params(self.w, self.w_lowp, self.P, hs.HS_BF16)
+        self.t = int(head.step)
+        adam = dict(beta1=head.beta1, beta2=head.beta2, eps=head.eps, weight_decay=head.weight_decay)
+        schedule = dict(max_lr=head.max_lr, warmup=int(head.warmup), total=int(head.total))
+        return adam, schedule, int(head.seed), int(head.epoch)

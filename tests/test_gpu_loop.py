@@ -1,0 +1,82 @@
+"""Multi-step training on the GPU against the oracle's loop: learning-rate schedule, fresh data every
+update, checkpoint and exact resume (section "Checkpointing", section "BERT Language Model")."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import hetseq_oracle as O
+from paper_2009_14783_amd import binding as hs
+from paper_2009_14783_amd import synth
+from paper_2009_14783_amd.step import Worker
+
+pytestmark = pytest.mark.gpu
+
+TINY = synth.MODELS["tiny"]
+ADAM = dict(beta1=0.9, beta2=0.999, eps=1e-6)
+LENS = [16, 32, 48, 64]
+
+
+def batches_of(seed, n_micro=1):
+    return lambda t: synth.step_micro_batches(seed, t, LENS, 64, TINY["vocab"], "uniform", n_micro)
+
+
+def test_loss_curve_of_100_updates_follows_oracle_fp32():
+    cfg = hs.make_cfg(**TINY, compute=hs.HS_FP32)
+    theta = synth.init_params(hs.hs_param_layout(cfg), 4321)
+    sched = dict(max_lr=1e-3, warmup=10, total=100)
+    st = dict(theta=theta.copy(), m=np.zeros_like(theta), v=np.zeros_like(theta), step=0)
+    want = O.train_loop(O.ModelCfg(**TINY), st, 100, batches_of(99), ADAM, sched)
+    wk = Worker(TINY, "fp32", theta)
+    got = wk.train(100, batches_of(99), ADAM, sched)
+    torch.cuda.synchronize()
+    want, got = np.array(want), np.array(got)
+    rel = np.abs(got - want) / np.abs(want)
+    print(f"loss {want[0]:.4f} -> {want[-1]:.4f}; max relative deviation over 100 updates {rel.max():.2e} (first 10: {rel[:10].max():.2e})")
+    # every point of the curve is held to the single-step bar of fp32 mode
+    assert rel.max() < 1e-4
+    w = wk.w.cpu().numpy()
+    assert np.linalg.norm(w - st["theta"]) / np.linalg.norm(st["theta"] - theta) < 2e-2   # same displacement
+    assert wk.t == st["step"] == 100
+    wk.close()
+
+
+@pytest.mark.parametrize("compute", ["fp32", "bf16"])
+def test_resume_from_checkpoint_is_bit_exact(tmp_path, compute):
+    cfg = hs.make_cfg(**TINY)
+    theta = synth.init_params(hs.hs_param_layout(cfg), 77)
+    sched = dict(max_lr=2e-3, warmup=3, total=12)
+    seed = 2024
+    data = lambda t: (synth.step_micro_batches(seed, t, LENS, 64, TINY["vocab"], "uniform", 2) + [None])   # a worker without data too
+    full = Worker(TINY, compute, theta)
+    l_full = full.train(9, data, ADAM, sched)
+    a = Worker(TINY, compute, theta)
+    l_a = a.train(4, data, ADAM, sched)
+    path = str(tmp_path / "run.hsckpt")
+    a.save_checkpoint(path, ADAM, sched, seed, epoch=1)
+    a.close()
+    b = Worker(TINY, compute, np.zeros_like(theta))        # a fresh process would start like this
+    adam, sched_b, seed_b, epoch = b.load_checkpoint(path)
+    assert (seed_b, epoch, b.t) == (seed, 1, 4) and sched_b == sched
+    assert adam == dict(ADAM, weight_decay=0.0)
+    data_b = lambda t: (synth.step_micro_batches(seed_b, t, LENS, 64, TINY["vocab"], "uniform", 2) + [None])
+    l_b = b.train(5, data_b, adam, sched_b)
+    torch.cuda.synchronize()
+    assert l_a + l_b == l_full
+    for name in ("w", "m", "v"):
+        x, y = getattr(full, name).cpu().numpy(), getattr(b, name).cpu().numpy()
+        assert np.array_equal(x.view(np.uint32), y.view(np.uint32)), name
+    if compute == "bf16":
+        assert torch.equal(full.w_lowp, b.w_lowp)
+    full.close(); b.close()
+
+
+def test_checkpoint_of_another_model_is_refused(tmp_path):
+    theta = synth.init_params(hs.hs_param_layout(hs.make_cfg(**TINY)), 1)
+    wk = Worker(TINY, "fp32", theta)
+    path = str(tmp_path / "x.hsckpt")
+    wk.save_checkpoint(path, ADAM, dict(max_lr=1e-3, warmup=1, total=2), seed=0)
+    other = dict(TINY, ffn=256)
+    wo = Worker(other, "fp32", synth.init_params(hs.hs_param_layout(hs.make_cfg(**other)), 1))
+    with pytest.raises(ValueError):
+        wo.load_checkpoint(path)
+    wk.close(); wo.close()
