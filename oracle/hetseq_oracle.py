@@ -22,6 +22,11 @@ fixes, and where:
 * Section "BERT Language Model": Adam with beta1 0.9, beta2 0.999, eps 1e-8,
   maximum learning rate 1e-4 (`adam_step`); linear-decay schedule with 10K warm-up updates of
   1M (`lr_linear`).
+* Section "Transformer Translation Model" trains with dropout 0.1 and section "Checkpointing" keeps
+  the random seed in the snapshot; the cited BERT model drops, with the same rate, its embedding
+  output, attention probabilities, attention output and feed-forward output.  `encoder_forward(...,
+  drop)` does so with a counter-based generator, so that a mask is a pure function of (seed,
+  stream, site, element) and both sides of a comparison can produce it.
 * Section "Checkpointing": a snapshot holds the parameters, the completed steps, the optimizer
   status with the scheduler's and the seed; training continues from it exactly (`train_loop`
   works on such a state).
@@ -39,7 +44,9 @@ parameter tensor; a pure-Python loop re-implementation of the forward pass; SciP
 logsumexp/erf; padding invariance; the concatenation invariant
 sum_i grad_i / sum_i n_i == grad(concatenated batch)/D; the paper's worked example
 with local batch sizes 2,2,1,0; Adam closed forms; the schedule's closed-form values at the
-paper's settings; a loop interrupted and resumed equals the uninterrupted one bit for bit.
+paper's settings; a loop interrupted and resumed equals the uninterrupted one bit for bit;
+the generator's published known-answer vectors, mask frequency and independence, unbiasedness,
+and finite differences through all four kinds of dropout sites.
 """
 from __future__ import annotations
 
@@ -149,10 +156,82 @@ def layer_norm_bwd(dy, cache, gain):
 
 
 # --------------------------------------------------------------------------------------
+# dropout with a counter-based generator
+# --------------------------------------------------------------------------------------
+# The generator is Philox4x32 with 10 rounds (Salmon, Moraes, Dror, Shaw: "Parallel random numbers:
+# as easy as 1, 2, 3", SC'11), written from its published definition: a 4 x 32-bit counter and a
+# 2 x 32-bit key go through 10 rounds; a round replaces (c0, c1, c2, c3) by
+# (hi(M1*c2) ^ c1 ^ k0, lo(M1*c2), hi(M0*c0) ^ c3 ^ k1, lo(M0*c0)) and the key is bumped by the two
+# Weyl constants between rounds.
+PHILOX_M0, PHILOX_M1 = 0xD2511F53, 0xCD9E8D57
+PHILOX_W0, PHILOX_W1 = 0x9E3779B9, 0xBB67AE85
+
+
+def philox4x32_10(counter: np.ndarray, key) -> np.ndarray:
+    """counter: uint32 [..., 4]; key: two 32-bit integers.  Returns uint32 [..., 4]."""
+    c = [counter[..., j].astype(np.uint64) for j in range(4)]
+    k0, k1 = np.uint64(key[0] & 0xFFFFFFFF), np.uint64(key[1] & 0xFFFFFFFF)
+    mask = np.uint64(0xFFFFFFFF)
+    for _ in range(10):
+        p0 = np.uint64(PHILOX_M0) * c[0]
+        p1 = np.uint64(PHILOX_M1) * c[2]
+        c = [(p1 >> np.uint64(32)) ^ c[1] ^ k0, p1 & mask, (p0 >> np.uint64(32)) ^ c[3] ^ k1, p0 & mask]
+        k0 = (k0 + np.uint64(PHILOX_W0)) & mask
+        k1 = (k1 + np.uint64(PHILOX_W1)) & mask
+    return np.stack(c, axis=-1).astype(np.uint32)
+
+
+def dropout_keep(drop: dict, site: int, n: int) -> np.ndarray:
+    """Which of the n elements of dropout site `site` survive.  Element e uses word e % 4 of the block
+    with counter (e // 4 low, e // 4 high, site, drop['stream']) under the key (seed low, seed high);
+    it is dropped when that word is below floor(p * 2^32).  `stream` tells apart the micro-batches
+    and updates of a run; the seed is the run's (section "Checkpointing" keeps it in the snapshot)."""
+    groups = (n + 3) // 4
+    g = np.arange(groups, dtype=np.uint64)
+    counter = np.empty((groups, 4), dtype=np.uint32)
+    counter[:, 0] = (g & np.uint64(0xFFFFFFFF)).astype(np.uint32)
+    counter[:, 1] = (g >> np.uint64(32)).astype(np.uint32)
+    counter[:, 2] = np.uint32(site)
+    counter[:, 3] = np.uint32(drop["stream"] & 0xFFFFFFFF)
+    seed = int(drop["seed"])
+    words = philox4x32_10(counter, (seed & 0xFFFFFFFF, (seed >> 32) & 0xFFFFFFFF)).reshape(-1)[:n]
+    thr = np.uint32(min(int(math.floor(drop["p"] * 4294967296.0)), 0xFFFFFFFF))
+    return words >= thr
+
+
+def _drop(x: np.ndarray, drop, site: int):
+    """Inverted dropout: survivors are scaled by 1 / (1 - p).  Returns (y, factor) with y = x * factor."""
+    if drop is None or drop["p"] <= 0.0:
+        return x, None
+    keep = dropout_keep(drop, site, x.size).reshape(x.shape)
+    factor = keep.astype(x.dtype) * x.dtype.type(1.0 / (1.0 - drop["p"]))
+    return x * factor, factor
+
+
+def site_embedding() -> int:
+    return 0
+
+
+def site_attention_prob(layer: int) -> int:
+    return 1 + 3 * layer
+
+
+def site_attention_out(layer: int) -> int:
+    return 2 + 3 * layer
+
+
+def site_ffn_out(layer: int) -> int:
+    return 3 + 3 * layer
+
+
+# --------------------------------------------------------------------------------------
 # forward: encoder, then masked-LM head and loss SUM
 # --------------------------------------------------------------------------------------
-def encoder_forward(cfg: ModelCfg, theta: np.ndarray, ids: np.ndarray, lens: np.ndarray):
-    """ids [B, L] int, lens [B] (each >= 1).  Returns hidden [B, L, H] and a cache."""
+def encoder_forward(cfg: ModelCfg, theta: np.ndarray, ids: np.ndarray, lens: np.ndarray, drop=None):
+    """ids [B, L] int, lens [B] (each >= 1).  Returns hidden [B, L, H] and a cache.
+    drop = dict(p, seed, stream) switches on dropout at BERT's four kinds of sites: the embedding
+    output, the attention probabilities, the attention output and the feed-forward output (the last
+    two before the residual is added)."""
     P = param_views(cfg, theta)
     dt = theta.dtype
     B, L = ids.shape
@@ -162,7 +241,8 @@ def encoder_forward(cfg: ModelCfg, theta: np.ndarray, ids: np.ndarray, lens: np.
 
     e = P["emb.word"][ids] + P["emb.pos"][:L][None, :, :]
     x, c_emb = layer_norm_fwd(e, P["emb.ln.g"], P["emb.ln.b"], cfg.ln_eps)
-    cache = {"ids": ids, "lens": np.asarray(lens), "valid": valid, "emb_ln": c_emb, "layers": []}
+    x, f_emb = _drop(x, drop, site_embedding())
+    cache = {"ids": ids, "lens": np.asarray(lens), "valid": valid, "emb_ln": c_emb, "f_emb": f_emb, "layers": []}
     scale = dt.type(1.0 / math.sqrt(d))
     for i in range(cfg.n_layers):
         p = f"l{i}."
@@ -173,15 +253,18 @@ def encoder_forward(cfg: ModelCfg, theta: np.ndarray, ids: np.ndarray, lens: np.
         s_max = s.max(axis=-1, keepdims=True)
         pexp = np.exp(s - s_max)
         prob = pexp / pexp.sum(axis=-1, keepdims=True)
-        ctx = (prob @ v).transpose(0, 2, 1, 3).reshape(B, L, H)
-        y1 = x + ctx @ P[p + "o.w"].T + P[p + "o.b"]
+        probd, f_prob = _drop(prob, drop, site_attention_prob(i))
+        ctx = (probd @ v).transpose(0, 2, 1, 3).reshape(B, L, H)
+        ao, f_ao = _drop(ctx @ P[p + "o.w"].T + P[p + "o.b"], drop, site_attention_out(i))
+        y1 = x + ao
         x1, c_ln1 = layer_norm_fwd(y1, P[p + "ln1.g"], P[p + "ln1.b"], cfg.ln_eps)
         hpre = x1 @ P[p + "ffn1.w"].T + P[p + "ffn1.b"]
         h = gelu(hpre)
-        y2 = x1 + h @ P[p + "ffn2.w"].T + P[p + "ffn2.b"]
+        fo, f_fo = _drop(h @ P[p + "ffn2.w"].T + P[p + "ffn2.b"], drop, site_ffn_out(i))
+        y2 = x1 + fo
         x2, c_ln2 = layer_norm_fwd(y2, P[p + "ln2.g"], P[p + "ln2.b"], cfg.ln_eps)
-        cache["layers"].append(dict(x=x, q=q, k=k, v=v, prob=prob, ctx=ctx, ln1=c_ln1, x1=x1,
-                                    hpre=hpre, h=h, ln2=c_ln2))
+        cache["layers"].append(dict(x=x, q=q, k=k, v=v, prob=prob, probd=probd, ctx=ctx, ln1=c_ln1, x1=x1,
+                                    hpre=hpre, h=h, ln2=c_ln2, f_prob=f_prob, f_ao=f_ao, f_fo=f_fo))
         x = x2
     return x, cache
 
@@ -254,10 +337,11 @@ def encoder_backward(cfg: ModelCfg, theta: np.ndarray, cache, d_hidden: np.ndarr
         dy2, dg_, db_ = layer_norm_bwd(dx, c["ln2"], P[p + "ln2.g"])
         G[p + "ln2.g"] += dg_
         G[p + "ln2.b"] += db_
-        dy2f = dy2.reshape(T, H)
+        dfo = dy2 if c["f_fo"] is None else dy2 * c["f_fo"]        # through the dropout of the FFN output
+        dy2f = dfo.reshape(T, H)
         G[p + "ffn2.b"] += dy2f.sum(axis=0)
         G[p + "ffn2.w"] += dy2f.T @ c["h"].reshape(T, -1)
-        dh = dy2 @ P[p + "ffn2.w"]
+        dh = dfo @ P[p + "ffn2.w"]
         dhpre = dh * gelu_grad(c["hpre"])
         dhpf = dhpre.reshape(T, -1)
         G[p + "ffn1.b"] += dhpf.sum(axis=0)
@@ -266,13 +350,16 @@ def encoder_backward(cfg: ModelCfg, theta: np.ndarray, cache, d_hidden: np.ndarr
         dy1, dg_, db_ = layer_norm_bwd(dx1, c["ln1"], P[p + "ln1.g"])
         G[p + "ln1.g"] += dg_
         G[p + "ln1.b"] += db_
-        dy1f = dy1.reshape(T, H)
+        dao = dy1 if c["f_ao"] is None else dy1 * c["f_ao"]        # through the dropout of the attention output
+        dy1f = dao.reshape(T, H)
         G[p + "o.b"] += dy1f.sum(axis=0)
         G[p + "o.w"] += dy1f.T @ c["ctx"].reshape(T, H)
-        dctx = (dy1 @ P[p + "o.w"]).reshape(B, L, A, d).transpose(0, 2, 1, 3)     # [B, A, L, d]
+        dctx = (dao @ P[p + "o.w"]).reshape(B, L, A, d).transpose(0, 2, 1, 3)     # [B, A, L, d]
         prob, q, k, v = c["prob"], c["q"], c["k"], c["v"]
-        dv = prob.transpose(0, 1, 3, 2) @ dctx
+        dv = c["probd"].transpose(0, 1, 3, 2) @ dctx
         dprob = dctx @ v.transpose(0, 1, 3, 2)
+        if c["f_prob"] is not None:
+            dprob = dprob * c["f_prob"]                           # through the dropout of the probabilities
         ds = prob * (dprob - (dprob * prob).sum(axis=-1, keepdims=True))          # softmax backward
         dq = (ds @ k) * scale
         dk = (ds.transpose(0, 1, 3, 2) @ q) * scale
@@ -281,6 +368,8 @@ def encoder_backward(cfg: ModelCfg, theta: np.ndarray, cache, d_hidden: np.ndarr
         G[p + "qkv.b"] += dqkvf.sum(axis=0)
         G[p + "qkv.w"] += dqkvf.T @ c["x"].reshape(T, H)
         dx = dy1 + dqkv @ P[p + "qkv.w"]
+    if cache["f_emb"] is not None:
+        dx = dx * cache["f_emb"]
     de, dg_, db_ = layer_norm_bwd(dx, cache["emb_ln"], P["emb.ln.g"])
     G["emb.ln.g"] += dg_
     G["emb.ln.b"] += db_
@@ -288,11 +377,11 @@ def encoder_backward(cfg: ModelCfg, theta: np.ndarray, cache, d_hidden: np.ndarr
     np.add.at(G["emb.word"], cache["ids"].reshape(-1), de.reshape(T, H))          # duplicates summed
 
 
-def micro_batch_grad(cfg: ModelCfg, theta: np.ndarray, ids, lens, mlm_pos, mlm_label):
+def micro_batch_grad(cfg: ModelCfg, theta: np.ndarray, ids, lens, mlm_pos, mlm_label, drop=None):
     """One forward/backward pass of one micro-batch.  Returns (loss_sum, flat gradient of
     loss_sum, n_seq, n_tok)."""
     ids = np.asarray(ids)
-    hidden, cache = encoder_forward(cfg, theta, ids, lens)
+    hidden, cache = encoder_forward(cfg, theta, ids, lens, drop)
     loss_sum, hcache = mlm_loss_forward(cfg, theta, hidden, mlm_pos, mlm_label)
     grad = np.zeros_like(theta)
     d_hidden = mlm_loss_backward(cfg, theta, hidden.shape, hcache, grad)
@@ -348,7 +437,8 @@ def train_step(cfg: ModelCfg, theta, m, v, t, micro_batches, lr=1e-4, beta1=0.9,
         if mb.get("dummy", False):
             G, n_total = accumulate(G, n_total, None, 0, ignore=True)
             continue
-        loss_sum, g, n_seq, _ = micro_batch_grad(cfg, theta, mb["ids"], mb["lens"], mb["mlm_pos"], mb["mlm_label"])
+        loss_sum, g, n_seq, _ = micro_batch_grad(cfg, theta, mb["ids"], mb["lens"], mb["mlm_pos"], mb["mlm_label"],
+                                                 mb.get("drop"))
         G, n_total = accumulate(G, n_total, g, n_seq)
         loss_total += float(loss_sum)
     D = n_total if denom is None else denom

@@ -503,3 +503,86 @@ def test_train_loop_resumed_equals_uninterrupted():
     for k in ("theta", "m", "v"):
         assert np.array_equal(snap[k], full[k])
     assert snap["step"] == full["step"] == 7
+
+
+# ---------------------------------------------------------------- dropout
+def test_philox_known_answers():
+    with open(os.path.join(GOLDEN, "philox4x32_10_known_answers.txt")) as f:
+        rows = [line.split() for line in f if line.strip() and not line.startswith("#")]
+    assert len(rows) == 3
+    for r in rows:
+        w = [int(x, 16) for x in r]
+        out = O.philox4x32_10(np.array([w[:4]], dtype=np.uint32), (w[4], w[5]))[0]
+        assert [int(x) for x in out] == w[6:], r
+    # vectorised calls give what single calls give
+    ctr = np.arange(40, dtype=np.uint32).reshape(10, 4)
+    many = O.philox4x32_10(ctr, (7, 9))
+    for i in range(10):
+        assert np.array_equal(many[i], O.philox4x32_10(ctr[i:i + 1], (7, 9))[0])
+
+
+def test_dropout_mask_properties():
+    drop = dict(p=0.1, seed=0x1234567890ABCDEF, stream=3)
+    n = 400_003                                             # not a multiple of 4
+    keep = O.dropout_keep(drop, 5, n)
+    assert keep.shape == (n,)
+    # drop frequency within 5 standard deviations of p
+    assert abs((~keep).mean() - 0.1) < 5 * math.sqrt(0.1 * 0.9 / n)
+    # a prefix of a longer site is the same mask (element e depends on e, site, stream, seed only)
+    assert np.array_equal(O.dropout_keep(drop, 5, 1001), keep[:1001])
+    # other site, stream or seed: another mask, and (nearly) independent of this one
+    for other in (O.dropout_keep(drop, 6, n), O.dropout_keep(dict(drop, stream=4), 5, n), O.dropout_keep(dict(drop, seed=1), 5, n)):
+        both = (~keep & ~other).mean()
+        assert abs(both - 0.01) < 5 * math.sqrt(0.01 * 0.99 / n)
+    # thresholds at the ends
+    assert O.dropout_keep(dict(drop, p=0.0), 0, 1000).all()
+    assert (~O.dropout_keep(dict(drop, p=1.0 - 2.0 ** -33), 0, 100000)).mean() > 0.9999
+    # exactly the definition for one element: word e % 4 of block e // 4
+    e = 123457
+    blk = O.philox4x32_10(np.array([[e // 4, 0, 5, 3]], dtype=np.uint32), (0x90ABCDEF, 0x12345678))[0]
+    assert keep[e] == (int(blk[e % 4]) >= int(math.floor(0.1 * 2 ** 32)))
+
+
+def test_dropout_is_unbiased_and_identity_at_zero():
+    x = np.linspace(-2.0, 3.0, 64).reshape(4, 16)
+    acc = np.zeros_like(x)
+    n = 4000
+    for s in range(n):
+        y, f = O._drop(x, dict(p=0.25, seed=11, stream=s), 2)
+        assert set(np.unique(f)) <= {0.0, 1.0 / 0.75}
+        acc += y
+    assert np.allclose(acc / n, x, atol=6 * 3.0 * math.sqrt(0.25 / 0.75 / n))
+    y0, f0 = O._drop(x, dict(p=0.0, seed=11, stream=0), 2)
+    assert y0 is x and f0 is None
+    cfg = MICRO
+    th = micro_theta(cfg, 5)
+    mb = micro_batch(cfg, [8, 4], 8, 3)
+    a = O.micro_batch_grad(cfg, th, mb["ids"], mb["lens"], mb["mlm_pos"], mb["mlm_label"])
+    b = O.micro_batch_grad(cfg, th, mb["ids"], mb["lens"], mb["mlm_pos"], mb["mlm_label"], dict(p=0.0, seed=1, stream=1))
+    assert a[0] == b[0] and np.array_equal(a[1], b[1])
+
+
+def test_gradients_with_dropout_match_finite_differences_fp64():
+    """With the masks fixed by (seed, stream) the dropped network is an ordinary differentiable
+    function: central differences pin the backward pass through all four kinds of sites."""
+    cfg = MICRO
+    th = micro_theta(cfg, 31)
+    mb = micro_batch(cfg, [8, 3, 5], 8, 19)
+    drop = dict(p=0.3, seed=99, stream=7)
+
+    def loss_d(theta):
+        hidden, _ = O.encoder_forward(cfg, theta, mb["ids"], mb["lens"], drop)
+        return float(O.mlm_loss_forward(cfg, theta, hidden, mb["mlm_pos"], mb["mlm_label"])[0])
+
+    loss, grad, _, _ = O.micro_batch_grad(cfg, th, mb["ids"], mb["lens"], mb["mlm_pos"], mb["mlm_label"], drop)
+    assert loss == pytest.approx(loss_d(th), rel=1e-14)
+    assert abs(loss - loss_of(cfg, th, mb)) > 1e-3          # dropout did change the function
+    rng = np.random.default_rng(8)
+    eps = 1e-5
+    for name, off, r, c in O.param_layout(cfg):
+        n = r * c
+        u = np.zeros_like(th)
+        u[off:off + n] = rng.standard_normal(n)
+        fd = (loss_d(th + eps * u) - loss_d(th - eps * u)) / (2 * eps)
+        an = float(grad @ u)
+        assert abs(fd - an) <= 1e-6 * max(abs(fd), abs(an)) + 1e-9, (name, fd, an)
