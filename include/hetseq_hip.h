@@ -91,6 +91,25 @@ size_t hs_acts_bytes(const hs_model_cfg* cfg, int32_t B, int32_t L, int32_t M);
  * maximum over the three calls, so one buffer serves all. */
 size_t hs_workspace_bytes(const hs_model_cfg* cfg, int32_t B, int32_t L, int32_t M);
 
+/* ---- dropout --------------------------------------------------------------------------------
+ * Section "Transformer Translation Model" trains with dropout 0.1 and section "Checkpointing" keeps
+ * the run's random seed; the cited BERT model drops its embedding output, attention probabilities,
+ * attention output and feed-forward output (the last two before the residual is added).
+ * hs_set_dropout sets the rate p in [0, 1), the seed and a 32-bit stream number for the following
+ * hs_encoder_fwd / hs_encoder_bwd calls on ctx (host state only; p = 0, the initial state, switches
+ * dropout off).  A mask is a pure function of (seed, stream, site, element): element e of a site
+ * uses word e % 4 of the Philox4x32-10 block with counter (e / 4 low, e / 4 high, site, stream) and
+ * key (seed low, seed high), is dropped when that word is below floor(p * 2^32), and is scaled by
+ * 1 / (1 - p) otherwise.  Sites: 0 = embedding output [B, L, H]; for layer l: 1 + 3 l = attention
+ * probabilities [B, heads, L, L], 2 + 3 l = attention output [B, L, H], 3 + 3 l = feed-forward
+ * output [B, L, H]; elements in row-major order of those shapes (L = the padded length).
+ * The backward call of a micro-batch must see the state its forward call saw; give every
+ * micro-batch of every update its own stream number.  The masked-LM head has no dropout. */
+hs_status hs_set_dropout(hs_ctx* ctx, double p, uint64_t seed, uint32_t stream);
+/* Test aid: writes the keep mask (1 = survives) of the first n elements of `site` under the current
+ * state of ctx to mask_out [n] (dev). */
+hs_status hs_dropout_keep_mask(hs_ctx* ctx, uint32_t site, size_t n, uint8_t* mask_out, void* stream);
+
 /* ---- learning-rate schedule (host) ---------------------------------------------------------
  * Section "BERT Language Model": linear-decay schedule with a maximum rate, `warmup` warm-up
  * updates and `total` updates in all.  Returns the rate of update number t (1-based):

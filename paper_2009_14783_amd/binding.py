@@ -61,6 +61,8 @@ _SIGNATURES = {
     "hs_grad_accum_normalize": (_I32, [_P, _P, _SZ, _I32, _D, _P]),
     "hs_adam_step": (_I32, [_P, _P, _P, _P, _P, _SZ, _D, _D, _D, _D, _D, _I64, _P]),
     "hs_cast_params": (_I32, [_P, _P, _SZ, _I32, _P]),
+    "hs_set_dropout": (_I32, [_P, _D, C.c_uint64, C.c_uint32]),
+    "hs_dropout_keep_mask": (_I32, [_P, C.c_uint32, _SZ, _P, _P]),
     "hs_lr_linear": (_D, [_I64, _D, _I64, _I64]),
     "hs_checkpoint_write": (_I32, [C.c_char_p, C.POINTER(hs_ckpt_header), _P, _P, _P]),
     "hs_checkpoint_read_header": (_I32, [C.c_char_p, C.POINTER(hs_ckpt_header)]),
@@ -219,6 +221,14 @@ def hs_mlm_loss(ctx, w, hidden, mlm_pos, mlm_label, M, B, L, loss_sum, d_hidden,
 def hs_encoder_bwd(ctx, w, acts, ids, lens, B, L, d_hidden, g, accumulate, workspace, workspace_bytes, stream=None):
     _check(lib().hs_encoder_bwd(ctx, _ptr(w), _ptr(acts), _ptr(ids), _ptr(lens), B, L, _ptr(d_hidden), _ptr(g), accumulate,
                                 _ptr(workspace), workspace_bytes, _stream(stream)), ctx)
+
+
+def hs_set_dropout(ctx, p, seed, stream_no):
+    _check(lib().hs_set_dropout(ctx, float(p), int(seed) & 0xFFFFFFFFFFFFFFFF, int(stream_no) & 0xFFFFFFFF), ctx)
+
+
+def hs_dropout_keep_mask(ctx, site, n, mask_out, stream=None):
+    _check(lib().hs_dropout_keep_mask(ctx, int(site), int(n), _ptr(mask_out), _stream(stream)), ctx)
 
 
 def hs_grad_accum_normalize(G, g, n, ignore, denom, stream=None):

@@ -71,7 +71,7 @@ HeadWs carve_head(const hs_model_cfg& c, int M, void* base) {
 struct BwdWs {
   // dy2, dy1, dh and dqkv exist twice (by layer parity): the weight-gradient GEMMs that read them run
   // on a second stream and may still be in flight while the next layer produces its own
-  void *dxa, *dxb, *dy2[2], *dy1[2], *dh[2], *dqkv[2], *dctx, *ln_part, *ln_part2[2], *ln_part1[2], *cs_part, *emb, *gemm_ws, *gemm_ws_side;
+  void *dxa, *dxb, *dy2[2], *dy1[2], *dy2m[2], *dy1m[2], *dh[2], *dqkv[2], *dctx, *ln_part, *ln_part2[2], *ln_part1[2], *cs_part, *emb, *gemm_ws, *gemm_ws_side;
   float* dvec;
   size_t total, gemm_ws_bytes;
 };
@@ -82,6 +82,7 @@ BwdWs carve_bwd(const hs_model_cfg& c, int B, int L, void* base) {
   w.dxa = cv.take(T * H * es); w.dxb = cv.take(T * H * es); w.dctx = cv.take(T * H * es);
   for (int k = 0; k < 2; ++k) {
     w.dy2[k] = cv.take(T * H * es); w.dy1[k] = cv.take(T * H * es);
+    w.dy2m[k] = cv.take(T * H * es); w.dy1m[k] = cv.take(T * H * es);     // masked copies (dropout only)
     w.dh[k] = cv.take(T * F * es); w.dqkv[k] = cv.take(T * 3 * H * es);
   }
   w.dvec = (float*)cv.take((size_t)B * c.n_heads * L * sizeof(float));
@@ -130,6 +131,7 @@ GemmArgs gemm_args(int dtype, int ak, int bk, int M, int N, int K, const void* A
   g.A = A; g.lda = lda; g.B = B; g.ldb = ldb; g.C = C; g.ldc = ldc;
   g.c_f32 = 0; g.beta = 0.f; g.bias = nullptr; g.epi = 0; g.aux = nullptr; g.ldaux = 0; g.C2 = nullptr;
   g.ws = nullptr; g.ws_bytes = 0;
+  g.drop = nullptr; g.drop_site = 0;
   return g;
 }
 
@@ -169,7 +171,8 @@ hs_status hs_encoder_fwd(hs_ctx* ctx, const void* w, const int32_t* ids, const i
   Acts a = carve_acts(c, B, L, acts);
 
   HS_TRY(launch_embed_ln_fwd(ctx, dt, W(ctx, w, o.emb_word), W(ctx, w, o.emb_pos), W(ctx, w, o.emb_ln_g), W(ctx, w, o.emb_ln_b), ids,
-                             a.e_pre, a.x0, a.emb_stats, B, L, H, c.vocab, c.ln_eps, s));
+                             a.e_pre, a.x0, a.emb_stats, B, L, H, c.vocab, c.ln_eps, s, &ctx->drop));
+  const DropCfg* drop = ctx->drop.thr ? &ctx->drop : nullptr;
   const void* x = a.x0;
   for (int i = 0; i < c.n_layers; ++i) {
     const LayerOff& lo = o.layer[i];
@@ -179,10 +182,11 @@ hs_status hs_encoder_fwd(hs_ctx* ctx, const void* w, const int32_t* ids, const i
     GemmArgs g = gemm_args(dt, 1, 1, T, 3 * H, H, x, H, W(ctx, w, lo.qkv_w), H, la.qkv, 3 * H);
     g.bias = W(ctx, w, lo.qkv_b);
     HS_TRY(launch_gemm(ctx, g, s));
-    HS_TRY(launch_attention_fwd(ctx, dt, la.qkv, lens, B, L, c.n_heads, la.ctx, la.lse, s));
+    HS_TRY(launch_attention_fwd(ctx, dt, la.qkv, lens, B, L, c.n_heads, la.ctx, la.lse, s, drop, site_attention_prob(i)));
     // y1 = x + ctx Wo^T + bo ; x1 = LN(y1)
     g = gemm_args(dt, 1, 1, T, H, H, la.ctx, H, W(ctx, w, lo.o_w), H, la.y1, H);
     g.bias = W(ctx, w, lo.o_b); g.epi = 1; g.aux = x; g.ldaux = H;
+    g.drop = drop; g.drop_site = site_attention_out(i);
     HS_TRY(launch_gemm(ctx, g, s));
     HS_TRY(launch_layernorm_fwd(ctx, dt, la.y1, W(ctx, w, lo.ln1_g), W(ctx, w, lo.ln1_b), la.x1, la.st1, T, H, c.ln_eps, s));
     // hpre = x1 W1^T + b1 ; h = GELU(hpre)
@@ -192,6 +196,7 @@ hs_status hs_encoder_fwd(hs_ctx* ctx, const void* w, const int32_t* ids, const i
     // y2 = x1 + h W2^T + b2 ; x2 = LN(y2)
     g = gemm_args(dt, 1, 1, T, H, F, la.h, F, W(ctx, w, lo.ffn2_w), F, la.y2, H);
     g.bias = W(ctx, w, lo.ffn2_b); g.epi = 1; g.aux = la.x1; g.ldaux = H;
+    g.drop = drop; g.drop_site = site_ffn_out(i);
     HS_TRY(launch_gemm(ctx, g, s));
     HS_TRY(launch_layernorm_fwd(ctx, dt, la.y2, W(ctx, w, lo.ln2_g), W(ctx, w, lo.ln2_b), x2, la.st2, T, H, c.ln_eps, s));
     x = x2;
@@ -271,6 +276,7 @@ hs_status hs_encoder_bwd(hs_ctx* ctx, const void* w, const void* acts, const int
   Acts a = carve_acts(c, B, L, const_cast<void*>(acts));
   BwdWs ws = carve_bwd(c, B, L, workspace);
   const float beta = accumulate ? 1.f : 0.f;
+  const DropCfg* drop = ctx->drop.thr ? &ctx->drop : nullptr;
   auto run_gemm = [&](GemmArgs& a) { a.ws = ws.gemm_ws; a.ws_bytes = ws.gemm_ws_bytes; return launch_gemm(ctx, a, s); };
 
   // The weight-gradient GEMMs only consume; they run on a second stream so that their ramp-up and tail
@@ -298,16 +304,21 @@ hs_status hs_encoder_bwd(hs_ctx* ctx, const void* w, const void* acts, const int
     const void* x_in = (i == 0) ? a.x0 : a.layer[i - 1].x2;
     const int par = i & 1;
     void *dy2 = ws.dy2[par], *dy1 = ws.dy1[par], *dh = ws.dh[par], *dqkv = ws.dqkv[par];
+    // With dropout the gradient that enters the two dropped branches is the masked one; the residual paths
+    // keep the unmasked gradient.
+    void* dy2b = drop ? ws.dy2m[par] : dy2;
+    void* dy1b = drop ? ws.dy1m[par] : dy1;
     if (overlap && i + 2 < NL) HS_HIP_CHECK(ctx, hipStreamWaitEvent(s, ev(i + 2, 4), 0));   // buffers of this parity are free again
     // LN2 backward: dy2 on the main chain; d gain/bias and colsum(dy2) = d b2 from its partials beside it
-    HS_TRY(launch_layernorm_bwd_rows(ctx, dt, dcur, la.y2, la.st2, W(ctx, w, lo.ln2_g), dy2, T, H, ws.ln_part2[par], s));
+    HS_TRY(launch_layernorm_bwd_rows(ctx, dt, dcur, la.y2, la.st2, W(ctx, w, lo.ln2_g), dy2, T, H, ws.ln_part2[par], s, drop,
+                                     site_ffn_out(i), drop ? 2 : 0, dy2b));
     HS_TRY(hand_over(i, 0));
     HS_TRY(launch_layernorm_bwd_cols(ctx, ws.ln_part2[par], g + lo.ln2_g, g + lo.ln2_b, g + lo.ffn2_b, beta, T, H, sd));
     // dW2 [H,F] = dy2^T h
-    GemmArgs ga = gemm_args(dt, 0, 0, H, F, T, dy2, H, la.h, F, g + lo.ffn2_w, F);
+    GemmArgs ga = gemm_args(dt, 0, 0, H, F, T, dy2b, H, la.h, F, g + lo.ffn2_w, F);
     HS_TRY(side_gemm(ga));
     // dhpre [T,F] = (dy2 W2) * GELU'(hpre)
-    ga = gemm_args(dt, 1, 0, T, F, H, dy2, H, W(ctx, w, lo.ffn2_w), F, dh, F);
+    ga = gemm_args(dt, 1, 0, T, F, H, dy2b, H, W(ctx, w, lo.ffn2_w), F, dh, F);
     ga.epi = 3; ga.aux = la.hpre; ga.ldaux = F;
     HS_TRY(run_gemm(ga));
     HS_TRY(hand_over(i, 1));
@@ -320,15 +331,17 @@ hs_status hs_encoder_bwd(hs_ctx* ctx, const void* w, const void* acts, const int
     ga.epi = 1; ga.aux = dy2; ga.ldaux = H;
     HS_TRY(run_gemm(ga));
     // LN1 backward: dy1, d gain/bias, colsum(dy1) = d bo
-    HS_TRY(launch_layernorm_bwd_rows(ctx, dt, ws.dxa, la.y1, la.st1, W(ctx, w, lo.ln1_g), dy1, T, H, ws.ln_part1[par], s));
+    HS_TRY(launch_layernorm_bwd_rows(ctx, dt, ws.dxa, la.y1, la.st1, W(ctx, w, lo.ln1_g), dy1, T, H, ws.ln_part1[par], s, drop,
+                                     site_attention_out(i), drop ? 2 : 0, dy1b));
     HS_TRY(hand_over(i, 2));
     HS_TRY(launch_layernorm_bwd_cols(ctx, ws.ln_part1[par], g + lo.ln1_g, g + lo.ln1_b, g + lo.o_b, beta, T, H, sd));
     // dWo [H,H] = dy1^T ctx ; dctx = dy1 Wo
-    ga = gemm_args(dt, 0, 0, H, H, T, dy1, H, la.ctx, H, g + lo.o_w, H);
+    ga = gemm_args(dt, 0, 0, H, H, T, dy1b, H, la.ctx, H, g + lo.o_w, H);
     HS_TRY(side_gemm(ga));
-    ga = gemm_args(dt, 1, 0, T, H, H, dy1, H, W(ctx, w, lo.o_w), H, ws.dctx, H);
+    ga = gemm_args(dt, 1, 0, T, H, H, dy1b, H, W(ctx, w, lo.o_w), H, ws.dctx, H);
     HS_TRY(run_gemm(ga));
-    HS_TRY(launch_attention_bwd(ctx, dt, la.qkv, la.ctx, la.lse, ws.dctx, lens, B, L, c.n_heads, dqkv, ws.dvec, s));
+    HS_TRY(launch_attention_bwd(ctx, dt, la.qkv, la.ctx, la.lse, ws.dctx, lens, B, L, c.n_heads, dqkv, ws.dvec, s, drop,
+                                site_attention_prob(i)));
     HS_TRY(hand_over(i, 3));
     HS_TRY(launch_colsum(ctx, dt, dqkv, 3 * H, T, 3 * H, g + lo.qkv_b, beta, ws.cs_part, sd));
     // dWqkv [3H,H] = dqkv^T x_in ; dx_in = dqkv Wqkv + dy1
@@ -342,7 +355,7 @@ hs_status hs_encoder_bwd(hs_ctx* ctx, const void* w, const void* acts, const int
   }
   // embedding LayerNorm, then the two embedding tables
   HS_TRY(launch_layernorm_bwd(ctx, dt, dcur, a.e_pre, a.emb_stats, W(ctx, w, o.emb_ln_g), ws.dxa, g + o.emb_ln_g,
-                              g + o.emb_ln_b, nullptr, beta, T, H, ws.ln_part, s));
+                              g + o.emb_ln_b, nullptr, beta, T, H, ws.ln_part, s, drop, site_embedding(), drop ? 1 : 0, nullptr));
   HS_TRY(launch_embed_bwd(ctx, dt, ws.dxa, ids, B, L, H, c.vocab, c.max_pos, g + o.emb_word, g + o.emb_pos, beta, ws.emb, s));
   // everything the second stream did is ordered before whatever the caller enqueues next
   if (overlap) HS_HIP_CHECK(ctx, hipStreamWaitEvent(s, ev(0, 4), 0));

@@ -23,7 +23,7 @@ __device__ __forceinline__ void stage_block(float (*dst)[D], const T* __restrict
 
 template <class T>
 __global__ __launch_bounds__(64) void attn_fwd_simt(const T* __restrict__ qkv, const int32_t* __restrict__ lens, int L, int A,
-                                                    T* __restrict__ out, float* __restrict__ lse) {
+                                                    T* __restrict__ out, float* __restrict__ lse, DropCfg drop, uint32_t site) {
   __shared__ float Ks[64][D];
   __shared__ float Vs[64][D];
   const int lane = threadIdx.x;
@@ -51,8 +51,10 @@ __global__ __launch_bounds__(64) void attn_fwd_simt(const T* __restrict__ qkv, c
       const float mn = fmaxf(m, s);
       const float alpha = __expf(m - mn), p = __expf(s - mn);
       l = l * alpha + p;
+      // dropout acts on the normalised probabilities: the row sum keeps every key, the value sum the survivors
+      const float pd = drop.thr ? p * drop_factor1(drop, site, (((uint64_t)b * A + h) * L + qi) * L + k0 + j) : p;
 #pragma unroll
-      for (int c = 0; c < D; ++c) acc[c] = fmaf(p, Vs[j][c], acc[c] * alpha);
+      for (int c = 0; c < D; ++c) acc[c] = fmaf(pd, Vs[j][c], acc[c] * alpha);
       m = mn;
     }
   }
@@ -69,7 +71,7 @@ __global__ __launch_bounds__(64) void attn_fwd_simt(const T* __restrict__ qkv, c
 template <class T>
 __global__ __launch_bounds__(64) void attn_bwd_dq_simt(const T* __restrict__ qkv, const T* __restrict__ out, const float* __restrict__ lse,
                                                        const T* __restrict__ d_out, const int32_t* __restrict__ lens, int L, int A,
-                                                       T* __restrict__ dqkv, float* __restrict__ dvec) {
+                                                       T* __restrict__ dqkv, float* __restrict__ dvec, DropCfg drop, uint32_t site) {
   __shared__ float Ks[64][D];
   __shared__ float Vs[64][D];
   const int lane = threadIdx.x;
@@ -103,6 +105,7 @@ __global__ __launch_bounds__(64) void attn_bwd_dq_simt(const T* __restrict__ qkv
 #pragma unroll
         for (int c = 0; c < D; ++c) { s = fmaf(q[c], Ks[j][c], s); dp = fmaf(go[c], Vs[j][c], dp); }
         const float p = __expf(s - row_lse);
+        if (drop.thr) dp *= drop_factor1(drop, site, (((uint64_t)b * A + h) * L + qi) * L + k0 + j);
         const float ds = p * (dp - dv_);
 #pragma unroll
         for (int c = 0; c < D; ++c) dq[c] = fmaf(ds, Ks[j][c], dq[c]);
@@ -120,7 +123,8 @@ __global__ __launch_bounds__(64) void attn_bwd_dq_simt(const T* __restrict__ qkv
 template <class T>
 __global__ __launch_bounds__(64) void attn_bwd_dkv_simt(const T* __restrict__ qkv, const float* __restrict__ lse,
                                                         const T* __restrict__ d_out, const float* __restrict__ dvec,
-                                                        const int32_t* __restrict__ lens, int L, int A, T* __restrict__ dqkv) {
+                                                        const int32_t* __restrict__ lens, int L, int A, T* __restrict__ dqkv, DropCfg drop,
+                                                        uint32_t site) {
   __shared__ float Qs[64][D];
   __shared__ float Gs[64][D];
   __shared__ float lse_s[64], dvec_s[64];
@@ -155,9 +159,11 @@ __global__ __launch_bounds__(64) void attn_bwd_dkv_simt(const T* __restrict__ qk
 #pragma unroll
         for (int c = 0; c < D; ++c) { s = fmaf(Qs[i][c], k[c], s); dp = fmaf(Gs[i][c], v[c], dp); }
         const float p = __expf(0.125f * s - lse_s[i]);
-        const float ds = p * (dp - dvec_s[i]);
+        const float f = drop.thr ? drop_factor1(drop, site, (((uint64_t)b * A + h) * L + q0 + i) * L + kj) : 1.0f;
+        const float ds = p * (f * dp - dvec_s[i]);
+        const float pd = p * f;
 #pragma unroll
-        for (int c = 0; c < D; ++c) { dv[c] = fmaf(p, Gs[i][c], dv[c]); dk[c] = fmaf(ds, Qs[i][c], dk[c]); }
+        for (int c = 0; c < D; ++c) { dv[c] = fmaf(pd, Gs[i][c], dv[c]); dk[c] = fmaf(ds, Qs[i][c], dk[c]); }
       }
     }
   }
@@ -170,36 +176,42 @@ __global__ __launch_bounds__(64) void attn_bwd_dkv_simt(const T* __restrict__ qk
 
 }  // namespace
 
-void launch_attention_fwd_mfma(const void* qkv, const int32_t* lens, int B, int L, int A, void* out, float* lse, hipStream_t s);
+void launch_attention_fwd_mfma(const void* qkv, const int32_t* lens, int B, int L, int A, void* out, float* lse, hipStream_t s,
+                               const DropCfg& drop, uint32_t site);
 void launch_attention_bwd_mfma(const void* qkv, const void* out, const float* lse, const void* d_out, const int32_t* lens, int B, int L,
-                               int A, void* dqkv, float* dvec, hipStream_t s);
+                               int A, void* dqkv, float* dvec, hipStream_t s, const DropCfg& drop, uint32_t site);
 
 hs_status launch_attention_fwd(hs_ctx* ctx, int dtype, const void* qkv, const int32_t* lens, int B, int L, int A, void* out, float* lse,
-                               hipStream_t s) {
+                               hipStream_t s, const DropCfg* drop_in, uint32_t site) {
   if (B <= 0 || L <= 0) return HS_OK;
+  const DropCfg drop = (drop_in && drop_in->thr) ? *drop_in : DropCfg{0u, 1.0f, 0u, 0u, 0u};
+  if (drop.thr && (L & 3)) return hs_fail(ctx, HS_ERR_SHAPE, "attention with dropout: the padded length must be a multiple of 4");
   const double fl = 4.0 * B * A * (double)L * L * D;
   const double by = (double)B * L * A * D * 4.0 * esize(dtype);
   KScope scope(ctx ? ctx->prof : nullptr, KC_ATTN_FWD, fl, by, s);
   dim3 grid((L + 63) / 64, A, B);
-  if (dtype == HS_BF16) launch_attention_fwd_mfma(qkv, lens, B, L, A, out, lse, s);
-  else hipLaunchKernelGGL(attn_fwd_simt<float>, grid, dim3(64), 0, s, (const float*)qkv, lens, L, A, (float*)out, lse);
+  if (dtype == HS_BF16) launch_attention_fwd_mfma(qkv, lens, B, L, A, out, lse, s, drop, site);
+  else hipLaunchKernelGGL(attn_fwd_simt<float>, grid, dim3(64), 0, s, (const float*)qkv, lens, L, A, (float*)out, lse, drop, site);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return hs_fail(ctx, HS_ERR_HIP, std::string("attention_fwd: ") + hipGetErrorString(e));
   return HS_OK;
 }
 
 hs_status launch_attention_bwd(hs_ctx* ctx, int dtype, const void* qkv, const void* out, const float* lse, const void* d_out,
-                               const int32_t* lens, int B, int L, int A, void* dqkv, float* dvec, hipStream_t s) {
+                               const int32_t* lens, int B, int L, int A, void* dqkv, float* dvec, hipStream_t s, const DropCfg* drop_in,
+                               uint32_t site) {
   if (B <= 0 || L <= 0) return HS_OK;
+  const DropCfg drop = (drop_in && drop_in->thr) ? *drop_in : DropCfg{0u, 1.0f, 0u, 0u, 0u};
+  if (drop.thr && (L & 3)) return hs_fail(ctx, HS_ERR_SHAPE, "attention with dropout: the padded length must be a multiple of 4");
   const double fl = 8.0 * B * A * (double)L * L * D;   // dV, dP, dQ, dK (recomputing the scores is not counted)
   const double by = (double)B * L * A * D * 8.0 * esize(dtype);
   KScope scope(ctx ? ctx->prof : nullptr, KC_ATTN_BWD, fl, by, s);
   dim3 grid((L + 63) / 64, A, B);
   if (dtype == HS_BF16) {
-    launch_attention_bwd_mfma(qkv, out, lse, d_out, lens, B, L, A, dqkv, dvec, s);
+    launch_attention_bwd_mfma(qkv, out, lse, d_out, lens, B, L, A, dqkv, dvec, s, drop, site);
   } else {
-    hipLaunchKernelGGL(attn_bwd_dq_simt<float>, grid, dim3(64), 0, s, (const float*)qkv, (const float*)out, lse, (const float*)d_out, lens, L, A, (float*)dqkv, dvec);
-    hipLaunchKernelGGL(attn_bwd_dkv_simt<float>, grid, dim3(64), 0, s, (const float*)qkv, lse, (const float*)d_out, (const float*)dvec, lens, L, A, (float*)dqkv);
+    hipLaunchKernelGGL(attn_bwd_dq_simt<float>, grid, dim3(64), 0, s, (const float*)qkv, (const float*)out, lse, (const float*)d_out, lens, L, A, (float*)dqkv, dvec, drop, site);
+    hipLaunchKernelGGL(attn_bwd_dkv_simt<float>, grid, dim3(64), 0, s, (const float*)qkv, lse, (const float*)d_out, (const float*)dvec, lens, L, A, (float*)dqkv, drop, site);
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return hs_fail(ctx, HS_ERR_HIP, std::string("attention_bwd: ") + hipGetErrorString(e));

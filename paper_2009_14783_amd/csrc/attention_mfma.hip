@@ -60,6 +60,24 @@ __device__ __forceinline__ bf16x8 frag_cols_t(const bf16* tile, int rb, int step
 // streamed-row index (within a 32-row tile) of result register r
 __device__ __forceinline__ int tile_row(int r, int lane) { return 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3); }
 
+// Dropout factors of a score tile whose STREAMED index is the key: registers 4a .. 4a+3 of a lane are four
+// consecutive keys of one query, i.e. one generator block.  row_base = ((b*A + h)*L + query) * L.
+__device__ __forceinline__ void drop_tile_keys(const DropCfg& d, uint32_t site, uint64_t row_base, int key0, int lane, f32x16& f) {
+#pragma unroll
+  for (int a = 0; a < 4; ++a) {
+    float t[4];
+    drop_factors4(d, site, (row_base + (uint64_t)(key0 + 8 * a + 4 * (lane >> 5))) >> 2, t);
+    f[4 * a] = t[0]; f[4 * a + 1] = t[1]; f[4 * a + 2] = t[2]; f[4 * a + 3] = t[3];
+  }
+}
+// ... and of a tile whose STREAMED index is the query (the lane owns one key): one element per block.
+// head_base = (b*A + h) * L; element = (head_base + query) * L + key.
+__device__ __forceinline__ void drop_tile_queries(const DropCfg& d, uint32_t site, uint64_t head_base, int L, int query0, int key, int lane,
+                                                  f32x16& f) {
+#pragma unroll
+  for (int r = 0; r < 16; ++r) f[r] = drop_factor1(d, site, (head_base + (uint64_t)(query0 + tile_row(r, lane))) * (uint64_t)L + (uint64_t)key);
+}
+
 __device__ __forceinline__ bf16x8 pack8(const f32x16& v, int step) {
   bf16x8 o;
 #pragma unroll
@@ -84,8 +102,9 @@ __device__ __forceinline__ void store_owned_rows(bf16* __restrict__ dst_row, con
 // ------------------------------------------------------------------------------------------
 // forward: wave owns 32 queries, streams keys/values
 // ------------------------------------------------------------------------------------------
+template <bool DROP>
 __global__ __launch_bounds__(256) void attn_fwd_mfma(const bf16* __restrict__ qkv, const int32_t* __restrict__ lens, int L, int A,
-                                                     bf16* __restrict__ out, float* __restrict__ lse) {
+                                                     bf16* __restrict__ out, float* __restrict__ lse, DropCfg drop, uint32_t site) {
   __shared__ __attribute__((aligned(16))) bf16 Ks[64 * LDT];
   __shared__ __attribute__((aligned(16))) bf16 Vs[64 * LDT];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -141,6 +160,12 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma(const bf16* __restrict__ qk
         }
         lsum = lsum * alpha + ps;
         m2 = mn;
+        if (DROP) {      // the row sum keeps every key, the value sum only the survivors (scaled)
+          f32x16 f;
+          drop_tile_keys(drop, site, (((uint64_t)b * A + h) * L + q) * (uint64_t)L, k0 + kb, lane, f);
+#pragma unroll
+          for (int r = 0; r < 16; ++r) st[r] *= f[r];
+        }
 #pragma unroll
         for (int db = 0; db < 2; ++db)
 #pragma unroll
@@ -164,10 +189,11 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma(const bf16* __restrict__ qk
 // ------------------------------------------------------------------------------------------
 // backward 1: wave owns 32 queries, streams keys/values -> dq and dvec[q] = sum_d dO[q,d] O[q,d]
 // ------------------------------------------------------------------------------------------
+template <bool DROP>
 __global__ __launch_bounds__(256) void attn_bwd_dq_mfma(const bf16* __restrict__ qkv, const bf16* __restrict__ out,
                                                         const float* __restrict__ lse, const bf16* __restrict__ d_out,
                                                         const int32_t* __restrict__ lens, int L, int A, bf16* __restrict__ dqkv,
-                                                        float* __restrict__ dvec) {
+                                                        float* __restrict__ dvec, DropCfg drop, uint32_t site) {
   __shared__ __attribute__((aligned(16))) bf16 Ks[64 * LDT];
   __shared__ __attribute__((aligned(16))) bf16 Vs[64 * LDT];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -217,6 +243,12 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma(const bf16* __restrict__
           st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(Ks, kb, ks, lane), qf[ks], st, 0, 0, 0);
           dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(Vs, kb, ks, lane), gf[ks], dp, 0, 0, 0);
         }
+        if (DROP) {
+          f32x16 f;
+          drop_tile_keys(drop, site, (((uint64_t)b * A + h) * L + q) * (uint64_t)L, k0 + kb, lane, f);
+#pragma unroll
+          for (int r = 0; r < 16; ++r) dp[r] *= f[r];
+        }
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const bool ok = (k0 + kb + tile_row(r, lane) < len) && (q < len);
@@ -241,9 +273,11 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma(const bf16* __restrict__
 // ------------------------------------------------------------------------------------------
 // backward 2: wave owns 32 keys, streams queries / output gradients -> dk, dv
 // ------------------------------------------------------------------------------------------
+template <bool DROP>
 __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma(const bf16* __restrict__ qkv, const float* __restrict__ lse,
                                                          const bf16* __restrict__ d_out, const float* __restrict__ dvec,
-                                                         const int32_t* __restrict__ lens, int L, int A, bf16* __restrict__ dqkv) {
+                                                         const int32_t* __restrict__ lens, int L, int A, bf16* __restrict__ dqkv, DropCfg drop,
+                                                         uint32_t site) {
   __shared__ __attribute__((aligned(16))) bf16 Qs[64 * LDT];
   __shared__ __attribute__((aligned(16))) bf16 Gs[64 * LDT];
   __shared__ float lse2_s[64], dvec_s[64];
@@ -293,13 +327,16 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma(const bf16* __restrict_
             st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(Qs, qb, ks, lane), kf[ks], st, 0, 0, 0);
             dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(Gs, qb, ks, lane), vf[ks], dp, 0, 0, 0);
           }
+          f32x16 f;
+          if (DROP) drop_tile_queries(drop, site, ((uint64_t)b * A + h) * L, L, q0 + qb, kj, lane, f);
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
             const int qi = qb + tile_row(r, lane);
             const bool ok = (q0 + qi < len) && (kj < len);
             const float p = ok ? fast_exp2(st[r] * SCALE2 - lse2_s[qi]) : 0.f;
-            st[r] = p;
-            dp[r] = p * (dp[r] - dvec_s[qi]);
+            const float fr = DROP ? f[r] : 1.0f;
+            st[r] = p * fr;
+            dp[r] = p * (fr * dp[r] - dvec_s[qi]);
           }
           const bf16x8 p0 = pack8(st, 0), p1 = pack8(st, 1), s0 = pack8(dp, 0), s1 = pack8(dp, 1);
 #pragma unroll
@@ -336,9 +373,11 @@ __device__ __forceinline__ void stage128(bf16* tile, const bf16* __restrict__ sr
   }
 }
 
+template <bool DROP>
 __global__ __launch_bounds__(256) void attn_bwd_fused128_mfma(const bf16* __restrict__ qkv, const bf16* __restrict__ out,
                                                               const float* __restrict__ lse, const bf16* __restrict__ d_out,
-                                                              const int32_t* __restrict__ lens, int L, int A, bf16* __restrict__ dqkv) {
+                                                              const int32_t* __restrict__ lens, int L, int A, bf16* __restrict__ dqkv,
+                                                              DropCfg drop, uint32_t site) {
   extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
   bf16* Qs = (bf16*)lds_raw;
   bf16* Ks = Qs + 128 * LDT;
@@ -402,6 +441,12 @@ __global__ __launch_bounds__(256) void attn_bwd_fused128_mfma(const bf16* __rest
         st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(Ks, kb, ks, lane), qf[ks], st, 0, 0, 0);
         dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(Vs, kb, ks, lane), gf[ks], dp, 0, 0, 0);
       }
+      if (DROP) {
+        f32x16 f;
+        drop_tile_keys(drop, site, (((uint64_t)b * A + h) * L + own) * (uint64_t)L, kb, lane, f);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) dp[r] *= f[r];
+      }
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const bool ok = (kb + tile_row(r, lane) < len) && (own < len);
@@ -441,13 +486,16 @@ __global__ __launch_bounds__(256) void attn_bwd_fused128_mfma(const bf16* __rest
         st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(Qs, qb, ks, lane), kf[ks], st, 0, 0, 0);
         dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(Gs, qb, ks, lane), vf[ks], dp, 0, 0, 0);
       }
+      f32x16 f;
+      if (DROP) drop_tile_queries(drop, site, ((uint64_t)b * A + h) * L, L, qb, own, lane, f);
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int qi = qb + tile_row(r, lane);
         const bool ok = (qi < len) && (own < len);
         const float pr = ok ? fast_exp2(st[r] * SCALE2 - lse2_s[qi]) : 0.f;
-        st[r] = pr;
-        dp[r] = pr * (dp[r] - dvec_s[qi]);
+        const float fr = DROP ? f[r] : 1.0f;
+        st[r] = pr * fr;
+        dp[r] = pr * (fr * dp[r] - dvec_s[qi]);
       }
       const bf16x8 p0 = pack8(st, 0), p1 = pack8(st, 1), s0 = pack8(dp, 0), s1 = pack8(dp, 1);
 #pragma unroll
@@ -468,24 +516,39 @@ __global__ __launch_bounds__(256) void attn_bwd_fused128_mfma(const bf16* __rest
 
 }  // namespace
 
-void launch_attention_fwd_mfma(const void* qkv, const int32_t* lens, int B, int L, int A, void* out, float* lse, hipStream_t s) {
+void launch_attention_fwd_mfma(const void* qkv, const int32_t* lens, int B, int L, int A, void* out, float* lse, hipStream_t s,
+                               const DropCfg& drop, uint32_t site) {
   dim3 grid((L + 127) / 128, A, B);
-  hipLaunchKernelGGL(attn_fwd_mfma, grid, dim3(256), 0, s, (const bf16*)qkv, lens, L, A, (bf16*)out, lse);
+  if (drop.thr) hipLaunchKernelGGL(attn_fwd_mfma<true>, grid, dim3(256), 0, s, (const bf16*)qkv, lens, L, A, (bf16*)out, lse, drop, site);
+  else hipLaunchKernelGGL(attn_fwd_mfma<false>, grid, dim3(256), 0, s, (const bf16*)qkv, lens, L, A, (bf16*)out, lse, drop, site);
 }
 
 void launch_attention_bwd_mfma(const void* qkv, const void* out, const float* lse, const void* d_out, const int32_t* lens, int B, int L,
-                               int A, void* dqkv, float* dvec, hipStream_t s) {
+                               int A, void* dqkv, float* dvec, hipStream_t s, const DropCfg& drop, uint32_t site) {
   if (L <= 128) {
     constexpr size_t lds = 4 * 128 * LDT * sizeof(bf16) + 2 * 128 * sizeof(float);
     static bool configured = false;
-    if (!configured) { (void)hipFuncSetAttribute((const void*)attn_bwd_fused128_mfma, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); configured = true; }
-    hipLaunchKernelGGL(attn_bwd_fused128_mfma, dim3(A, B), dim3(256), lds, s, (const bf16*)qkv, (const bf16*)out, lse, (const bf16*)d_out, lens,
-                       L, A, (bf16*)dqkv);
+    if (!configured) {
+      (void)hipFuncSetAttribute((const void*)attn_bwd_fused128_mfma<false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      (void)hipFuncSetAttribute((const void*)attn_bwd_fused128_mfma<true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      configured = true;
+    }
+    if (drop.thr) hipLaunchKernelGGL(attn_bwd_fused128_mfma<true>, dim3(A, B), dim3(256), lds, s, (const bf16*)qkv, (const bf16*)out, lse,
+                                     (const bf16*)d_out, lens, L, A, (bf16*)dqkv, drop, site);
+    else hipLaunchKernelGGL(attn_bwd_fused128_mfma<false>, dim3(A, B), dim3(256), lds, s, (const bf16*)qkv, (const bf16*)out, lse,
+                            (const bf16*)d_out, lens, L, A, (bf16*)dqkv, drop, site);
     return;
   }
   dim3 grid((L + 127) / 128, A, B);
-  hipLaunchKernelGGL(attn_bwd_dq_mfma, grid, dim3(256), 0, s, (const bf16*)qkv, (const bf16*)out, lse, (const bf16*)d_out, lens, L, A,
-                     (bf16*)dqkv, dvec);
-  hipLaunchKernelGGL(attn_bwd_dkv_mfma, grid, dim3(256), 0, s, (const bf16*)qkv, lse, (const bf16*)d_out, (const float*)dvec, lens, L, A,
-                     (bf16*)dqkv);
+  if (drop.thr) {
+    hipLaunchKernelGGL(attn_bwd_dq_mfma<true>, grid, dim3(256), 0, s, (const bf16*)qkv, (const bf16*)out, lse, (const bf16*)d_out, lens, L, A,
+                       (bf16*)dqkv, dvec, drop, site);
+    hipLaunchKernelGGL(attn_bwd_dkv_mfma<true>, grid, dim3(256), 0, s, (const bf16*)qkv, lse, (const bf16*)d_out, (const float*)dvec, lens, L, A,
+                       (bf16*)dqkv, drop, site);
+  } else {
+    hipLaunchKernelGGL(attn_bwd_dq_mfma<false>, grid, dim3(256), 0, s, (const bf16*)qkv, (const bf16*)out, lse, (const bf16*)d_out, lens, L, A,
+                       (bf16*)dqkv, dvec, drop, site);
+    hipLaunchKernelGGL(attn_bwd_dkv_mfma<false>, grid, dim3(256), 0, s, (const bf16*)qkv, lse, (const bf16*)d_out, (const float*)dvec, lens, L, A,
+                       (bf16*)dqkv, drop, site);
+  }
 }

@@ -55,6 +55,49 @@ __device__ __forceinline__ void normal_cdf_pdf(float x, float& cdf, float& pdf) 
 __device__ __forceinline__ float gelu_fast(float x) { float c, d; normal_cdf_pdf(x, c, d); return x * c; }
 __device__ __forceinline__ float gelu_grad_fast(float x) { float c, d; normal_cdf_pdf(x, c, d); return fmaf(x, d, c); }
 
+// ---- dropout with a counter-based generator ---------------------------------------------------
+// Philox4x32 with 10 rounds (Salmon, Moraes, Dror, Shaw, "Parallel random numbers: as easy as 1, 2, 3",
+// SC'11), from its published definition.  Element e of dropout site `site` uses word e % 4 of the block
+// with counter (e / 4 low, e / 4 high, site, stream) under the key (seed low, seed high) and is dropped
+// when that word is below thr = floor(p * 2^32); survivors are scaled by 1 / (1 - p).  thr == 0: off.
+struct DropCfg {
+  uint32_t thr;
+  float scale;
+  uint32_t k0, k1;
+  uint32_t stream;
+};
+__device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0, uint32_t k1,
+                                              uint32_t (&out)[4]) {
+#pragma unroll
+  for (int round = 0; round < 10; ++round) {
+    const uint32_t hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
+    const uint32_t hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
+    c0 = hi1 ^ c1 ^ k0; c1 = lo1; c2 = hi0 ^ c3 ^ k1; c3 = lo0;
+    k0 += 0x9E3779B9u; k1 += 0xBB67AE85u;
+  }
+  out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+// factors (0 or scale) of the four elements 4*group .. 4*group + 3 of a site
+__device__ __forceinline__ void drop_factors4(const DropCfg& d, uint32_t site, uint64_t group, float (&f)[4]) {
+  uint32_t w[4];
+  philox4x32_10((uint32_t)group, (uint32_t)(group >> 32), site, d.stream, d.k0, d.k1, w);
+#pragma unroll
+  for (int t = 0; t < 4; ++t) f[t] = (w[t] >= d.thr) ? d.scale : 0.0f;
+}
+// factor of the single element e
+__device__ __forceinline__ float drop_factor1(const DropCfg& d, uint32_t site, uint64_t e) {
+  uint32_t w[4];
+  philox4x32_10((uint32_t)(e >> 2), (uint32_t)(e >> 34), site, d.stream, d.k0, d.k1, w);
+  const uint32_t x = (e & 3) == 0 ? w[0] : ((e & 3) == 1 ? w[1] : ((e & 3) == 2 ? w[2] : w[3]));
+  return (x >= d.thr) ? d.scale : 0.0f;
+}
+// site numbers: the embedding output, then per layer the attention probabilities, the attention
+// output and the feed-forward output (the last two before the residual is added)
+__host__ __device__ static inline uint32_t site_embedding() { return 0; }
+__host__ __device__ static inline uint32_t site_attention_prob(int layer) { return 1 + 3 * (uint32_t)layer; }
+__host__ __device__ static inline uint32_t site_attention_out(int layer) { return 2 + 3 * (uint32_t)layer; }
+__host__ __device__ static inline uint32_t site_ffn_out(int layer) { return 3 + 3 * (uint32_t)layer; }
+
 // ---- kernel classes for the optional per-launch timing ---------------------------------
 enum KClass {
   KC_GEMM_FWD = 0,   // A k-major, B k-major   (y = x W^T)
@@ -106,6 +149,7 @@ struct hs_ctx {
   // activation-gradient chain, with the events that order the two (created on first use)
   hipStream_t side;
   std::vector<hipEvent_t> events;
+  DropCfg drop;    // dropout of the forward/backward calls on this context (thr == 0: off)
 };
 
 hs_status hs_fail(hs_ctx* ctx, hs_status st, const std::string& msg);  // records msg, returns st
@@ -130,29 +174,36 @@ struct GemmArgs {
   const void* bias;
   int epi; const void* aux; int64_t ldaux; void* C2;
   void* ws; size_t ws_bytes;   // optional scratch for split-K partial sums
+  const DropCfg* drop; uint32_t drop_site;   // optional (epi == 1): dropout of product + bias before the residual
 };
 hs_status launch_gemm(hs_ctx* ctx, const GemmArgs& g, hipStream_t s);
 
 hs_status launch_layernorm_fwd(hs_ctx* ctx, int dtype, const void* x, const void* gain, const void* bias, void* y,
                                float* stats, int R, int H, float eps, hipStream_t s);
 size_t layernorm_bwd_scratch(int R, int H);
+// drop_mode 0: no dropout.  1: dy is the gradient of this LayerNorm's dropped output (site) and is masked as
+// it is read.  2: dx also feeds a dropped branch (site): dxm gets its masked copy and d_colsum sums that copy.
 hs_status launch_layernorm_bwd(hs_ctx* ctx, int dtype, const void* dy, const void* x, const float* stats, const void* gain,
                                void* dx, float* d_gain, float* d_bias, float* d_colsum, float beta, int R, int H,
-                               void* partials, hipStream_t s);
+                               void* partials, hipStream_t s, const DropCfg* drop = nullptr, uint32_t site = 0, int drop_mode = 0,
+                               void* dxm = nullptr);
 hs_status launch_layernorm_bwd_rows(hs_ctx* ctx, int dtype, const void* dy, const void* x, const float* stats, const void* gain, void* dx,
-                                    int R, int H, void* partials, hipStream_t s);
+                                    int R, int H, void* partials, hipStream_t s, const DropCfg* drop = nullptr, uint32_t site = 0,
+                                    int drop_mode = 0, void* dxm = nullptr);
 hs_status launch_layernorm_bwd_cols(hs_ctx* ctx, const void* partials, float* d_gain, float* d_bias, float* d_colsum, float beta, int R, int H,
                                     hipStream_t s);
 hs_status launch_embed_ln_fwd(hs_ctx* ctx, int dtype, const void* word, const void* pos, const void* gain, const void* bias,
                               const int32_t* ids, void* e_pre, void* x0, float* stats, int B, int L, int H, int V, float eps,
-                              hipStream_t s);
+                              hipStream_t s, const DropCfg* drop = nullptr);
 size_t embed_bwd_scratch(int T, int H);
 hs_status launch_embed_bwd(hs_ctx* ctx, int dtype, const void* de, const int32_t* ids, int B, int L, int H, int V, int max_pos,
                            float* g_word, float* g_pos, float beta_pos, void* scratch, hipStream_t s);
+// drop/site: dropout of the attention probabilities (element ((b*A + h)*L + query)*L + key of the site)
 hs_status launch_attention_fwd(hs_ctx* ctx, int dtype, const void* qkv, const int32_t* lens, int B, int L, int A, void* out,
-                               float* lse, hipStream_t s);
+                               float* lse, hipStream_t s, const DropCfg* drop = nullptr, uint32_t site = 0);
 hs_status launch_attention_bwd(hs_ctx* ctx, int dtype, const void* qkv, const void* out, const float* lse, const void* d_out,
-                               const int32_t* lens, int B, int L, int A, void* dqkv, float* dvec, hipStream_t s);
+                               const int32_t* lens, int B, int L, int A, void* dqkv, float* dvec, hipStream_t s,
+                               const DropCfg* drop = nullptr, uint32_t site = 0);
 size_t colsum_scratch(int R, int C);
 hs_status launch_colsum(hs_ctx* ctx, int dtype, const void* x, int64_t ldx, int R, int C, float* out, float beta, void* partials,
                         hipStream_t s);

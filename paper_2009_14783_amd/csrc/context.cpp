@@ -117,6 +117,7 @@ hs_status hs_ctx_create(const hs_model_cfg* cfg, hs_ctx** out) {
   hs_model_offsets(*cfg, &c->off);
   c->prof = nullptr;
   c->side = nullptr;
+  c->drop = DropCfg{0u, 1.0f, 0u, 0u, 0u};
   *out = c;
   return HS_OK;
 }
@@ -331,5 +332,18 @@ extern "C" hs_status hs_checkpoint_read(const char* path, hs_ckpt_header* header
   uint64_t stored = 0;
   if (fread(&stored, 1, sizeof(stored), in.f) != sizeof(stored) || stored != sum.h)
     return hs_fail(nullptr, HS_ERR_STATE, std::string("checkpoint: checksum mismatch in ") + path);
+  return HS_OK;
+}
+
+// ---- dropout state of a context ------------------------------------------------------------------
+extern "C" hs_status hs_set_dropout(hs_ctx* ctx, double p, uint64_t seed, uint32_t stream) {
+  if (!ctx) return hs_fail(nullptr, HS_ERR_INVALID_ARG, "hs_set_dropout: ctx is NULL");
+  if (!(p >= 0.0) || !(p < 1.0)) return hs_fail(ctx, HS_ERR_INVALID_ARG, "hs_set_dropout: p must be in [0, 1)");
+  const double t = std::floor(p * 4294967296.0);
+  ctx->drop.thr = (uint32_t)(t > 4294967295.0 ? 4294967295.0 : t);
+  ctx->drop.scale = (float)(1.0 / (1.0 - p));
+  ctx->drop.k0 = (uint32_t)(seed & 0xffffffffull);
+  ctx->drop.k1 = (uint32_t)(seed >> 32);
+  ctx->drop.stream = stream;
   return HS_OK;
 }

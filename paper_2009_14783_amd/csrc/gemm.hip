@@ -15,12 +15,36 @@ struct GemmDev {
   float beta;
   float* partial;      // split-K partial sums [splits][M][N], or null
   int k_per_split;     // multiple of the k-tile
+  DropCfg drop;        // dropout of (product + bias) before the residual is added (epi == 1 only; thr == 0: off)
+  uint32_t drop_site;  // element index of the site = row * N + col
 };
+
+// dropout factors of n (4 or 8) consecutive output columns of one row, starting at a column that is a
+// multiple of 4: one generator block per four columns when the row length allows it
+template <int NV>
+__device__ __forceinline__ void drop_row_factors(const GemmDev& p, int row, int col, float (&f)[NV]) {
+  const uint64_t e = (uint64_t)row * (uint64_t)p.N + (uint64_t)col;
+  if ((p.N & 3) == 0) {
+#pragma unroll
+    for (int q = 0; q < NV / 4; ++q) {
+      float t[4];
+      drop_factors4(p.drop, p.drop_site, (e >> 2) + q, t);
+      f[4 * q] = t[0]; f[4 * q + 1] = t[1]; f[4 * q + 2] = t[2]; f[4 * q + 3] = t[3];
+    }
+  } else {
+#pragma unroll
+    for (int t = 0; t < NV; ++t) f[t] = drop_factor1(p.drop, p.drop_site, e + t);
+  }
+}
+__device__ __forceinline__ float drop_elem(const GemmDev& p, int row, int col) {
+  return drop_factor1(p.drop, p.drop_site, (uint64_t)row * (uint64_t)p.N + (uint64_t)col);
+}
 
 template <class T>
 __device__ __forceinline__ void epilogue_store(const GemmDev& p, int row, int col, float v) {
   if (row >= p.M || col >= p.N) return;
   if (p.bias) v += to_f(((const T*)p.bias)[col]);
+  if (p.epi == 1 && p.drop.thr) v *= drop_elem(p, row, col);
   if (p.epi == 1) v += to_f(((const T*)p.aux)[(int64_t)row * p.ldaux + col]);
   else if (p.epi == 3) v *= gelu_grad_f(to_f(((const T*)p.aux)[(int64_t)row * p.ldaux + col]));
   const int64_t o = (int64_t)row * p.ldc + col;
@@ -57,6 +81,11 @@ __device__ __forceinline__ void store_quad(const GemmDev& p, int row, int col, f
       *C = v;
     } else {
       const int64_t o = (int64_t)row * p.ldc + col;
+      if (MODE == EPI_ACT_RES && p.drop.thr) {
+        float f[4];
+        drop_row_factors<4>(p, row, col, f);
+        v.x *= f[0]; v.y *= f[1]; v.z *= f[2]; v.w *= f[3];
+      }
       if (MODE == EPI_ACT_RES || MODE == EPI_ACT_DGELU) {
         const bf16x4 a = *(const bf16x4*)(aux + (int64_t)row * p.ldaux + col);
         if (MODE == EPI_ACT_RES) { v.x += (float)a[0]; v.y += (float)a[1]; v.z += (float)a[2]; v.w += (float)a[3]; }
@@ -84,6 +113,7 @@ __device__ __forceinline__ void store_quad(const GemmDev& p, int row, int col, f
         *C = (p.beta != 0.0f) ? p.beta * *C + x : x;
       } else {
         const int64_t o = (int64_t)row * p.ldc + col + t;
+        if (MODE == EPI_ACT_RES && p.drop.thr) x *= drop_elem(p, row, col + t);
         if (MODE == EPI_ACT_RES) x += (float)aux[(int64_t)row * p.ldaux + col + t];
         if (MODE == EPI_ACT_DGELU) x *= gelu_grad_fast((float)aux[(int64_t)row * p.ldaux + col + t]);
         ((bf16*)p.C)[o] = (bf16)x;
@@ -138,6 +168,7 @@ __device__ __forceinline__ void tile_epilogue(const GemmDev& p, const f32x16 (&a
             float* C = (float*)p.C + oc + j * 32;
             *C = (p.beta != 0.0f) ? p.beta * *C + v : v;
           } else {
+            if (MODE == EPI_ACT_RES && p.drop.thr) v *= drop_elem(p, row, col0 + j * 32);
             if (MODE == EPI_ACT_RES) v += (float)((const bf16*)p.aux)[oa + j * 32];
             if (MODE == EPI_ACT_DGELU) v *= gelu_grad_fast((float)((const bf16*)p.aux)[oa + j * 32]);
             ((bf16*)p.C)[oc + j * 32] = (bf16)v;
@@ -181,6 +212,12 @@ __device__ __forceinline__ void store_octet(const GemmDev& p, int row, int col, 
       *(float4*)(C + 4) = make_float4(v[4], v[5], v[6], v[7]);
     } else {
       const int64_t o = (int64_t)row * p.ldc + col;
+      if (MODE == EPI_ACT_RES && p.drop.thr) {
+        float f[8];
+        drop_row_factors<8>(p, row, col, f);
+#pragma unroll
+        for (int t = 0; t < 8; ++t) v[t] *= f[t];
+      }
       if (MODE == EPI_ACT_RES || MODE == EPI_ACT_DGELU) {
         const bf16x8 a = *(const bf16x8*)(aux + (int64_t)row * p.ldaux + col);
 #pragma unroll
@@ -209,6 +246,7 @@ __device__ __forceinline__ void store_octet(const GemmDev& p, int row, int col, 
         *C = (p.beta != 0.0f) ? p.beta * *C + x : x;
       } else {
         const int64_t o = (int64_t)row * p.ldc + col + t;
+        if (MODE == EPI_ACT_RES && p.drop.thr) x *= drop_elem(p, row, col + t);
         if (MODE == EPI_ACT_RES) x += (float)aux[(int64_t)row * p.ldaux + col + t];
         if (MODE == EPI_ACT_DGELU) x *= gelu_grad_fast((float)aux[(int64_t)row * p.ldaux + col + t]);
         ((bf16*)p.C)[o] = (bf16)x;
@@ -618,6 +656,8 @@ hs_status launch_gemm(hs_ctx* ctx, const GemmArgs& g, hipStream_t s) {
   p.lda = g.lda; p.ldb = g.ldb; p.ldc = g.ldc; p.ldaux = g.ldaux;
   p.M = g.M; p.N = g.N; p.K = g.K; p.c_f32 = g.c_f32; p.epi = g.epi; p.beta = g.beta;
   p.partial = nullptr; p.k_per_split = g.K;
+  p.drop = (g.drop && g.drop->thr && g.epi == 1) ? *g.drop : DropCfg{0u, 1.0f, 0u, 0u, 0u};
+  p.drop_site = g.drop_site;
   const double flops = 2.0 * g.M * g.N * (double)g.K;
   const double bytes = ((double)g.M * g.K + (double)g.N * g.K) * esize(g.dtype) + (double)g.M * g.N * (g.c_f32 ? 4 : esize(g.dtype));
   const int kc = (g.a_kmajor && g.b_kmajor) ? KC_GEMM_FWD : (g.a_kmajor ? KC_GEMM_DX : KC_GEMM_DW);

@@ -79,6 +79,14 @@ __global__ void key_mask_kernel(const int32_t* __restrict__ lens, int B, int L, 
   mask[i] = (l < lens[b]) ? 1 : 0;
 }
 
+__global__ void keep_mask_kernel(DropCfg d, uint32_t site, size_t n, uint8_t* __restrict__ mask) {
+  const size_t g = (size_t)blockIdx.x * blockDim.x + threadIdx.x;     // one group of four elements per thread
+  if (4 * g >= n) return;
+  float f[4];
+  drop_factors4(d, site, g, f);
+  for (int t = 0; t < 4; ++t) if (4 * g + t < n) mask[4 * g + t] = f[t] != 0.0f ? 1 : 0;
+}
+
 unsigned flat_grid(size_t work_items) {
   size_t blocks = (work_items + 255) / 256;
   if (blocks < 1) blocks = 1;
@@ -133,6 +141,15 @@ hs_status hs_cast_params(const float* src, void* dst, size_t n, int32_t dst_dtyp
   else if (dst_dtype == HS_FP32) hipLaunchKernelGGL(cast_kernel<float>, dim3(flat_grid(n)), dim3(256), 0, (hipStream_t)stream, src, (float*)dst, n);
   else return hs_fail(nullptr, HS_ERR_INVALID_ARG, "hs_cast_params: bad dtype");
   return check_launch("hs_cast_params");
+}
+
+hs_status hs_dropout_keep_mask(hs_ctx* ctx, uint32_t site, size_t n, uint8_t* mask_out, void* stream) {
+  if (!ctx) return hs_fail(nullptr, HS_ERR_INVALID_ARG, "hs_dropout_keep_mask: ctx is NULL");
+  if (n == 0) return HS_OK;
+  if (!mask_out) return hs_fail(ctx, HS_ERR_INVALID_ARG, "hs_dropout_keep_mask: NULL buffer");
+  const size_t groups = (n + 3) / 4;
+  hipLaunchKernelGGL(keep_mask_kernel, dim3((unsigned)((groups + 255) / 256)), dim3(256), 0, (hipStream_t)stream, ctx->drop, site, n, mask_out);
+  return check_launch("hs_dropout_keep_mask");
 }
 
 hs_status hs_key_mask(const int32_t* lens, int32_t B, int32_t L, uint8_t* mask_out, void* stream) {

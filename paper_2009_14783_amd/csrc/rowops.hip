@@ -35,7 +35,8 @@ template <> struct Vec4<bf16> {
 // ------------------------------------------------------------------------------------------
 template <class T>
 __device__ __forceinline__ void ln_row(float4 (&v)[MAXCH], int nch, int H, int lane, const T* __restrict__ gain,
-                                       const T* __restrict__ bias, float eps, T* __restrict__ y, float* mean_out, float* rstd_out) {
+                                       const T* __restrict__ bias, float eps, T* __restrict__ y, float* mean_out, float* rstd_out,
+                                       const DropCfg* drop = nullptr, uint32_t site = 0, int64_t row = 0) {
   float s = 0.f;
 #pragma unroll
   for (int c = 0; c < MAXCH; ++c) if (c * 64 + lane < nch) s += (v[c].x + v[c].y) + (v[c].z + v[c].w);
@@ -55,6 +56,11 @@ __device__ __forceinline__ void ln_row(float4 (&v)[MAXCH], int nch, int H, int l
     float4 o;
     o.x = (v[c].x - mu) * rstd * g.x + b.x; o.y = (v[c].y - mu) * rstd * g.y + b.y;
     o.z = (v[c].z - mu) * rstd * g.z + b.z; o.w = (v[c].w - mu) * rstd * g.w + b.w;
+    if (drop) {                                   // dropout of the output: one generator block per chunk
+      float f[4];
+      drop_factors4(*drop, site, (uint64_t)(row * H + col) >> 2, f);
+      o.x *= f[0]; o.y *= f[1]; o.z *= f[2]; o.w *= f[3];
+    }
     Vec4<T>::st(y + col, o);
   }
   if (lane == 0) { *mean_out = mu; *rstd_out = rstd; }
@@ -77,7 +83,7 @@ template <class T>
 __global__ __launch_bounds__(256) void embed_ln_fwd_kernel(const T* __restrict__ word, const T* __restrict__ pos,
                                                            const T* __restrict__ gain, const T* __restrict__ bias,
                                                            const int32_t* __restrict__ ids, T* __restrict__ e_pre, T* __restrict__ x0,
-                                                           float* __restrict__ stats, int R, int L, int H, int V, float eps) {
+                                                           float* __restrict__ stats, int R, int L, int H, int V, float eps, DropCfg drop) {
   const int lane = threadIdx.x & 63;
   const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= R) return;
@@ -95,17 +101,21 @@ __global__ __launch_bounds__(256) void embed_ln_fwd_kernel(const T* __restrict__
     Vec4<T>::st(e_pre + (int64_t)row * H + col, e);
     v[c] = e;
   }
-  ln_row<T>(v, nch, H, lane, gain, bias, eps, x0 + (int64_t)row * H, stats + row, stats + R + row);
+  ln_row<T>(v, nch, H, lane, gain, bias, eps, x0 + (int64_t)row * H, stats + row, stats + R + row, drop.thr ? &drop : nullptr,
+            site_embedding(), row);
 }
 
 // ------------------------------------------------------------------------------------------
 // LayerNorm backward.  Each wave walks rows with a fixed stride and keeps per-column partial
 // sums of dy*xhat, dy and dx; blocks write partials, a second kernel adds them in block order.
 // ------------------------------------------------------------------------------------------
-template <class T>
+template <class T, int drop_mode>
 __global__ __launch_bounds__(256) void ln_bwd_kernel(const T* __restrict__ dy, const T* __restrict__ x, const float* __restrict__ stats,
                                                      const T* __restrict__ gain, T* __restrict__ dx, float* __restrict__ partials,
-                                                     int R, int H) {
+                                                     int R, int H, DropCfg drop, uint32_t site, T* __restrict__ dxm) {
+  // drop_mode 1: dy is the gradient of a dropped OUTPUT of this LayerNorm and is masked as it is read.
+  // drop_mode 2: dx feeds a dropped branch (site) besides a residual path: dxm gets the masked copy and the
+  //              column sums of dx (the bias gradient of that branch) are taken over the masked values.
   __shared__ float4 red[4][MAXCH * 64];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int nch = H / 4;
@@ -136,6 +146,14 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(const T* __restrict__ dy, c
     float4 xh[MAXCH], dyv[MAXCH];
 #pragma unroll
     for (int c = 0; c < MAXCH; ++c) { xh[c] = nx[c]; dyv[c] = ndy[c]; }
+    if (drop_mode == 1) {
+#pragma unroll
+      for (int c = 0; c < MAXCH; ++c) if (c * 64 + lane < nch) {
+        float f[4];
+        drop_factors4(drop, site, (uint64_t)((int64_t)row * H + 4 * (c * 64 + lane)) >> 2, f);
+        dyv[c].x *= f[0]; dyv[c].y *= f[1]; dyv[c].z *= f[2]; dyv[c].w *= f[3];
+      }
+    }
     const int next = row + stride;
     if (next < R) {
       nmu = stats[next]; nrstd = stats[R + next];
@@ -162,11 +180,20 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(const T* __restrict__ dy, c
       float4 d;
       d.x = rstd * (dyv[c].x * g[c].x - s1 - xh[c].x * s2); d.y = rstd * (dyv[c].y * g[c].y - s1 - xh[c].y * s2);
       d.z = rstd * (dyv[c].z * g[c].z - s1 - xh[c].z * s2); d.w = rstd * (dyv[c].w * g[c].w - s1 - xh[c].w * s2);
+      float4 dm = d;
       d = Vec4<T>::round(d);
       Vec4<T>::st(dx + (int64_t)row * H + 4 * (c * 64 + lane), d);
+      if (drop_mode == 2) {
+        float f[4];
+        drop_factors4(drop, site, (uint64_t)((int64_t)row * H + 4 * (c * 64 + lane)) >> 2, f);
+        dm = Vec4<T>::round(make_float4(dm.x * f[0], dm.y * f[1], dm.z * f[2], dm.w * f[3]));
+        Vec4<T>::st(dxm + (int64_t)row * H + 4 * (c * 64 + lane), dm);
+      } else {
+        dm = d;
+      }
       ag[c].x += dyv[c].x * xh[c].x; ag[c].y += dyv[c].y * xh[c].y; ag[c].z += dyv[c].z * xh[c].z; ag[c].w += dyv[c].w * xh[c].w;
       ab[c].x += dyv[c].x; ab[c].y += dyv[c].y; ab[c].z += dyv[c].z; ab[c].w += dyv[c].w;
-      as[c].x += d.x; as[c].y += d.y; as[c].z += d.z; as[c].w += d.w;
+      as[c].x += dm.x; as[c].y += dm.y; as[c].z += dm.z; as[c].w += dm.w;
     }
   }
   // combine the four waves of the block in wave order, one quantity at a time
@@ -582,12 +609,19 @@ size_t layernorm_bwd_scratch(int R, int H) { return align_up((size_t)ln_bwd_bloc
 
 // main kernel: dx and the per-block partial column sums
 hs_status launch_layernorm_bwd_rows(hs_ctx* ctx, int dtype, const void* dy, const void* x, const float* stats, const void* gain, void* dx,
-                                    int R, int H, void* partials, hipStream_t s) {
+                                    int R, int H, void* partials, hipStream_t s, const DropCfg* drop, uint32_t site, int drop_mode,
+                                    void* dxm) {
   if (R <= 0) return HS_OK;
   const int nb = ln_bwd_blocks(R);
   KScope scope(prof_of(ctx), KC_LN_BWD, 14.0 * R * H, 3.0 * R * H * esize(dtype), s);
-  if (dtype == HS_BF16) hipLaunchKernelGGL(ln_bwd_kernel<bf16>, dim3(nb), dim3(256), 0, s, (const bf16*)dy, (const bf16*)x, stats, (const bf16*)gain, (bf16*)dx, (float*)partials, R, H);
-  else hipLaunchKernelGGL(ln_bwd_kernel<float>, dim3(nb), dim3(256), 0, s, (const float*)dy, (const float*)x, stats, (const float*)gain, (float*)dx, (float*)partials, R, H);
+  DropCfg d{0u, 1.0f, 0u, 0u, 0u};
+  if (drop && drop->thr && drop_mode) d = *drop; else drop_mode = 0;
+  if (drop_mode == 2 && !dxm) return hs_fail(ctx, HS_ERR_INVALID_ARG, "layernorm_bwd: masked output buffer missing");
+#define HS_LN_BWD(TT, MODE) hipLaunchKernelGGL((ln_bwd_kernel<TT, MODE>), dim3(nb), dim3(256), 0, s, (const TT*)dy, (const TT*)x, stats, \
+                                              (const TT*)gain, (TT*)dx, (float*)partials, R, H, d, site, (TT*)dxm)
+  if (dtype == HS_BF16) { if (drop_mode == 0) HS_LN_BWD(bf16, 0); else if (drop_mode == 1) HS_LN_BWD(bf16, 1); else HS_LN_BWD(bf16, 2); }
+  else { if (drop_mode == 0) HS_LN_BWD(float, 0); else if (drop_mode == 1) HS_LN_BWD(float, 1); else HS_LN_BWD(float, 2); }
+#undef HS_LN_BWD
   LAUNCH_CHECK(ctx, "layernorm_bwd");
   return HS_OK;
 }
@@ -602,20 +636,23 @@ hs_status launch_layernorm_bwd_cols(hs_ctx* ctx, const void* partials, float* d_
   return HS_OK;
 }
 hs_status launch_layernorm_bwd(hs_ctx* ctx, int dtype, const void* dy, const void* x, const float* stats, const void* gain, void* dx,
-                               float* d_gain, float* d_bias, float* d_colsum, float beta, int R, int H, void* partials, hipStream_t s) {
-  hs_status st = launch_layernorm_bwd_rows(ctx, dtype, dy, x, stats, gain, dx, R, H, partials, s);
+                               float* d_gain, float* d_bias, float* d_colsum, float beta, int R, int H, void* partials, hipStream_t s,
+                               const DropCfg* drop, uint32_t site, int drop_mode, void* dxm) {
+  hs_status st = launch_layernorm_bwd_rows(ctx, dtype, dy, x, stats, gain, dx, R, H, partials, s, drop, site, drop_mode, dxm);
   if (st != HS_OK) return st;
   return launch_layernorm_bwd_cols(ctx, partials, d_gain, d_bias, d_colsum, beta, R, H, s);
 }
 
 hs_status launch_embed_ln_fwd(hs_ctx* ctx, int dtype, const void* word, const void* pos, const void* gain, const void* bias,
-                              const int32_t* ids, void* e_pre, void* x0, float* stats, int B, int L, int H, int V, float eps, hipStream_t s) {
+                              const int32_t* ids, void* e_pre, void* x0, float* stats, int B, int L, int H, int V, float eps, hipStream_t s,
+                              const DropCfg* drop) {
+  const DropCfg dcfg = (drop && drop->thr) ? *drop : DropCfg{0u, 1.0f, 0u, 0u, 0u};
   const int R = B * L;
   if (R <= 0) return HS_OK;
   KScope scope(prof_of(ctx), KC_EMBED, 10.0 * R * H, 4.0 * R * H * esize(dtype), s);
   dim3 grid((R + 3) / 4);
-  if (dtype == HS_BF16) hipLaunchKernelGGL(embed_ln_fwd_kernel<bf16>, grid, dim3(256), 0, s, (const bf16*)word, (const bf16*)pos, (const bf16*)gain, (const bf16*)bias, ids, (bf16*)e_pre, (bf16*)x0, stats, R, L, H, V, eps);
-  else hipLaunchKernelGGL(embed_ln_fwd_kernel<float>, grid, dim3(256), 0, s, (const float*)word, (const float*)pos, (const float*)gain, (const float*)bias, ids, (float*)e_pre, (float*)x0, stats, R, L, H, V, eps);
+  if (dtype == HS_BF16) hipLaunchKernelGGL(embed_ln_fwd_kernel<bf16>, grid, dim3(256), 0, s, (const bf16*)word, (const bf16*)pos, (const bf16*)gain, (const bf16*)bias, ids, (bf16*)e_pre, (bf16*)x0, stats, R, L, H, V, eps, dcfg);
+  else hipLaunchKernelGGL(embed_ln_fwd_kernel<float>, grid, dim3(256), 0, s, (const float*)word, (const float*)pos, (const float*)gain, (const float*)bias, ids, (float*)e_pre, (float*)x0, stats, R, L, H, V, eps, dcfg);
   LAUNCH_CHECK(ctx, "embed_ln_fwd");
   return HS_OK;
 }

@@ -37,6 +37,7 @@ class Worker:
         else:
             self.w_lowp = None
         self.t = 0
+        self._drop_on = False
         self._acts = self._ws = self._hidden = self._dhidden = None
         self._acts_bytes = self._ws_bytes = 0
         self.loss_buf = torch.zeros(64, dtype=torch.float32, device=dev)
@@ -74,7 +75,7 @@ class Worker:
                    lens=torch.from_numpy(np.ascontiguousarray(mb["lens"], dtype=np.int32)).to(dev),
                    mlm_pos=torch.from_numpy(np.ascontiguousarray(mb["mlm_pos"], dtype=np.int32)).to(dev),
                    mlm_label=torch.from_numpy(np.ascontiguousarray(mb["mlm_label"], dtype=np.int32)).to(dev),
-                   n_seq=int(mb["ids"].shape[0]))
+                   n_seq=int(mb["ids"].shape[0]), drop=mb.get("drop"))
         self._reserve(out["B"], out["L"], out["M"])
         return out
 
@@ -82,6 +83,10 @@ class Worker:
         """hs_encoder_fwd -> hs_mlm_loss -> hs_encoder_bwd for one uploaded micro-batch."""
         B, L, M = d["B"], d["L"], d["M"]
         self._reserve(B, L, M)
+        drop = d.get("drop")           # dict(p, seed, stream) or None: the state both calls below must see
+        if drop is not None or self._drop_on:
+            hs.hs_set_dropout(self.ctx, drop["p"] if drop else 0.0, drop["seed"] if drop else 0, drop["stream"] if drop else 0)
+            self._drop_on = drop is not None
         w = self.w_compute
         hs.hs_encoder_fwd(self.ctx, w, d["ids"], d["lens"], d["lens_host"], B, L, self._acts, self._hidden, self._ws,
                           self._ws_bytes)

@@ -135,9 +135,14 @@ def concat_micro_batches(mbs: list) -> dict:
                 n_real_tokens=int(lens.sum()))
 
 
-def step_micro_batches(seed: int, t: int, lens, L: int, vocab: int, dist: str, n_micro: int = 1) -> list:
+def step_micro_batches(seed: int, t: int, lens, L: int, vocab: int, dist: str, n_micro: int = 1, dropout: float = 0.0) -> list:
     """The micro-batches of update number t of a multi-step run: drawn from a generator seeded with
     seed + t, so that a run resumed after any number of updates sees the same data as an
-    uninterrupted one (the seed is part of a checkpoint)."""
+    uninterrupted one (the seed is part of a checkpoint).  With dropout > 0 every micro-batch carries
+    its dropout state: the run's seed and a stream number of its own (64 t + index)."""
     rng = rng_for(seed + t)
-    return [make_micro_batch(rng, lens, L, vocab, dist) for _ in range(n_micro)]
+    out = [make_micro_batch(rng, lens, L, vocab, dist) for _ in range(n_micro)]
+    if dropout > 0.0:
+        for i, mb in enumerate(out):
+            mb["drop"] = dict(p=dropout, seed=seed, stream=64 * t + i)
+    return out

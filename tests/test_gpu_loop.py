@@ -40,13 +40,29 @@ def test_loss_curve_of_100_updates_follows_oracle_fp32():
     wk.close()
 
 
-@pytest.mark.parametrize("compute", ["fp32", "bf16"])
-def test_resume_from_checkpoint_is_bit_exact(tmp_path, compute):
+def test_loss_curve_with_dropout_follows_oracle_fp32():
+    cfg = hs.make_cfg(**TINY, compute=hs.HS_FP32)
+    theta = synth.init_params(hs.hs_param_layout(cfg), 555)
+    sched = dict(max_lr=1e-3, warmup=5, total=40)
+    data = lambda t: synth.step_micro_batches(31, t, LENS, 64, TINY["vocab"], "uniform", 2, 0.1)
+    st = dict(theta=theta.copy(), m=np.zeros_like(theta), v=np.zeros_like(theta), step=0)
+    want = np.array(O.train_loop(O.ModelCfg(**TINY), st, 40, data, ADAM, sched))
+    wk = Worker(TINY, "fp32", theta)
+    got = np.array(wk.train(40, data, ADAM, sched))
+    torch.cuda.synchronize()
+    rel = np.abs(got - want) / np.abs(want)
+    print(f"with dropout 0.1: max relative deviation over 40 updates {rel.max():.2e}")
+    assert rel.max() < 1e-4
+    wk.close()
+
+
+@pytest.mark.parametrize("compute,dropout", [("fp32", 0.0), ("bf16", 0.0), ("bf16", 0.1)])
+def test_resume_from_checkpoint_is_bit_exact(tmp_path, compute, dropout):
     cfg = hs.make_cfg(**TINY)
     theta = synth.init_params(hs.hs_param_layout(cfg), 77)
     sched = dict(max_lr=2e-3, warmup=3, total=12)
     seed = 2024
-    data = lambda t: (synth.step_micro_batches(seed, t, LENS, 64, TINY["vocab"], "uniform", 2) + [None])   # a worker without data too
+    data = lambda t: (synth.step_micro_batches(seed, t, LENS, 64, TINY["vocab"], "uniform", 2, dropout) + [None])   # a worker without data too
     full = Worker(TINY, compute, theta)
     l_full = full.train(9, data, ADAM, sched)
     a = Worker(TINY, compute, theta)
@@ -58,7 +74,7 @@ def test_resume_from_checkpoint_is_bit_exact(tmp_path, compute):
     adam, sched_b, seed_b, epoch = b.load_checkpoint(path)
     assert (seed_b, epoch, b.t) == (seed, 1, 4) and sched_b == sched
     assert adam == dict(ADAM, weight_decay=0.0)
-    data_b = lambda t: (synth.step_micro_batches(seed_b, t, LENS, 64, TINY["vocab"], "uniform", 2) + [None])
+    data_b = lambda t: (synth.step_micro_batches(seed_b, t, LENS, 64, TINY["vocab"], "uniform", 2, dropout) + [None])
     l_b = b.train(5, data_b, adam, sched_b)
     torch.cuda.synchronize()
     assert l_a + l_b == l_full
