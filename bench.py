@@ -94,6 +94,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--profile-steps", type=int, default=3, help="extra steps with per-kernel event timing")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--dropout", type=float, default=0.0,
+                    help="dropout rate at the model's four kinds of sites (the headline figure is taken without: 0)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus must be 1 (no collectives, no sharding in this path)",
@@ -117,6 +119,9 @@ def main():
     mbs = synth.workload_micro_batches(widx)
     lengths = np.concatenate([mb["lens"] for mb in mbs]).astype(np.int32)
     worker = Worker(model, wl["compute"], theta)
+    if args.dropout > 0.0:
+        for i, mb in enumerate(mbs):
+            mb["drop"] = dict(p=args.dropout, seed=wl["seed"], stream=i)
     dev_batches = [worker.upload(mb) for mb in mbs]      # inputs resident in HBM before timing
     tokens_per_step = int(sum(mb["n_real_tokens"] for mb in mbs))
     flops_per_step = algorithmic_flops(model, mbs)
@@ -207,7 +212,7 @@ def main():
                                     "tied MLM head; 64 sequences x 128 tokens (max-tokens cap 8192), Zipf(1.1) ids, 15% MLM "
                                     "targets, bf16 compute with fp32 master weights and accumulation",
                            tokens_per_step=tokens_per_step, mlm_targets=int(sum(d["M"] for d in dev_batches)),
-                           global_batch=D, seq_len=128, params=P),
+                           global_batch=D, seq_len=128, params=P, dropout=args.dropout),
                whole_step_tflops=flops_per_step / (ms_per_step * 1e-3) / 1e12,
                whole_step_mfma_frac=flops_per_step / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
                loss=loss, roofline=roofline, kernels=kernels)

@@ -91,6 +91,22 @@ size_t hs_acts_bytes(const hs_model_cfg* cfg, int32_t B, int32_t L, int32_t M);
  * maximum over the three calls, so one buffer serves all. */
 size_t hs_workspace_bytes(const hs_model_cfg* cfg, int32_t B, int32_t L, int32_t M);
 
+/* ---- optimizer update inside the last backward pass ----------------------------------------
+ * Sections "Backpropagation" / "Optimizer and Learning Rate Scheduler": once the gradients of all
+ * micro-batches are summed, they are divided by the global weight and the optimizer updates the
+ * parameters.  hs_arm_update arms exactly that (hs_grad_accum_normalize with `denom`, then
+ * hs_adam_step with the given arguments, same arithmetic, same results bit for bit) for the NEXT
+ * hs_encoder_bwd call on ctx whose gradient buffer g is G: that call then normalises and updates
+ * every parameter group (head, each layer, embeddings) on a stream of its own as soon as the
+ * group's gradient is final, beside the rest of the backward pass, and joins that work before it
+ * returns work to the caller's stream.  Arm it for the LAST micro-batch of an update only (denom is
+ * the global sample count of the whole update); hs_mlm_loss of that micro-batch must already have been
+ * enqueued on the same stream with the same G.  All pointers dev, sizes = hs_param_count; the
+ * armed state is cleared by the backward call that consumes it (also when that call fails).
+ * HS_ERR_STATE from hs_encoder_bwd if an update is armed for another buffer. */
+hs_status hs_arm_update(hs_ctx* ctx, float* w, float* m, float* v, float* G, void* w_lowp_out /*nullable*/, double denom, double lr,
+                        double beta1, double beta2, double eps, double weight_decay, int64_t t);
+
 /* ---- dropout --------------------------------------------------------------------------------
  * Section "Transformer Translation Model" trains with dropout 0.1 and section "Checkpointing" keeps
  * the run's random seed; the cited BERT model drops its embedding output, attention probabilities,

@@ -61,6 +61,7 @@ _SIGNATURES = {
     "hs_grad_accum_normalize": (_I32, [_P, _P, _SZ, _I32, _D, _P]),
     "hs_adam_step": (_I32, [_P, _P, _P, _P, _P, _SZ, _D, _D, _D, _D, _D, _I64, _P]),
     "hs_cast_params": (_I32, [_P, _P, _SZ, _I32, _P]),
+    "hs_arm_update": (_I32, [_P, _P, _P, _P, _P, _P, _D, _D, _D, _D, _D, _D, _I64]),
     "hs_set_dropout": (_I32, [_P, _D, C.c_uint64, C.c_uint32]),
     "hs_dropout_keep_mask": (_I32, [_P, C.c_uint32, _SZ, _P, _P]),
     "hs_lr_linear": (_D, [_I64, _D, _I64, _I64]),
@@ -221,6 +222,11 @@ def hs_mlm_loss(ctx, w, hidden, mlm_pos, mlm_label, M, B, L, loss_sum, d_hidden,
 def hs_encoder_bwd(ctx, w, acts, ids, lens, B, L, d_hidden, g, accumulate, workspace, workspace_bytes, stream=None):
     _check(lib().hs_encoder_bwd(ctx, _ptr(w), _ptr(acts), _ptr(ids), _ptr(lens), B, L, _ptr(d_hidden), _ptr(g), accumulate,
                                 _ptr(workspace), workspace_bytes, _stream(stream)), ctx)
+
+
+def hs_arm_update(ctx, w, m, v, G, w_lowp_out, denom, lr, beta1, beta2, eps, weight_decay, t):
+    _check(lib().hs_arm_update(ctx, _ptr(w), _ptr(m), _ptr(v), _ptr(G), _ptr(w_lowp_out), float(denom), lr, beta1, beta2, eps,
+                               weight_decay, t), ctx)
 
 
 def hs_set_dropout(ctx, p, seed, stream_no):

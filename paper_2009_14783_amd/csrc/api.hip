@@ -261,12 +261,54 @@ hs_status hs_mlm_loss(hs_ctx* ctx, const void* w, const void* hidden, const int3
   return HS_OK;
 }
 
+hs_status hs_arm_update(hs_ctx* ctx, float* w, float* m, float* v, float* G, void* w_lowp_out, double denom, double lr, double beta1,
+                        double beta2, double eps, double weight_decay, int64_t t) {
+  if (!ctx) return HS_ERR_INVALID_ARG;
+  if (!w || !m || !v || !G) return hs_fail(ctx, HS_ERR_INVALID_ARG, "hs_arm_update: NULL buffer");
+  if (t < 1) return hs_fail(ctx, HS_ERR_INVALID_ARG, "hs_arm_update: t must be >= 1");
+  if (!(denom >= 0.0) || std::isinf(denom)) return hs_fail(ctx, HS_ERR_INVALID_ARG, "hs_arm_update: denom must be finite and >= 0");
+  if (!(beta1 >= 0.0 && beta1 < 1.0) || !(beta2 >= 0.0 && beta2 < 1.0) || !(eps >= 0.0))
+    return hs_fail(ctx, HS_ERR_INVALID_ARG, "hs_arm_update: betas must be in [0,1), eps >= 0");
+  if (((uintptr_t)w % 16) || ((uintptr_t)m % 16) || ((uintptr_t)v % 16) || ((uintptr_t)G % 16) || ((uintptr_t)w_lowp_out % 8))
+    return hs_fail(ctx, HS_ERR_INVALID_ARG, "hs_arm_update: buffers must be 16-byte aligned");
+  ctx->armed = hs_ctx::Armed{true, w, m, v, G, w_lowp_out, denom, lr, beta1, beta2, eps, weight_decay, t};
+  return HS_OK;
+}
+
+// normalise + Adam on the parameters [begin, end) of an armed update
+static hs_status update_slice(hs_ctx* ctx, const hs_ctx::Armed& u, int64_t begin, int64_t end, hipStream_t s) {
+  const size_t n = (size_t)(end - begin);
+  if (n == 0) return HS_OK;
+  hs_status st = hs_grad_accum_normalize(u.G + begin, nullptr, n, 0, u.denom, s);
+  if (st != HS_OK) return hs_fail(ctx, st, hs_last_error(nullptr));
+  void* wl = u.wl ? (void*)((bf16*)u.wl + begin) : nullptr;
+  st = hs_adam_step(u.w + begin, u.m + begin, u.v + begin, u.G + begin, wl, n, u.lr, u.beta1, u.beta2, u.eps, u.wd, u.t, s);
+  if (st != HS_OK) return hs_fail(ctx, st, hs_last_error(nullptr));
+  return HS_OK;
+}
+
+static hs_status encoder_bwd_impl(hs_ctx* ctx, const hs_ctx::Armed& upd, const void* w, const void* acts, const int32_t* ids,
+                                  const int32_t* lens, int32_t B, int32_t L, const void* d_hidden, float* g, int32_t accumulate,
+                                  void* workspace, size_t workspace_bytes, void* stream);
+
 hs_status hs_encoder_bwd(hs_ctx* ctx, const void* w, const void* acts, const int32_t* ids, const int32_t* lens, int32_t B, int32_t L,
                          const void* d_hidden, float* g, int32_t accumulate, void* workspace, size_t workspace_bytes, void* stream) {
   if (!ctx) return HS_ERR_INVALID_ARG;
+  const hs_ctx::Armed upd = ctx->armed;       // consumed by this call, whatever its outcome
+  ctx->armed.on = false;
+  if (upd.on && upd.G != g) return hs_fail(ctx, HS_ERR_STATE, "hs_encoder_bwd: an update is armed for another gradient buffer");
+  return encoder_bwd_impl(ctx, upd, w, acts, ids, lens, B, L, d_hidden, g, accumulate, workspace, workspace_bytes, stream);
+}
+
+static hs_status encoder_bwd_impl(hs_ctx* ctx, const hs_ctx::Armed& upd, const void* w, const void* acts, const int32_t* ids,
+                                  const int32_t* lens, int32_t B, int32_t L, const void* d_hidden, float* g, int32_t accumulate,
+                                  void* workspace, size_t workspace_bytes, void* stream) {
   std::string why;
   if (!shape_ok(ctx, B, L, &why)) return hs_fail(ctx, HS_ERR_SHAPE, "hs_encoder_bwd: " + why);
-  if (B == 0) return HS_OK;
+  if (B == 0) {      // nothing to back-propagate: an armed update still takes place, on the caller's stream
+    if (upd.on) return update_slice(ctx, upd, 0, ctx->off.total, (hipStream_t)stream);
+    return HS_OK;
+  }
   if (!w || !acts || !ids || !lens || !d_hidden || !g || !workspace) return hs_fail(ctx, HS_ERR_INVALID_ARG, "hs_encoder_bwd: NULL buffer");
   const hs_model_cfg& c = ctx->cfg;
   const ModelOff& o = ctx->off;
@@ -280,15 +322,36 @@ hs_status hs_encoder_bwd(hs_ctx* ctx, const void* w, const void* acts, const int
   auto run_gemm = [&](GemmArgs& a) { a.ws = ws.gemm_ws; a.ws_bytes = ws.gemm_ws_bytes; return launch_gemm(ctx, a, s); };
 
   // The weight-gradient GEMMs only consume; they run on a second stream so that their ramp-up and tail
-  // overlap the activation-gradient chain.  Per layer: four "operand ready" events (main -> side) and
+  // overlap the activation-gradient chain.  Per layer: four "operand ready" events (main -> side),
   // one "layer done" event (side -> main, waited on before the operand buffers of that parity are
   // reused two layers later and at the end of the call).  With per-launch timing enabled everything
   // stays on the caller's stream so that the timings do not overlap.
   const bool overlap = ctx->prof == nullptr;
   const int NL = c.n_layers;
-  if (overlap) HS_TRY(ensure_side_stream(ctx, (size_t)5 * NL));
+  if (overlap) HS_TRY(ensure_side_stream(ctx, (size_t)6 * NL + 3));
   hipStream_t sd = overlap ? ctx->side : s;
-  auto ev = [&](int layer, int k) { return ctx->events[(size_t)layer * 5 + k]; };
+  // third stream for an armed optimizer update (events 6 NL .. 6 NL + 2: head ready, embeddings ready, done)
+  if (overlap && upd.on && !ctx->upd) HS_HIP_CHECK(ctx, hipStreamCreateWithFlags(&ctx->upd, hipStreamNonBlocking));
+  hipStream_t su = (overlap && upd.on) ? ctx->upd : s;
+  // the update stream continues after the caller's stream has got here (the caller's stream may be the
+  // null stream, so it cannot double as a flag) ...
+  auto after_main = [&](hipEvent_t e) -> hs_status {
+    if (!overlap) return HS_OK;
+    HS_HIP_CHECK(ctx, hipEventRecord(e, s));
+    HS_HIP_CHECK(ctx, hipStreamWaitEvent(su, e, 0));
+    return HS_OK;
+  };
+  // ... or after an event that has already been recorded on the second stream
+  auto after_event = [&](hipEvent_t e) -> hs_status {
+    if (!overlap) return HS_OK;
+    HS_HIP_CHECK(ctx, hipStreamWaitEvent(su, e, 0));
+    return HS_OK;
+  };
+  if (upd.on) {      // the head's gradients were completed by hs_mlm_loss, earlier on the caller's stream
+    HS_TRY(after_main(ctx->events[(size_t)6 * NL]));
+    HS_TRY(update_slice(ctx, upd, o.head_t_w, o.total, su));
+  }
+  auto ev = [&](int layer, int k) { return ctx->events[(size_t)layer * 6 + k]; };
   auto hand_over = [&](int layer, int k) -> hs_status {      // main has produced operand k of this layer
     if (!overlap) return HS_OK;
     HS_HIP_CHECK(ctx, hipEventRecord(ev(layer, k), s));
@@ -352,11 +415,26 @@ hs_status hs_encoder_bwd(hs_ctx* ctx, const void* w, const void* acts, const int
     ga.epi = 1; ga.aux = dy1; ga.ldaux = H;
     HS_TRY(run_gemm(ga));
     dcur = ws.dxb;
+    if (upd.on) {
+      // Every gradient of this layer is final once the second stream has got to its "layer done" event, and
+      // its weights are no longer read once the main chain has finished the GEMM above.
+      HS_TRY(after_event(ev(i, 4)));
+      HS_TRY(after_main(ev(i, 5)));
+      HS_TRY(update_slice(ctx, upd, lo.qkv_w, i + 1 < NL ? o.layer[i + 1].qkv_w : o.head_t_w, su));
+    }
   }
   // embedding LayerNorm, then the two embedding tables
   HS_TRY(launch_layernorm_bwd(ctx, dt, dcur, a.e_pre, a.emb_stats, W(ctx, w, o.emb_ln_g), ws.dxa, g + o.emb_ln_g,
                               g + o.emb_ln_b, nullptr, beta, T, H, ws.ln_part, s, drop, site_embedding(), drop ? 1 : 0, nullptr));
   HS_TRY(launch_embed_bwd(ctx, dt, ws.dxa, ids, B, L, H, c.vocab, c.max_pos, g + o.emb_word, g + o.emb_pos, beta, ws.emb, s));
+  if (upd.on) {      // the embedding tables and their LayerNorm last
+    HS_TRY(after_main(ctx->events[(size_t)6 * NL + 1]));
+    HS_TRY(update_slice(ctx, upd, 0, o.layer[0].qkv_w, su));
+    if (overlap) {
+      HS_HIP_CHECK(ctx, hipEventRecord(ctx->events[(size_t)6 * NL + 2], su));
+      HS_HIP_CHECK(ctx, hipStreamWaitEvent(s, ctx->events[(size_t)6 * NL + 2], 0));
+    }
+  }
   // everything the second stream did is ordered before whatever the caller enqueues next
   if (overlap) HS_HIP_CHECK(ctx, hipStreamWaitEvent(s, ev(0, 4), 0));
   return HS_OK;

@@ -150,6 +150,10 @@ struct hs_ctx {
   hipStream_t side;
   std::vector<hipEvent_t> events;
   DropCfg drop;    // dropout of the forward/backward calls on this context (thr == 0: off)
+  // an optimizer update armed for the next backward call: each parameter group is normalised and updated
+  // on a third stream as soon as its gradient is final
+  struct Armed { bool on; float *w, *m, *v, *G; void* wl; double denom, lr, beta1, beta2, eps, wd; int64_t t; } armed;
+  hipStream_t upd;
 };
 
 hs_status hs_fail(hs_ctx* ctx, hs_status st, const std::string& msg);  // records msg, returns st

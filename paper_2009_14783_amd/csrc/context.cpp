@@ -118,6 +118,8 @@ hs_status hs_ctx_create(const hs_model_cfg* cfg, hs_ctx** out) {
   c->prof = nullptr;
   c->side = nullptr;
   c->drop = DropCfg{0u, 1.0f, 0u, 0u, 0u};
+  c->armed.on = false;
+  c->upd = nullptr;
   *out = c;
   return HS_OK;
 }
@@ -127,6 +129,7 @@ hs_status hs_ctx_destroy(hs_ctx* ctx) {
   delete ctx->prof;
   for (hipEvent_t e : ctx->events) (void)hipEventDestroy(e);
   if (ctx->side) (void)hipStreamDestroy(ctx->side);
+  if (ctx->upd) (void)hipStreamDestroy(ctx->upd);
   delete ctx;
   return HS_OK;
 }

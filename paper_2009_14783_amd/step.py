@@ -96,13 +96,16 @@ class Worker:
         hs.hs_encoder_bwd(self.ctx, w, self._acts, d["ids"], d["lens"], B, L, self._dhidden, g, accumulate, self._ws,
                           self._ws_bytes)
 
-    def accumulate_micro_batches(self, batches: list, fused: bool = True) -> int:
+    def accumulate_micro_batches(self, batches: list, fused: bool = True, arm_last=None) -> int:
         """Runs every micro-batch and leaves the SUM of their gradients in G.  Entries that are
         None or carry dummy=True are workers/passes without data: they go through
-        hs_grad_accum_normalize(ignore=1) and change nothing.  Returns the sample count."""
+        hs_grad_accum_normalize(ignore=1) and change nothing.  Returns the sample count.
+        arm_last: a callable invoked right before the last real micro-batch of a fused run (used to arm
+        the optimizer update that its backward pass then carries out)."""
         n_total, first = 0, True
         assert len(batches) <= self.loss_buf.numel()
         self.loss_buf.zero_()
+        real = [i for i, d in enumerate(batches) if d is not None and not d.get("dummy", False)]
         for i, d in enumerate(batches):
             if d is None or d.get("dummy", False):
                 hs.hs_grad_accum_normalize(self.G, None, self.P, 1, 0.0)
@@ -111,6 +114,8 @@ class Worker:
                 if first and d["M"] == 0:
                     self.G.zero_()
                     first = False
+                if arm_last is not None and i == real[-1]:
+                    arm_last()
                 self.forward_backward(d, self.G, 0 if first else 1, i)
             else:
                 if self.g is None:
@@ -127,15 +132,27 @@ class Worker:
             self.G.zero_()
         return n_total
 
-    def train_step(self, batches: list, adam: dict, denom=None, fused: bool = True):
+    def train_step(self, batches: list, adam: dict, denom=None, fused: bool = True, update_in_backward: bool = True):
         """The whole hot path for one optimizer step.  Returns the sample count D; the loss sums
-        stay on the device in loss_buf (read with reported_loss after synchronising)."""
+        stay on the device in loss_buf (read with reported_loss after synchronising).
+        update_in_backward (fused accumulation only): normalisation and Adam are armed for the last
+        micro-batch's backward pass, which applies them per parameter group as soon as that group's
+        gradient is final (same arithmetic, same bits as the two separate calls)."""
+        real = [d for d in batches if d is not None and not d.get("dummy", False)]
+        D = sum(d["n_seq"] for d in real) if denom is None else denom
+        wd = adam.get("weight_decay", 0.0)
+        if fused and update_in_backward and real and D > 0:
+            arm = lambda: hs.hs_arm_update(self.ctx, self.w, self.m, self.v, self.G, self.w_lowp, float(D), adam["lr"], adam["beta1"],
+                                           adam["beta2"], adam["eps"], wd, self.t + 1)
+            self.accumulate_micro_batches(batches, True, arm_last=arm)
+            self.t += 1
+            return D
         n_total = self.accumulate_micro_batches(batches, fused)
         D = n_total if denom is None else denom
         hs.hs_grad_accum_normalize(self.G, None, self.P, 0, float(D))
         self.t += 1
         hs.hs_adam_step(self.w, self.m, self.v, self.G, self.w_lowp, self.P, adam["lr"], adam["beta1"], adam["beta2"],
-                        adam["eps"], adam.get("weight_decay", 0.0), self.t)
+                        adam["eps"], wd, self.t)
         return D
 
     def reported_loss(self, D) -> float:

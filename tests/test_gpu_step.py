@@ -282,3 +282,31 @@ def test_workload4_bert_large_shape(W):
     assert abs(loss1 / mbs[0]["mlm_pos"].size - math.log(30522)) < 0.3
     assert abs(loss4 - 4 * loss1) / abs(4 * loss1) < 1e-5
     compare_flat(full_layout, G4, 4.0 * g1, 1e-5, "4 accumulated passes vs 4 x one pass")
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("compute", ["fp32", "bf16"])
+def test_update_inside_backward_gives_the_bits_of_the_separate_calls(W, compute):
+    """Normalise + Adam armed for the last micro-batch's backward pass (per parameter group, on a third
+    stream) against hs_grad_accum_normalize + hs_adam_step after it: identical state, two updates in a row,
+    unequal micro-batches and workers without data in between."""
+    from paper_2009_14783_amd import binding as hs
+    Worker = W
+    model = dict(n_layers=3, hidden=128, n_heads=2, ffn=512, vocab=1000, max_pos=64, ln_eps=1e-12)
+    cfg = hs.make_cfg(**model)
+    theta = synth.init_params(hs.hs_param_layout(cfg), 31)
+    rng = synth.rng_for(77)
+    mbs = [synth.make_micro_batch(rng, lens, 64, model["vocab"], "uniform") for lens in ([64, 30, 7], [64] * 5, [12])]
+    adam = dict(lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.01)
+    states = []
+    for in_backward in (False, True):
+        wk = Worker(model, compute, theta)
+        dev = [None, wk.upload(mbs[0]), wk.upload(mbs[1]), dict(dummy=True), wk.upload(mbs[2]), None]
+        for _ in range(2):
+            D = wk.train_step(dev, adam, update_in_backward=in_backward)
+        torch.cuda.synchronize()
+        assert D == 9 and wk.t == 2
+        states.append({k: getattr(wk, k).clone() for k in ("w", "m", "v", "G")} | ({"w_lowp": wk.w_lowp.clone()} if compute == "bf16" else {}))
+        wk.close()
+    for k in states[0]:
+        assert torch.equal(states[0][k], states[1][k]), k
