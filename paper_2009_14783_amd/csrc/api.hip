@@ -170,36 +170,69 @@ hs_status hs_encoder_fwd(hs_ctx* ctx, const void* w, const int32_t* ids, const i
   hipStream_t s = (hipStream_t)stream;
   Acts a = carve_acts(c, B, L, acts);
 
-  HS_TRY(launch_embed_ln_fwd(ctx, dt, W(ctx, w, o.emb_word), W(ctx, w, o.emb_pos), W(ctx, w, o.emb_ln_g), W(ctx, w, o.emb_ln_b), ids,
-                             a.e_pre, a.x0, a.emb_stats, B, L, H, c.vocab, c.ln_eps, s, &ctx->drop));
   const DropCfg* drop = ctx->drop.thr ? &ctx->drop : nullptr;
+  const size_t es = esize(dt);
+  // Sequences are independent in the forward pass.  A large batch is run as two halves on two streams (the
+  // caller's and the context's second one): one half's launch ramp-ups, epilogues and tails fill with the
+  // other half's work.  Every kernel sees a row range of the same buffers, so the results are those of one
+  // pass.  Not with dropout (its element indices count rows of the whole batch) nor with per-launch timing.
+  const bool split = ctx->prof == nullptr && !drop && B >= 2 && T >= 4096;
+  const int nparts = split ? 2 : 1;
+  if (split) HS_TRY(ensure_side_stream(ctx, 2));
+  if (split) {
+    HS_HIP_CHECK(ctx, hipEventRecord(ctx->events[0], s));
+    HS_HIP_CHECK(ctx, hipStreamWaitEvent(ctx->side, ctx->events[0], 0));
+  }
+  struct Part { int b0, nb; hipStream_t st; };
+  Part part[2] = {{0, split ? B / 2 : B, s}, {B / 2, B - B / 2, split ? ctx->side : s}};
+  auto rows = [&](const void* p, const Part& pt, size_t width) { return (const void*)((const char*)p + (size_t)pt.b0 * L * width * es); };
+  auto rows_w = [&](void* p, const Part& pt, size_t width) { return (void*)((char*)p + (size_t)pt.b0 * L * width * es); };
+
+  for (int k = 0; k < nparts; ++k) {
+    const Part& pt = part[k];
+    HS_TRY(launch_embed_ln_fwd(ctx, dt, W(ctx, w, o.emb_word), W(ctx, w, o.emb_pos), W(ctx, w, o.emb_ln_g), W(ctx, w, o.emb_ln_b),
+                               ids + (size_t)pt.b0 * L, rows_w(a.e_pre, pt, H), rows_w(a.x0, pt, H), a.emb_stats + (size_t)pt.b0 * L, pt.nb, L, H,
+                               c.vocab, c.ln_eps, pt.st, &ctx->drop, T));
+  }
   const void* x = a.x0;
   for (int i = 0; i < c.n_layers; ++i) {
     const LayerOff& lo = o.layer[i];
     LayerActs& la = a.layer[i];
     void* x2 = la.x2 ? la.x2 : hidden_out;
-    // q | k | v = x Wqkv^T + b
-    GemmArgs g = gemm_args(dt, 1, 1, T, 3 * H, H, x, H, W(ctx, w, lo.qkv_w), H, la.qkv, 3 * H);
-    g.bias = W(ctx, w, lo.qkv_b);
-    HS_TRY(launch_gemm(ctx, g, s));
-    HS_TRY(launch_attention_fwd(ctx, dt, la.qkv, lens, B, L, c.n_heads, la.ctx, la.lse, s, drop, site_attention_prob(i)));
-    // y1 = x + ctx Wo^T + bo ; x1 = LN(y1)
-    g = gemm_args(dt, 1, 1, T, H, H, la.ctx, H, W(ctx, w, lo.o_w), H, la.y1, H);
-    g.bias = W(ctx, w, lo.o_b); g.epi = 1; g.aux = x; g.ldaux = H;
-    g.drop = drop; g.drop_site = site_attention_out(i);
-    HS_TRY(launch_gemm(ctx, g, s));
-    HS_TRY(launch_layernorm_fwd(ctx, dt, la.y1, W(ctx, w, lo.ln1_g), W(ctx, w, lo.ln1_b), la.x1, la.st1, T, H, c.ln_eps, s));
-    // hpre = x1 W1^T + b1 ; h = GELU(hpre)
-    g = gemm_args(dt, 1, 1, T, F, H, la.x1, H, W(ctx, w, lo.ffn1_w), H, la.hpre, F);
-    g.bias = W(ctx, w, lo.ffn1_b); g.epi = 2; g.C2 = la.h;
-    HS_TRY(launch_gemm(ctx, g, s));
-    // y2 = x1 + h W2^T + b2 ; x2 = LN(y2)
-    g = gemm_args(dt, 1, 1, T, H, F, la.h, F, W(ctx, w, lo.ffn2_w), F, la.y2, H);
-    g.bias = W(ctx, w, lo.ffn2_b); g.epi = 1; g.aux = la.x1; g.ldaux = H;
-    g.drop = drop; g.drop_site = site_ffn_out(i);
-    HS_TRY(launch_gemm(ctx, g, s));
-    HS_TRY(launch_layernorm_fwd(ctx, dt, la.y2, W(ctx, w, lo.ln2_g), W(ctx, w, lo.ln2_b), x2, la.st2, T, H, c.ln_eps, s));
+    for (int k = 0; k < nparts; ++k) {
+      const Part& pt = part[k];
+      const int Tp = pt.nb * L;
+      hipStream_t st = pt.st;
+      // q | k | v = x Wqkv^T + b
+      GemmArgs g = gemm_args(dt, 1, 1, Tp, 3 * H, H, rows(x, pt, H), H, W(ctx, w, lo.qkv_w), H, rows_w(la.qkv, pt, 3 * H), 3 * H);
+      g.bias = W(ctx, w, lo.qkv_b);
+      HS_TRY(launch_gemm(ctx, g, st));
+      HS_TRY(launch_attention_fwd(ctx, dt, rows(la.qkv, pt, 3 * H), lens + pt.b0, pt.nb, L, c.n_heads, rows_w(la.ctx, pt, H),
+                                  la.lse + (size_t)pt.b0 * c.n_heads * L, st, drop, site_attention_prob(i)));
+      // y1 = x + ctx Wo^T + bo ; x1 = LN(y1)
+      g = gemm_args(dt, 1, 1, Tp, H, H, rows(la.ctx, pt, H), H, W(ctx, w, lo.o_w), H, rows_w(la.y1, pt, H), H);
+      g.bias = W(ctx, w, lo.o_b); g.epi = 1; g.aux = rows(x, pt, H); g.ldaux = H;
+      g.drop = drop; g.drop_site = site_attention_out(i);
+      HS_TRY(launch_gemm(ctx, g, st));
+      HS_TRY(launch_layernorm_fwd(ctx, dt, rows(la.y1, pt, H), W(ctx, w, lo.ln1_g), W(ctx, w, lo.ln1_b), rows_w(la.x1, pt, H),
+                                  la.st1 + (size_t)pt.b0 * L, Tp, H, c.ln_eps, st, T));
+      // hpre = x1 W1^T + b1 ; h = GELU(hpre)
+      g = gemm_args(dt, 1, 1, Tp, F, H, rows(la.x1, pt, H), H, W(ctx, w, lo.ffn1_w), H, rows_w(la.hpre, pt, F), F);
+      g.bias = W(ctx, w, lo.ffn1_b); g.epi = 2; g.C2 = rows_w(la.h, pt, F);
+      HS_TRY(launch_gemm(ctx, g, st));
+      // y2 = x1 + h W2^T + b2 ; x2 = LN(y2)
+      g = gemm_args(dt, 1, 1, Tp, H, F, rows(la.h, pt, F), F, W(ctx, w, lo.ffn2_w), F, rows_w(la.y2, pt, H), H);
+      g.bias = W(ctx, w, lo.ffn2_b); g.epi = 1; g.aux = rows(la.x1, pt, H); g.ldaux = H;
+      g.drop = drop; g.drop_site = site_ffn_out(i);
+      HS_TRY(launch_gemm(ctx, g, st));
+      HS_TRY(launch_layernorm_fwd(ctx, dt, rows(la.y2, pt, H), W(ctx, w, lo.ln2_g), W(ctx, w, lo.ln2_b), rows_w(x2, pt, H),
+                                  la.st2 + (size_t)pt.b0 * L, Tp, H, c.ln_eps, st, T));
+    }
     x = x2;
+  }
+  if (split) {     // the second half is ordered before whatever the caller enqueues next
+    HS_HIP_CHECK(ctx, hipEventRecord(ctx->events[1], ctx->side));
+    HS_HIP_CHECK(ctx, hipStreamWaitEvent(s, ctx->events[1], 0));
   }
   return HS_OK;
 }

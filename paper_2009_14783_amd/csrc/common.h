@@ -182,8 +182,9 @@ struct GemmArgs {
 };
 hs_status launch_gemm(hs_ctx* ctx, const GemmArgs& g, hipStream_t s);
 
+// stats: R means, then (stat_ld floats after the first mean; default R) R reciprocal standard deviations
 hs_status launch_layernorm_fwd(hs_ctx* ctx, int dtype, const void* x, const void* gain, const void* bias, void* y,
-                               float* stats, int R, int H, float eps, hipStream_t s);
+                               float* stats, int R, int H, float eps, hipStream_t s, int stat_ld = 0);
 size_t layernorm_bwd_scratch(int R, int H);
 // drop_mode 0: no dropout.  1: dy is the gradient of this LayerNorm's dropped output (site) and is masked as
 // it is read.  2: dx also feeds a dropped branch (site): dxm gets its masked copy and d_colsum sums that copy.
@@ -198,7 +199,7 @@ hs_status launch_layernorm_bwd_cols(hs_ctx* ctx, const void* partials, float* d_
                                     hipStream_t s);
 hs_status launch_embed_ln_fwd(hs_ctx* ctx, int dtype, const void* word, const void* pos, const void* gain, const void* bias,
                               const int32_t* ids, void* e_pre, void* x0, float* stats, int B, int L, int H, int V, float eps,
-                              hipStream_t s, const DropCfg* drop = nullptr);
+                              hipStream_t s, const DropCfg* drop = nullptr, int stat_ld = 0);
 size_t embed_bwd_scratch(int T, int H);
 hs_status launch_embed_bwd(hs_ctx* ctx, int dtype, const void* de, const int32_t* ids, int B, int L, int H, int V, int max_pos,
                            float* g_word, float* g_pos, float beta_pos, void* scratch, hipStream_t s);

@@ -68,7 +68,7 @@ __device__ __forceinline__ void ln_row(float4 (&v)[MAXCH], int nch, int H, int l
 
 template <class T>
 __global__ __launch_bounds__(256) void ln_fwd_kernel(const T* __restrict__ x, const T* __restrict__ gain, const T* __restrict__ bias,
-                                                     T* __restrict__ y, float* __restrict__ stats, int R, int H, float eps) {
+                                                     T* __restrict__ y, float* __restrict__ stats, int R, int H, float eps, int stat_ld) {
   const int lane = threadIdx.x & 63;
   const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= R) return;
@@ -76,14 +76,15 @@ __global__ __launch_bounds__(256) void ln_fwd_kernel(const T* __restrict__ x, co
   float4 v[MAXCH];
 #pragma unroll
   for (int c = 0; c < MAXCH; ++c) if (c * 64 + lane < nch) v[c] = Vec4<T>::ld(x + (int64_t)row * H + 4 * (c * 64 + lane));
-  ln_row<T>(v, nch, H, lane, gain, bias, eps, y + (int64_t)row * H, stats + row, stats + R + row);
+  ln_row<T>(v, nch, H, lane, gain, bias, eps, y + (int64_t)row * H, stats + row, stats + stat_ld + row);
 }
 
 template <class T>
 __global__ __launch_bounds__(256) void embed_ln_fwd_kernel(const T* __restrict__ word, const T* __restrict__ pos,
                                                            const T* __restrict__ gain, const T* __restrict__ bias,
                                                            const int32_t* __restrict__ ids, T* __restrict__ e_pre, T* __restrict__ x0,
-                                                           float* __restrict__ stats, int R, int L, int H, int V, float eps, DropCfg drop) {
+                                                           float* __restrict__ stats, int R, int L, int H, int V, float eps, DropCfg drop,
+                                                           int stat_ld) {
   const int lane = threadIdx.x & 63;
   const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= R) return;
@@ -101,7 +102,7 @@ __global__ __launch_bounds__(256) void embed_ln_fwd_kernel(const T* __restrict__
     Vec4<T>::st(e_pre + (int64_t)row * H + col, e);
     v[c] = e;
   }
-  ln_row<T>(v, nch, H, lane, gain, bias, eps, x0 + (int64_t)row * H, stats + row, stats + R + row, drop.thr ? &drop : nullptr,
+  ln_row<T>(v, nch, H, lane, gain, bias, eps, x0 + (int64_t)row * H, stats + row, stats + stat_ld + row, drop.thr ? &drop : nullptr,
             site_embedding(), row);
 }
 
@@ -594,12 +595,13 @@ __global__ __launch_bounds__(256) void word_grad_join_kernel(const int32_t* __re
 static inline Profiler* prof_of(hs_ctx* ctx) { return ctx ? ctx->prof : nullptr; }
 
 hs_status launch_layernorm_fwd(hs_ctx* ctx, int dtype, const void* x, const void* gain, const void* bias, void* y, float* stats,
-                               int R, int H, float eps, hipStream_t s) {
+                               int R, int H, float eps, hipStream_t s, int stat_ld) {
   if (R <= 0) return HS_OK;
+  if (stat_ld <= 0) stat_ld = R;      // the reciprocal standard deviations start stat_ld floats after the means
   KScope scope(prof_of(ctx), KC_LN_FWD, 8.0 * R * H, 2.0 * R * H * esize(dtype), s);
   dim3 grid((R + 3) / 4);
-  if (dtype == HS_BF16) hipLaunchKernelGGL(ln_fwd_kernel<bf16>, grid, dim3(256), 0, s, (const bf16*)x, (const bf16*)gain, (const bf16*)bias, (bf16*)y, stats, R, H, eps);
-  else hipLaunchKernelGGL(ln_fwd_kernel<float>, grid, dim3(256), 0, s, (const float*)x, (const float*)gain, (const float*)bias, (float*)y, stats, R, H, eps);
+  if (dtype == HS_BF16) hipLaunchKernelGGL(ln_fwd_kernel<bf16>, grid, dim3(256), 0, s, (const bf16*)x, (const bf16*)gain, (const bf16*)bias, (bf16*)y, stats, R, H, eps, stat_ld);
+  else hipLaunchKernelGGL(ln_fwd_kernel<float>, grid, dim3(256), 0, s, (const float*)x, (const float*)gain, (const float*)bias, (float*)y, stats, R, H, eps, stat_ld);
   LAUNCH_CHECK(ctx, "layernorm_fwd");
   return HS_OK;
 }
@@ -645,14 +647,15 @@ hs_status launch_layernorm_bwd(hs_ctx* ctx, int dtype, const void* dy, const voi
 
 hs_status launch_embed_ln_fwd(hs_ctx* ctx, int dtype, const void* word, const void* pos, const void* gain, const void* bias,
                               const int32_t* ids, void* e_pre, void* x0, float* stats, int B, int L, int H, int V, float eps, hipStream_t s,
-                              const DropCfg* drop) {
+                              const DropCfg* drop, int stat_ld) {
   const DropCfg dcfg = (drop && drop->thr) ? *drop : DropCfg{0u, 1.0f, 0u, 0u, 0u};
+  if (stat_ld <= 0) stat_ld = B * L;
   const int R = B * L;
   if (R <= 0) return HS_OK;
   KScope scope(prof_of(ctx), KC_EMBED, 10.0 * R * H, 4.0 * R * H * esize(dtype), s);
   dim3 grid((R + 3) / 4);
-  if (dtype == HS_BF16) hipLaunchKernelGGL(embed_ln_fwd_kernel<bf16>, grid, dim3(256), 0, s, (const bf16*)word, (const bf16*)pos, (const bf16*)gain, (const bf16*)bias, ids, (bf16*)e_pre, (bf16*)x0, stats, R, L, H, V, eps, dcfg);
-  else hipLaunchKernelGGL(embed_ln_fwd_kernel<float>, grid, dim3(256), 0, s, (const float*)word, (const float*)pos, (const float*)gain, (const float*)bias, ids, (float*)e_pre, (float*)x0, stats, R, L, H, V, eps, dcfg);
+  if (dtype == HS_BF16) hipLaunchKernelGGL(embed_ln_fwd_kernel<bf16>, grid, dim3(256), 0, s, (const bf16*)word, (const bf16*)pos, (const bf16*)gain, (const bf16*)bias, ids, (bf16*)e_pre, (bf16*)x0, stats, R, L, H, V, eps, dcfg, stat_ld);
+  else hipLaunchKernelGGL(embed_ln_fwd_kernel<float>, grid, dim3(256), 0, s, (const float*)word, (const float*)pos, (const float*)gain, (const float*)bias, ids, (float*)e_pre, (float*)x0, stats, R, L, H, V, eps, dcfg, stat_ld);
   LAUNCH_CHECK(ctx, "embed_ln_fwd");
   return HS_OK;
 }
