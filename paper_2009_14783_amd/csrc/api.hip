@@ -46,7 +46,7 @@ size_t gemm_scratch_bytes(const hs_model_cfg& c) {
 }
 
 struct HeadWs {
-  void *grow, *tpre, *tact, *t, *dlogits, *dt, *dtact, *dtpre, *dg, *ln_part, *cs_part, *gemm_ws;
+  void *grow, *tpre, *tact, *t, *dlogits, *dt, *dtact, *dtpre, *dg, *ln_part, *cs_part, *cs_part_side, *gemm_ws;
   float *stats, *logits, *row_loss;
   size_t total, gemm_ws_bytes;
 };
@@ -62,6 +62,7 @@ HeadWs carve_head(const hs_model_cfg& c, int M, void* base) {
   w.dt = cv.take(m * H * es); w.dtact = cv.take(m * H * es); w.dtpre = cv.take(m * H * es); w.dg = cv.take(m * H * es);
   w.ln_part = cv.take(layernorm_bwd_scratch(M, (int)H));
   w.cs_part = cv.take(colsum_scratch(M, (int)Vp));
+  w.cs_part_side = cv.take(colsum_scratch(M, (int)Vp));
   w.gemm_ws_bytes = gemm_scratch_bytes(c);
   w.gemm_ws = cv.take(w.gemm_ws_bytes);
   w.total = cv.off;
@@ -273,11 +274,22 @@ hs_status hs_mlm_loss(hs_ctx* ctx, const void* w, const void* hidden, const int3
   ga.c_f32 = 1; ga.beta = 0.f; ga.bias = W(ctx, w, o.head_dec_b);
   HS_TRY(run_gemm(ga));
   HS_TRY(launch_ce_loss(ctx, dt, h.logits, Vp, mlm_label, M, V, h.dlogits, h.row_loss, loss_sum, s));
-  // decoder bias and the decoder's share of the tied word embedding
-  HS_TRY(launch_colsum(ctx, dt, h.dlogits, Vp, M, V, g + o.head_dec_b, beta, h.cs_part, s));
+  // Decoder bias and the decoder's share of the tied word embedding only consume d logits: beside the chain
+  // that goes on to d hidden, on the context's second stream (own partial-sum buffer, no split-K scratch),
+  // joined before this call returns work to the caller's stream.
+  const bool overlap = ctx->prof == nullptr;
+  hipStream_t sd = s;
+  if (overlap) {
+    HS_TRY(ensure_side_stream(ctx, 2));
+    sd = ctx->side;
+    HS_HIP_CHECK(ctx, hipEventRecord(ctx->events[0], s));
+    HS_HIP_CHECK(ctx, hipStreamWaitEvent(sd, ctx->events[0], 0));
+  }
+  HS_TRY(launch_colsum(ctx, dt, h.dlogits, Vp, M, V, g + o.head_dec_b, beta, h.cs_part_side, sd));
   ga = gemm_args(dt, 0, 0, V, H, M, h.dlogits, Vp, h.t, H, g + o.emb_word, H);
   ga.c_f32 = 1; ga.beta = beta;
-  HS_TRY(run_gemm(ga));
+  if (overlap) HS_TRY(launch_gemm(ctx, ga, sd)); else HS_TRY(run_gemm(ga));
+  if (overlap) HS_HIP_CHECK(ctx, hipEventRecord(ctx->events[1], sd));
   // dt = dlogits E
   ga = gemm_args(dt, 1, 0, M, H, V, h.dlogits, Vp, W(ctx, w, o.emb_word), H, h.dt, H);
   HS_TRY(run_gemm(ga));
@@ -291,6 +303,7 @@ hs_status hs_mlm_loss(hs_ctx* ctx, const void* w, const void* hidden, const int3
   ga = gemm_args(dt, 1, 0, M, H, H, h.dtpre, H, W(ctx, w, o.head_t_w), H, h.dg, H);
   HS_TRY(run_gemm(ga));
   HS_TRY(launch_scatter_rows(ctx, dt, h.dg, mlm_pos, M, H, d_hidden, s));
+  if (overlap) HS_HIP_CHECK(ctx, hipStreamWaitEvent(s, ctx->events[1], 0));
   return HS_OK;
 }
 
