@@ -126,6 +126,46 @@ hs_status hs_set_dropout(hs_ctx* ctx, double p, uint64_t seed, uint32_t stream);
  * state of ctx to mask_out [n] (dev). */
 hs_status hs_dropout_keep_mask(hs_ctx* ctx, uint32_t site, size_t n, uint8_t* mask_out, void* stream);
 
+/* ---- host data path ---------------------------------------------------------------------------
+ * Section "Dataset and Dataloader": the dataset is split into shards, the lengths of the shards are
+ * accumulated and the index of a training instance is mapped to an offset inside its shard; the
+ * shuffle is reproducible.  Section "Forward Pass": batches under the max-tokens criterion.
+ * Section "Prefetch and Cache": the next batches are fetched while the current one trains, and a
+ * least-recently-used cache keeps instances in memory.  Everything here is host code.
+ * Shard file (little-endian): the 8 bytes "HSSHARD1", int64 n_seq, int64 n_tokens, int32
+ * lengths[n_seq], int32 tokens[n_tokens].  Instances are numbered through the shards in the order
+ * the shards are given. */
+typedef struct hs_dataset hs_dataset;
+/* Writes a shard (for synthetic data and tests).  lengths [n_seq], tokens [sum of lengths], host. */
+hs_status hs_shard_write(const char* path, const int32_t* lengths, int64_t n_seq, const int32_t* tokens);
+/* Opens the shards and reads their headers and lengths only (tokens are read on demand).
+ * cache_instances: capacity of the least-recently-used instance cache (0: none); prefetch_batches
+ * (1..64): how many batches the background thread may be ahead of hs_dataset_next.
+ * HS_ERR_STATE for a missing, malformed or truncated shard. */
+hs_status hs_dataset_open(const char* const* paths, int32_t n_shards, int64_t cache_instances, int32_t prefetch_batches, hs_dataset** out);
+hs_status hs_dataset_close(hs_dataset* d);
+int64_t hs_dataset_size(const hs_dataset* d);                                   /* number of instances */
+hs_status hs_dataset_lengths(const hs_dataset* d, int32_t* lengths_out /*[size]*/);
+/* The index map: shard and row of a global instance index. */
+hs_status hs_dataset_locate(const hs_dataset* d, int64_t instance, int32_t* shard_out, int64_t* row_out);
+/* Starts an epoch: forms the batches of the whole dataset with hs_make_batches(bucket_width, max_tokens,
+ * cap_mode), shuffles their order (Fisher-Yates: for i = n-1 .. 1 swap batch i with batch
+ * w mod (i + 1), w = word 0 of the Philox4x32-10 block with counter (i low, i high, epoch, 0x5AFF1E) and
+ * key (seed low, seed high)), keeps the batches rank, rank + world, ... for this worker and starts the
+ * background thread.  *n_batches_out = this worker's number of batches.  An epoch in progress is
+ * abandoned. */
+hs_status hs_dataset_begin_epoch(hs_dataset* d, uint64_t seed, int64_t epoch, int32_t bucket_width, int64_t max_tokens, int32_t cap_mode,
+                                 int32_t world, int32_t rank, int64_t* n_batches_out);
+/* Shape of the next batch (sequences, padded length); 0, 0 when the epoch is over. */
+hs_status hs_dataset_peek(hs_dataset* d, int32_t* B_out, int32_t* L_out);
+/* Copies the next batch into the caller's host buffers (pinned memory makes the following upload
+ * asynchronous): ids_out [B * L] padded with 0, lens_out [B], instance_out [B] (nullable) the global
+ * instance indices.  Blocks until the background thread has assembled the batch.  HS_ERR_STATE at
+ * the end of the epoch or after a read error.  One consumer thread per dataset. */
+hs_status hs_dataset_next(hs_dataset* d, int32_t* ids_out, int32_t* lens_out, int64_t* instance_out);
+/* Instances read from the shards and instances served by the cache, over the batches assembled so far. */
+hs_status hs_dataset_stats(hs_dataset* d, int64_t* loads_out, int64_t* hits_out);
+
 /* ---- learning-rate schedule (host) ---------------------------------------------------------
  * Section "BERT Language Model": linear-decay schedule with a maximum rate, `warmup` warm-up
  * updates and `total` updates in all.  Returns the rate of update number t (1-based):

@@ -64,6 +64,16 @@ _SIGNATURES = {
     "hs_arm_update": (_I32, [_P, _P, _P, _P, _P, _P, _D, _D, _D, _D, _D, _D, _I64]),
     "hs_set_dropout": (_I32, [_P, _D, C.c_uint64, C.c_uint32]),
     "hs_dropout_keep_mask": (_I32, [_P, C.c_uint32, _SZ, _P, _P]),
+    "hs_shard_write": (_I32, [C.c_char_p, _P, _I64, _P]),
+    "hs_dataset_open": (_I32, [C.POINTER(C.c_char_p), _I32, _I64, _I32, C.POINTER(_P)]),
+    "hs_dataset_close": (_I32, [_P]),
+    "hs_dataset_size": (_I64, [_P]),
+    "hs_dataset_lengths": (_I32, [_P, _P]),
+    "hs_dataset_locate": (_I32, [_P, _I64, C.POINTER(_I32), C.POINTER(_I64)]),
+    "hs_dataset_begin_epoch": (_I32, [_P, C.c_uint64, _I64, _I32, _I64, _I32, _I32, _I32, C.POINTER(_I64)]),
+    "hs_dataset_peek": (_I32, [_P, C.POINTER(_I32), C.POINTER(_I32)]),
+    "hs_dataset_next": (_I32, [_P, _P, _P, _P]),
+    "hs_dataset_stats": (_I32, [_P, C.POINTER(_I64), C.POINTER(_I64)]),
     "hs_lr_linear": (_D, [_I64, _D, _I64, _I64]),
     "hs_checkpoint_write": (_I32, [C.c_char_p, C.POINTER(hs_ckpt_header), _P, _P, _P]),
     "hs_checkpoint_read_header": (_I32, [C.c_char_p, C.POINTER(hs_ckpt_header)]),
@@ -129,6 +139,67 @@ def make_cfg(n_layers, hidden, n_heads, ffn, vocab, max_pos, ln_eps=1e-12, compu
 
 
 # ---- host-only calls ---------------------------------------------------------------------
+def hs_shard_write(path: str, sequences: list):
+    lengths = np.array([len(q) for q in sequences], dtype=np.int32)
+    tokens = np.concatenate([np.asarray(q, dtype=np.int32) for q in sequences]) if len(sequences) else np.zeros(0, np.int32)
+    _check(lib().hs_shard_write(path.encode(), _ptr(lengths), len(sequences), _ptr(tokens) if tokens.size else None))
+
+
+class Dataset:
+    """Thin wrapper of the hs_dataset_* calls (argument marshalling only)."""
+
+    def __init__(self, paths, cache_instances=0, prefetch_batches=2):
+        arr = (C.c_char_p * len(paths))(*[p.encode() for p in paths])
+        self.h = _P()
+        _check(lib().hs_dataset_open(arr, len(paths), cache_instances, prefetch_batches, C.byref(self.h)))
+
+    def close(self):
+        if self.h:
+            _check(lib().hs_dataset_close(self.h))
+            self.h = None
+
+    def __len__(self):
+        return lib().hs_dataset_size(self.h)
+
+    def lengths(self) -> np.ndarray:
+        out = np.empty(len(self), dtype=np.int32)
+        _check(lib().hs_dataset_lengths(self.h, _ptr(out)))
+        return out
+
+    def locate(self, instance: int):
+        s, r = _I32(), _I64()
+        _check(lib().hs_dataset_locate(self.h, instance, C.byref(s), C.byref(r)))
+        return s.value, r.value
+
+    def begin_epoch(self, seed, epoch, bucket_width, max_tokens, cap_mode=0, world=1, rank=0) -> int:
+        n = _I64()
+        _check(lib().hs_dataset_begin_epoch(self.h, seed & 0xFFFFFFFFFFFFFFFF, epoch, bucket_width, max_tokens, cap_mode, world, rank,
+                                            C.byref(n)))
+        return n.value
+
+    def peek(self):
+        b, l = _I32(), _I32()
+        _check(lib().hs_dataset_peek(self.h, C.byref(b), C.byref(l)))
+        return b.value, l.value
+
+    def next(self, ids_out=None, lens_out=None):
+        """Returns (ids [B, L], lens [B], instance indices [B]); ids_out / lens_out may be preallocated
+        (for example pinned) int32 arrays or tensors of sufficient size."""
+        B, L = self.peek()
+        if B == 0:
+            raise StopIteration
+        ids = np.empty((B, L), dtype=np.int32) if ids_out is None else ids_out
+        lens = np.empty(B, dtype=np.int32) if lens_out is None else lens_out
+        inst = np.empty(B, dtype=np.int64)
+        _check(lib().hs_dataset_next(self.h, _ptr(ids), _ptr(lens), _ptr(inst)))
+        return ids, lens, inst
+
+    def stats(self):
+        a, b = _I64(), _I64()
+        _check(lib().hs_dataset_stats(self.h, C.byref(a), C.byref(b)))
+        return a.value, b.value
+
+
 def hs_lr_linear(t, max_lr, warmup, total) -> float:
     lr = lib().hs_lr_linear(int(t), float(max_lr), int(warmup), int(total))
     if lr != lr:
