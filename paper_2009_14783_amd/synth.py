@@ -146,3 +146,20 @@ def step_micro_batches(seed: int, t: int, lens, L: int, vocab: int, dist: str, n
         for i, mb in enumerate(out):
             mb["drop"] = dict(p=dropout, seed=seed, stream=64 * t + i)
     return out
+
+
+def mask_batch(rng: np.random.Generator, ids: np.ndarray, lens) -> dict:
+    """Masked-LM targets for a padded batch whose tokens are given (for batches that come from a
+    dataset): per sequence n_targets(len) distinct real positions get MASK, their ids become labels."""
+    ids = np.array(ids, dtype=np.int32, copy=True)
+    lens = np.asarray(lens, dtype=np.int32)
+    B, L = ids.shape
+    pos, lab = [], []
+    for b in range(B):
+        n = int(lens[b])
+        for l in np.sort(rng.permutation(n)[:n_targets(n)]):
+            pos.append(b * L + int(l))
+            lab.append(int(ids[b, l]))
+            ids[b, l] = MASK_ID
+    return dict(ids=ids, lens=lens, mlm_pos=np.asarray(pos, dtype=np.int32), mlm_label=np.asarray(lab, dtype=np.int32),
+                n_seq=B, n_real_tokens=int(lens.sum()))
