@@ -163,3 +163,41 @@ def mask_batch(rng: np.random.Generator, ids: np.ndarray, lens) -> dict:
             ids[b, l] = MASK_ID
     return dict(ids=ids, lens=lens, mlm_pos=np.asarray(pos, dtype=np.int32), mlm_label=np.asarray(lab, dtype=np.int32),
                 n_seq=B, n_real_tokens=int(lens.sum()))
+
+
+# ---- translation workload (source / target pairs) ---------------------------------------------
+EOS_ID = 2
+S2S_MODELS = {
+    "s2s_tiny": dict(n_enc=2, n_dec=2, hidden=128, n_heads=2, ffn=256, vocab=600, max_pos=64, ln_eps=1e-5),
+    "transformer_base": dict(n_enc=6, n_dec=6, hidden=512, n_heads=8, ffn=2048, vocab=37000, max_pos=256, ln_eps=1e-5),
+}
+
+
+def make_pair_batch(rng: np.random.Generator, src_lens, tgt_lens, Ls: int, Lt: int, vocab: int, dist: str) -> dict:
+    """One padded batch of sentence pairs.  src [B, Ls]; a target of length n is n - 1 drawn tokens followed
+    by EOS: tgt_out [B, Lt] holds it, tgt_in [B, Lt] the same shifted right behind a leading EOS (the decoder's
+    input).  PAD beyond the lengths."""
+    src_lens = np.asarray(src_lens, dtype=np.int32)
+    tgt_lens = np.asarray(tgt_lens, dtype=np.int32)
+    B = len(src_lens)
+    assert len(tgt_lens) == B and np.all(src_lens >= 1) and np.all(src_lens <= Ls) and np.all(tgt_lens >= 1) and np.all(tgt_lens <= Lt)
+    src = np.full((B, Ls), PAD_ID, dtype=np.int32)
+    tgt_in = np.full((B, Lt), PAD_ID, dtype=np.int32)
+    tgt_out = np.full((B, Lt), PAD_ID, dtype=np.int32)
+    for b in range(B):
+        ns, nt = int(src_lens[b]), int(tgt_lens[b])
+        src[b, :ns] = draw_ids(rng, ns, vocab, dist)
+        y = np.concatenate([draw_ids(rng, nt - 1, vocab, dist), [EOS_ID]]).astype(np.int32)
+        tgt_out[b, :nt] = y
+        tgt_in[b, 0] = EOS_ID
+        tgt_in[b, 1:nt] = y[:nt - 1]
+    return dict(src=src, src_lens=src_lens, tgt_in=tgt_in, tgt_out=tgt_out, tgt_lens=tgt_lens, n_seq=B,
+                n_src_tokens=int(src_lens.sum()), n_tgt_tokens=int(tgt_lens.sum()))
+
+
+def draw_pair_lengths(rng: np.random.Generator, n: int, lo: int, hi: int):
+    """Source lengths uniform in [lo, hi]; each target length is its source length times a factor uniform
+    in [0.8, 1.25], clipped to [lo, hi] (sentence pairs of similar length, as translation corpora have)."""
+    s = rng.integers(lo, hi + 1, size=n)
+    t = np.clip(np.rint(s * rng.uniform(0.8, 1.25, size=n)), lo, hi).astype(np.int32)
+    return s.astype(np.int32), t
