@@ -285,6 +285,68 @@ hs_status hs_adam_step(float* w, float* m, float* v, const float* G, void* w_low
  * HS_FP32); used once to seed the low-precision weights before the first step. */
 hs_status hs_cast_params(const float* src, void* dst, size_t n, int32_t dst_dtype, void* stream);
 
+/* ---- translation workload: encoder-decoder step ---------------------------------------------
+ * Section "Transformer Translation Model": the base Transformer (6 + 6 layers, hidden 512, 8 heads,
+ * dropout 0.1, label-smoothed cross-entropy with epsilon 0.1, Adam 0.9 / 0.98 / 1e-9), trained with
+ * 4096 tokens per worker (table 1).  The model is the cited one written out: one embedding matrix E
+ * shared by source tokens, target tokens and the output projection; inputs sqrt(H) E[id] + PE[pos] with
+ * PE[p, 2i] = sin(p / 10000^(2i/H)), PE[p, 2i+1] = cos(p / 10000^(2i/H)); post-LN sub-layers
+ * x <- LN(x + drop(sublayer(x))); encoder layer = self-attention over the real source tokens, ReLU
+ * feed-forward; decoder layer = causal self-attention, attention over the encoder output (masked by
+ * the source lengths), ReLU feed-forward; dropout (hs_set_dropout) on the two embedding sums and on
+ * every sub-layer output; logits = decoder output times E^T.  The optimizer calls above serve this
+ * workload unchanged (the caller passes the token count as denom). */
+typedef struct {
+  int32_t n_enc, n_dec, hidden, n_heads, ffn, vocab, max_pos;
+  float ln_eps;
+  int32_t compute; /* hs_dtype */
+} hs_s2s_cfg;
+
+/* A context for the calls below (destroyed with hs_ctx_destroy; hs_set_dropout, hs_profile_* and
+ * hs_last_error apply).  hidden = 64 * n_heads, a multiple of 64 and <= 1024; ffn and vocab as in hs_ctx_create. */
+hs_status hs_s2s_ctx_create(const hs_s2s_cfg* cfg, hs_ctx** out);
+size_t hs_s2s_param_count(const hs_s2s_cfg* cfg);
+/* Same protocol as hs_param_layout.  Order: emb; enc<i>.{qkv.w, qkv.b, o.w, o.b, ln1.g, ln1.b, ffn1.w, ffn1.b,
+ * ffn2.w, ffn2.b, ln2.g, ln2.b}; dec<i>.{qkv, o, ln1, cq.w, cq.b, ckv.w, ckv.b, co.w, co.b, lnc.g, lnc.b, ffn1, ffn2, ln2}. */
+hs_status hs_s2s_param_layout(const hs_s2s_cfg* cfg, hs_param_entry* out, int32_t* n);
+size_t hs_s2s_acts_bytes(const hs_s2s_cfg* cfg, int32_t B, int32_t Ls, int32_t Lt);
+size_t hs_s2s_workspace_bytes(const hs_s2s_cfg* cfg, int32_t B, int32_t Ls, int32_t Lt);
+
+/* Forward pass of one batch of sentence pairs.  src [B, Ls], tgt_in [B, Lt] dev int32 in [0, vocab) (tgt_in is the
+ * target shifted right); src_lens, tgt_lens [B] dev int32 with 1 <= len <= Ls (Lt).  Ls, Lt multiples of 8, <= max_pos.
+ * acts: dev, hs_s2s_acts_bytes(); dec_out [B, Lt, H] dev, activation type (rows of padding: finite don't-care).
+ * Sub-layer dropout needs H * Ls and H * Lt to be multiples of 4 (always true). */
+hs_status hs_s2s_fwd(hs_ctx* ctx, const void* w, const int32_t* src, const int32_t* src_lens, const int32_t* tgt_in,
+                     const int32_t* tgt_lens, int32_t B, int32_t Ls, int32_t Lt, void* acts, void* dec_out, void* stream);
+
+/* Output projection, label-smoothed loss SUM over the real target positions and its backward.
+ * Per real position with label y: nll = logsumexp(z) - z_y; loss = (1 - eps) nll + eps (logsumexp(z) - mean_v z_v), i.e.
+ * the cross-entropy to the target (1 - eps) onehot(y) + eps / V.  *loss_sum and *nll_sum (dev scalars, nll_sum may be
+ * NULL) are overwritten; nothing is divided (the weight, normally the number of real target tokens, travels beside the sum).
+ * tgt_out [B, Lt] dev int32 labels.  d_dec_out [B, Lt, H] dev is fully written (zero rows at padding); the projection's
+ * share of the emb gradient goes to g (flat fp32 [P] dev): overwritten when accumulate == 0, added when 1. */
+hs_status hs_s2s_loss(hs_ctx* ctx, const void* w, const void* dec_out, const int32_t* tgt_out, const int32_t* tgt_lens, int32_t B,
+                      int32_t Lt, double eps, float* loss_sum, float* nll_sum, void* d_dec_out, float* g, int32_t accumulate,
+                      void* workspace, size_t workspace_bytes, void* stream);
+
+/* Backward through decoder and encoder down to the embedding.  Gradients of enc*. and dec*. go to g (overwritten when
+ * accumulate == 0, added when 1); emb is ALWAYS added to (call hs_s2s_loss first). */
+hs_status hs_s2s_bwd(hs_ctx* ctx, const void* w, const void* acts, const int32_t* src, const int32_t* src_lens, const int32_t* tgt_in,
+                     const int32_t* tgt_lens, int32_t B, int32_t Ls, int32_t Lt, const void* d_dec_out, float* g, int32_t accumulate,
+                     void* workspace, size_t workspace_bytes, void* stream);
+
+/* Building block, exported for tests: attention with separate query and key/value sequences (head dimension 64).
+ * q rows b*Lq + i (stride ldq elements), k and v rows b*Lk + j (stride ldkv); key j takes part iff j < klens[b] and, when
+ * causal != 0 (needs Lq == Lk), j <= i.  ctx_out [B*Lq, A*64]; lse [B, A, Lq] fp32.  Backward: queries at or beyond
+ * qlens[b] get zero gradients; dq (stride lddq), dk, dv (stride lddkv) are written for every row; dvec [B, A, Lq] scratch. */
+hs_status hs_op_attention_general_fwd(int32_t dtype, const void* q, int64_t ldq, const void* k, const void* v, int64_t ldkv,
+                                      const int32_t* qlens, const int32_t* klens, int32_t B, int32_t Lq, int32_t Lk, int32_t A,
+                                      int32_t causal, void* ctx_out, float* lse, void* stream);
+hs_status hs_op_attention_general_bwd(int32_t dtype, const void* q, int64_t ldq, const void* k, const void* v, int64_t ldkv,
+                                      const int32_t* qlens, const int32_t* klens, int32_t B, int32_t Lq, int32_t Lk, int32_t A,
+                                      int32_t causal, const void* ctx_in, const float* lse, const void* d_ctx, void* dq, int64_t lddq,
+                                      void* dk, void* dv, int64_t lddkv, float* dvec, void* stream);
+
 /* ---- per-kernel timing (optional) -------------------------------------------------------
  * When enabled, every kernel launch of the ctx-taking calls is bracketed by a pair of HIP
  * events on the launch stream.  hs_profile_read synchronises those events and returns, per

@@ -21,6 +21,11 @@ class hs_model_cfg(C.Structure):
                 ("vocab", C.c_int32), ("max_pos", C.c_int32), ("ln_eps", C.c_float), ("compute", C.c_int32)]
 
 
+class hs_s2s_cfg(C.Structure):
+    _fields_ = [("n_enc", C.c_int32), ("n_dec", C.c_int32), ("hidden", C.c_int32), ("n_heads", C.c_int32), ("ffn", C.c_int32),
+                ("vocab", C.c_int32), ("max_pos", C.c_int32), ("ln_eps", C.c_float), ("compute", C.c_int32)]
+
+
 class hs_param_entry(C.Structure):
     _fields_ = [("name", C.c_char * 48), ("offset", C.c_int64), ("rows", C.c_int32), ("cols", C.c_int32)]
 
@@ -86,6 +91,17 @@ _SIGNATURES = {
     "hs_op_layernorm_bwd": (_I32, [_I32, _P, _P, _P, _P, _P, _P, _P, _P, _F, _I32, _I32, _P, _P]),
     "hs_op_attention_fwd": (_I32, [_I32, _P, _P, _I32, _I32, _I32, _P, _P, _P]),
     "hs_op_attention_bwd": (_I32, [_I32, _P, _P, _P, _P, _P, _I32, _I32, _I32, _P, _P, _P]),
+    "hs_s2s_ctx_create": (_I32, [C.POINTER(hs_s2s_cfg), C.POINTER(_P)]),
+    "hs_s2s_param_count": (_SZ, [C.POINTER(hs_s2s_cfg)]),
+    "hs_s2s_param_layout": (_I32, [C.POINTER(hs_s2s_cfg), C.POINTER(hs_param_entry), C.POINTER(_I32)]),
+    "hs_s2s_acts_bytes": (_SZ, [C.POINTER(hs_s2s_cfg), _I32, _I32, _I32]),
+    "hs_s2s_workspace_bytes": (_SZ, [C.POINTER(hs_s2s_cfg), _I32, _I32, _I32]),
+    "hs_s2s_fwd": (_I32, [_P, _P, _P, _P, _P, _P, _I32, _I32, _I32, _P, _P, _P]),
+    "hs_s2s_loss": (_I32, [_P, _P, _P, _P, _P, _I32, _I32, _D, _P, _P, _P, _P, _I32, _P, _SZ, _P]),
+    "hs_s2s_bwd": (_I32, [_P, _P, _P, _P, _P, _P, _P, _I32, _I32, _I32, _P, _P, _I32, _P, _SZ, _P]),
+    "hs_op_attention_general_fwd": (_I32, [_I32, _P, _I64, _P, _P, _I64, _P, _P, _I32, _I32, _I32, _I32, _I32, _P, _P, _P]),
+    "hs_op_attention_general_bwd": (_I32, [_I32, _P, _I64, _P, _P, _I64, _P, _P, _I32, _I32, _I32, _I32, _I32, _P, _P, _P, _P, _I64, _P,
+                                           _P, _I64, _P, _P]),
 }
 EXPORTS = tuple(_SIGNATURES)
 
@@ -360,3 +376,63 @@ def hs_op_attention_fwd(dtype, qkv, lens, B, L, A, ctx_out, lse, stream=None):
 def hs_op_attention_bwd(dtype, qkv, ctx_in, lse, d_ctx, lens, B, L, A, dqkv, dvec, stream=None):
     _check(lib().hs_op_attention_bwd(dtype, _ptr(qkv), _ptr(ctx_in), _ptr(lse), _ptr(d_ctx), _ptr(lens), B, L, A, _ptr(dqkv),
                                      _ptr(dvec), _stream(stream)))
+
+
+# ---- translation workload -----------------------------------------------------------------
+def make_s2s_cfg(n_enc, n_dec, hidden, n_heads, ffn, vocab, max_pos, ln_eps=1e-5, compute=HS_BF16) -> hs_s2s_cfg:
+    return hs_s2s_cfg(n_enc, n_dec, hidden, n_heads, ffn, vocab, max_pos, ln_eps, compute)
+
+
+def hs_s2s_ctx_create(cfg: hs_s2s_cfg):
+    h = _P()
+    _check(lib().hs_s2s_ctx_create(C.byref(cfg), C.byref(h)))
+    return h
+
+
+def hs_s2s_param_count(cfg) -> int:
+    return int(lib().hs_s2s_param_count(C.byref(cfg)))
+
+
+def hs_s2s_param_layout(cfg):
+    """List of (name, offset, rows, cols)."""
+    n = _I32(0)
+    _check(lib().hs_s2s_param_layout(C.byref(cfg), None, C.byref(n)))
+    arr = (hs_param_entry * n.value)()
+    _check(lib().hs_s2s_param_layout(C.byref(cfg), arr, C.byref(n)))
+    return [(e.name.decode(), int(e.offset), int(e.rows), int(e.cols)) for e in arr[:n.value]]
+
+
+def hs_s2s_acts_bytes(cfg, B, Ls, Lt) -> int:
+    return int(lib().hs_s2s_acts_bytes(C.byref(cfg), B, Ls, Lt))
+
+
+def hs_s2s_workspace_bytes(cfg, B, Ls, Lt) -> int:
+    return int(lib().hs_s2s_workspace_bytes(C.byref(cfg), B, Ls, Lt))
+
+
+def hs_s2s_fwd(ctx, w, src, src_lens, tgt_in, tgt_lens, B, Ls, Lt, acts, dec_out, stream=None):
+    _check(lib().hs_s2s_fwd(ctx, _ptr(w), _ptr(src), _ptr(src_lens), _ptr(tgt_in), _ptr(tgt_lens), B, Ls, Lt, _ptr(acts), _ptr(dec_out),
+                            _stream(stream)), ctx)
+
+
+def hs_s2s_loss(ctx, w, dec_out, tgt_out, tgt_lens, B, Lt, eps, loss_sum, nll_sum, d_dec_out, g, accumulate, workspace, workspace_bytes,
+                stream=None):
+    _check(lib().hs_s2s_loss(ctx, _ptr(w), _ptr(dec_out), _ptr(tgt_out), _ptr(tgt_lens), B, Lt, float(eps), _ptr(loss_sum), _ptr(nll_sum),
+                             _ptr(d_dec_out), _ptr(g), accumulate, _ptr(workspace), workspace_bytes, _stream(stream)), ctx)
+
+
+def hs_s2s_bwd(ctx, w, acts, src, src_lens, tgt_in, tgt_lens, B, Ls, Lt, d_dec_out, g, accumulate, workspace, workspace_bytes, stream=None):
+    _check(lib().hs_s2s_bwd(ctx, _ptr(w), _ptr(acts), _ptr(src), _ptr(src_lens), _ptr(tgt_in), _ptr(tgt_lens), B, Ls, Lt, _ptr(d_dec_out),
+                            _ptr(g), accumulate, _ptr(workspace), workspace_bytes, _stream(stream)), ctx)
+
+
+def hs_op_attention_general_fwd(dtype, q, ldq, k, v, ldkv, qlens, klens, B, Lq, Lk, A, causal, ctx_out, lse, stream=None):
+    _check(lib().hs_op_attention_general_fwd(dtype, _ptr(q), ldq, _ptr(k), _ptr(v), ldkv, _ptr(qlens), _ptr(klens), B, Lq, Lk, A, causal,
+                                             _ptr(ctx_out), _ptr(lse), _stream(stream)))
+
+
+def hs_op_attention_general_bwd(dtype, q, ldq, k, v, ldkv, qlens, klens, B, Lq, Lk, A, causal, ctx_in, lse, d_ctx, dq, lddq, dk, dv, lddkv,
+                                dvec, stream=None):
+    _check(lib().hs_op_attention_general_bwd(dtype, _ptr(q), ldq, _ptr(k), _ptr(v), ldkv, _ptr(qlens), _ptr(klens), B, Lq, Lk, A, causal,
+                                             _ptr(ctx_in), _ptr(lse), _ptr(d_ctx), _ptr(dq), lddq, _ptr(dk), _ptr(dv), lddkv, _ptr(dvec),
+                                             _stream(stream)))

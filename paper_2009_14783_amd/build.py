@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libhetseq_hip.so")
-SOURCES = ["context.cpp", "dataset.cpp", "gemm.hip", "attention.hip", "attention_mfma.hip", "rowops.hip", "optim.hip", "api.hip"]
+SOURCES = ["context.cpp", "dataset.cpp", "gemm.hip", "attention.hip", "attention_mfma.hip", "attention_general.hip", "rowops.hip", "seq2seq_ops.hip", "seq2seq.hip", "optim.hip", "api.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-x", "hip",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

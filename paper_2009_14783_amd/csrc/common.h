@@ -154,6 +154,9 @@ struct hs_ctx {
   // on a third stream as soon as its gradient is final
   struct Armed { bool on; float *w, *m, *v, *G; void* wl; double denom, lr, beta1, beta2, eps, wd; int64_t t; } armed;
   hipStream_t upd;
+  // translation workload (contexts made by hs_s2s_ctx_create): cfg above holds the shared sizes (n_layers = encoder layers)
+  bool is_s2s;
+  hs_s2s_cfg s2s;
 };
 
 hs_status hs_fail(hs_ctx* ctx, hs_status st, const std::string& msg);  // records msg, returns st
@@ -217,5 +220,28 @@ hs_status launch_scatter_rows(hs_ctx* ctx, int dtype, const void* src, const int
 hs_status launch_fill_zero(hs_ctx* ctx, void* p, size_t bytes, hipStream_t s);
 hs_status launch_gelu_fwd(hs_ctx* ctx, int dtype, const void* x, void* y, size_t n, hipStream_t s);
 hs_status launch_gelu_bwd(hs_ctx* ctx, int dtype, const void* dy, const void* pre, void* dx, size_t n, hipStream_t s);
+// Attention with separate query and key/value sequences (attention_general.hip).  Row b*Lq + i of q (stride ldq) is
+// query i of sequence b, row b*Lk + j of k and v (stride ldkv) key j; key j takes part iff j < klens[b] and, when
+// causal (Lq == Lk), j <= i; queries at or beyond qlens[b] get zero gradients.  out/d_out are [B*Lq, A*64], lse and
+// dvec [B, A, Lq]; dq (stride lddq), dk and dv (stride lddkv) are written for every row.
+struct AttnOperands {
+  const void *q, *k, *v;
+  int64_t ldq, ldkv;
+  const int32_t *qlens, *klens;
+  int Lq, Lk, A, causal;
+};
+hs_status launch_attention_general_fwd(hs_ctx* ctx, int dtype, const AttnOperands& x, int B, void* out, float* lse, hipStream_t s);
+hs_status launch_attention_general_bwd(hs_ctx* ctx, int dtype, const AttnOperands& x, int B, const void* out, const float* lse,
+                                       const void* d_out, void* dq, int64_t lddq, void* dk, void* dv, int64_t lddkv, float* dvec,
+                                       hipStream_t s);
+// translation workload (seq2seq_ops.hip)
+hs_status launch_embed_scale_pos(hs_ctx* ctx, int dtype, const void* emb, const int32_t* ids, void* x, int B, int L, int H, int V, float scale,
+                                 const DropCfg* drop, uint32_t site, hipStream_t s);
+hs_status launch_mask_scale(hs_ctx* ctx, int dtype, const void* x, void* y, size_t n, float alpha, const DropCfg* drop, uint32_t site,
+                            hipStream_t s);
+hs_status launch_relu(hs_ctx* ctx, int dtype, void* x, size_t n, hipStream_t s);
+hs_status launch_relu_bwd(hs_ctx* ctx, int dtype, void* dx, const void* h, size_t n, hipStream_t s);
+hs_status launch_smoothed_ce(hs_ctx* ctx, int dtype, const float* logits, int64_t ldl, const int32_t* labels, const int32_t* lens, int B, int L,
+                             int V, float eps, void* dlogits, float* row_loss, float* row_nll, float* loss_sum, float* nll_sum, hipStream_t s);
 hs_status launch_ce_loss(hs_ctx* ctx, int dtype, const float* logits, int64_t ldl, const int32_t* labels, int M, int V, void* dlogits,
                          float* row_loss, float* loss_sum, hipStream_t s);

@@ -120,6 +120,7 @@ hs_status hs_ctx_create(const hs_model_cfg* cfg, hs_ctx** out) {
   c->drop = DropCfg{0u, 1.0f, 0u, 0u, 0u};
   c->armed.on = false;
   c->upd = nullptr;
+  c->is_s2s = false;
   *out = c;
   return HS_OK;
 }

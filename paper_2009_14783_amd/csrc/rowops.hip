@@ -671,7 +671,7 @@ hs_status launch_embed_bwd(hs_ctx* ctx, int dtype, const void* de, const int32_t
   const int T = B * L;
   if (T <= 0) return HS_OK;
   KScope scope(prof_of(ctx), KC_EMBED, 2.0 * T * H, (double)T * H * (2.0 * esize(dtype) + 8.0) + 8.0 * max_pos * H, s);
-  {
+  if (g_pos) {     // a model with a fixed position table has no position gradient
     const int64_t n = (int64_t)max_pos * H;
     dim3 grid((unsigned)((n + 255) / 256));
     if (dtype == HS_BF16) hipLaunchKernelGGL(pos_grad_kernel<bf16>, grid, dim3(256), 0, s, (const bf16*)de, B, L, H, max_pos, g_pos, beta_pos);

@@ -198,3 +198,106 @@ class Worker:
         adam = dict(beta1=head.beta1, beta2=head.beta2, eps=head.eps, weight_decay=head.weight_decay)
         schedule = dict(max_lr=head.max_lr, warmup=int(head.warmup), total=int(head.total))
         return adam, schedule, int(head.seed), int(head.epoch)
+
+
+class PairWorker:
+    """The translation workload's step (section "Transformer Translation Model") through the C ABI: hs_s2s_fwd ->
+    hs_s2s_loss -> hs_s2s_bwd per micro-batch with the gradients summed in G, then normalisation by the global weight
+    (the number of real target tokens unless the caller says otherwise) and Adam.  Buffer ownership and call order only."""
+
+    def __init__(self, model: dict, compute: str, theta0: np.ndarray, label_smoothing: float = 0.1, device: str = "cuda:0"):
+        self.device = torch.device(device)
+        self.compute = hs.HS_BF16 if compute == "bf16" else hs.HS_FP32
+        self.cfg = hs.make_s2s_cfg(model["n_enc"], model["n_dec"], model["hidden"], model["n_heads"], model["ffn"], model["vocab"],
+                                   model["max_pos"], model.get("ln_eps", 1e-5), self.compute)
+        self.ctx = hs.hs_s2s_ctx_create(self.cfg)
+        self.P = hs.hs_s2s_param_count(self.cfg)
+        assert theta0.dtype == np.float32 and theta0.size == self.P
+        self.H = model["hidden"]
+        self.eps_ls = label_smoothing
+        self.act_dtype = torch.bfloat16 if self.compute == hs.HS_BF16 else torch.float32
+        dev = self.device
+        self.w = torch.from_numpy(theta0.copy()).to(dev)
+        self.m = torch.zeros(self.P, dtype=torch.float32, device=dev)
+        self.v = torch.zeros(self.P, dtype=torch.float32, device=dev)
+        self.G = torch.zeros(self.P, dtype=torch.float32, device=dev)
+        self.w_lowp = None
+        if self.compute == hs.HS_BF16:
+            self.w_lowp = torch.empty(self.P, dtype=torch.bfloat16, device=dev)
+            hs.hs_cast_params(self.w, self.w_lowp, self.P, hs.HS_BF16)
+        self.t = 0
+        self._drop_on = False
+        self._acts = self._ws = self._out = self._dout = None
+        self._acts_bytes = self._ws_bytes = 0
+        self.loss_buf = torch.zeros(128, dtype=torch.float32, device=dev)      # slot i: loss sum, slot 64 + i: nll sum
+
+    def close(self):
+        if self.ctx is not None:
+            hs.hs_ctx_destroy(self.ctx)
+            self.ctx = None
+
+    @property
+    def w_compute(self):
+        return self.w_lowp if self.compute == hs.HS_BF16 else self.w
+
+    def _reserve(self, B, Ls, Lt):
+        ab, wb = hs.hs_s2s_acts_bytes(self.cfg, B, Ls, Lt), hs.hs_s2s_workspace_bytes(self.cfg, B, Ls, Lt)
+        if ab > self._acts_bytes:
+            self._acts, self._acts_bytes = torch.empty(ab, dtype=torch.uint8, device=self.device), ab
+        if wb > self._ws_bytes:
+            self._ws, self._ws_bytes = torch.empty(wb, dtype=torch.uint8, device=self.device), wb
+        n = B * Lt * self.H
+        if self._out is None or self._out.numel() < n:
+            self._out = torch.empty(n, dtype=self.act_dtype, device=self.device)
+            self._dout = torch.empty(n, dtype=self.act_dtype, device=self.device)
+
+    def upload(self, mb: dict) -> dict:
+        dev = self.device
+        t = lambda k: torch.from_numpy(np.ascontiguousarray(mb[k], dtype=np.int32)).to(dev)
+        out = dict(B=int(mb["src"].shape[0]), Ls=int(mb["src"].shape[1]), Lt=int(mb["tgt_in"].shape[1]), src=t("src"), src_lens=t("src_lens"),
+                   tgt_in=t("tgt_in"), tgt_out=t("tgt_out"), tgt_lens=t("tgt_lens"), n_seq=int(mb["src"].shape[0]),
+                   n_tok=int(np.asarray(mb["tgt_lens"]).sum()), drop=mb.get("drop"))
+        self._reserve(out["B"], out["Ls"], out["Lt"])
+        return out
+
+    def forward_backward(self, d: dict, g: torch.Tensor, accumulate: int, slot: int):
+        B, Ls, Lt = d["B"], d["Ls"], d["Lt"]
+        self._reserve(B, Ls, Lt)
+        drop = d.get("drop")
+        if drop is not None or self._drop_on:
+            hs.hs_set_dropout(self.ctx, drop["p"] if drop else 0.0, drop["seed"] if drop else 0, drop["stream"] if drop else 0)
+            self._drop_on = drop is not None
+        w = self.w_compute
+        hs.hs_s2s_fwd(self.ctx, w, d["src"], d["src_lens"], d["tgt_in"], d["tgt_lens"], B, Ls, Lt, self._acts, self._out)
+        base = self.loss_buf.data_ptr()
+        hs.hs_s2s_loss(self.ctx, w, self._out, d["tgt_out"], d["tgt_lens"], B, Lt, self.eps_ls, base + 4 * slot, base + 4 * (64 + slot),
+                       self._dout, g, accumulate, self._ws, self._ws_bytes)
+        hs.hs_s2s_bwd(self.ctx, w, self._acts, d["src"], d["src_lens"], d["tgt_in"], d["tgt_lens"], B, Ls, Lt, self._dout, g, accumulate,
+                      self._ws, self._ws_bytes)
+
+    def train_step(self, batches: list, adam: dict, denom=None):
+        """One optimizer step over the uploaded micro-batches (None = a pass without data).  Returns the weight D used
+        (the number of real target tokens by default)."""
+        assert len(batches) <= 64
+        self.loss_buf.zero_()
+        n_tok, first = 0, True
+        for i, d in enumerate(batches):
+            if d is None:
+                hs.hs_grad_accum_normalize(self.G, None, self.P, 1, 0.0)
+                continue
+            self.forward_backward(d, self.G, 0 if first else 1, i)
+            first = False
+            n_tok += d["n_tok"]
+        if first:
+            self.G.zero_()
+        D = float(denom if denom is not None else max(n_tok, 1))
+        self.t += 1
+        hs.hs_grad_accum_normalize(self.G, None, self.P, 0, D)
+        hs.hs_adam_step(self.w, self.m, self.v, self.G, self.w_lowp, self.P, adam["lr"], adam["beta1"], adam["beta2"], adam["eps"],
+                        adam.get("weight_decay", 0.0), self.t)
+        return D
+
+    def reported_loss(self, D):
+        """(smoothed loss, negative log-likelihood), both per unit of weight; synchronises."""
+        lb = self.loss_buf.cpu().numpy().astype(np.float64)
+        return lb[:64].sum() / D, lb[64:].sum() / D
