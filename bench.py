@@ -87,6 +87,119 @@ def cpu_baseline(model, wl, theta, mbs, n_seq_sample=16):
                 host_cores_available=len(os.sched_getaffinity(0)))
 
 
+def pair_workload(synth, seed=1240, B=128, L=32):
+    """The translation workload's batch: 128 sentence pairs in buffers of 32 positions per side (4096 positions per
+    side, the per-worker max-tokens of table 1), lengths uniform in [16, 32] with targets 0.8 .. 1.25 times the source."""
+    rng = synth.rng_for(seed)
+    sl, tl = synth.draw_pair_lengths(rng, B, L // 2, L)
+    return synth.make_pair_batch(rng, sl, tl, L, L, synth.S2S_MODELS["transformer_base"]["vocab"], "zipf")
+
+
+def pair_flops(model, mb):
+    """Forward + backward (2x forward) algorithmic flops: per real source token and encoder layer 8 H^2 + 4 H F + 4 Ls H;
+    per real target token and decoder layer 12 H^2 + 4 H F + 2 Lt H (causal: half the pairs) + 4 Ls H, plus the key/value
+    projection of the encoder output 4 H^2 per source token and decoder layer; output projection 2 H V per target token."""
+    H, F, V = model["hidden"], model["ffn"], model["vocab"]
+    Ls, Lt = mb["src"].shape[1], mb["tgt_in"].shape[1]
+    ns, nt = mb["n_src_tokens"], mb["n_tgt_tokens"]
+    fwd = model["n_enc"] * ns * (8.0 * H * H + 4.0 * H * F + 4.0 * Ls * H)
+    fwd += model["n_dec"] * (nt * (12.0 * H * H + 4.0 * H * F + 2.0 * Lt * H + 4.0 * Ls * H) + ns * 4.0 * H * H)
+    fwd += nt * 2.0 * H * V
+    return 3.0 * fwd
+
+
+def main_pairs(args):
+    """Second workload: one step of the Transformer-base translation model (section "Transformer Translation Model")."""
+    import torch
+    from paper_2009_14783_amd import binding as hs
+    from paper_2009_14783_amd import synth
+    from paper_2009_14783_amd.step import PairWorker
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    hs.lib()
+    model = synth.S2S_MODELS["transformer_base"]
+    adam = dict(lr=5e-4, beta1=0.9, beta2=0.98, eps=1e-9)
+    cfg = hs.make_s2s_cfg(**model)
+    theta = synth.init_params(hs.hs_s2s_param_layout(cfg), 1240)
+    mb = pair_workload(synth)
+    if args.dropout > 0.0:
+        mb["drop"] = dict(p=args.dropout, seed=1240, stream=0)
+    worker = PairWorker(model, "bf16", theta)
+    d = worker.upload(mb)
+    lengths = np.maximum(mb["src_lens"], mb["tgt_lens"]).astype(np.int32)
+
+    def one_step():
+        hs.hs_make_batches(lengths, 32, 4096, 1)      # batch formation under the cap (host); its batch is the uploaded one
+        return worker.train_step([d], adam)
+
+    for _ in range(args.warmup):
+        one_step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        D = one_step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms = 1e3 * dt / args.steps
+    loss, nll = worker.reported_loss(D)
+    hs.hs_profile_enable(worker.ctx, 1)
+    prof = {}
+    for _ in range(args.profile_steps):
+        worker.forward_backward(d, worker.G, 0, 0)
+        torch.cuda.synchronize()
+        for k, e in hs.hs_profile_read(worker.ctx).items():
+            q = prof.setdefault(k, dict(launches=0, ms=0.0, flops=0.0, bytes=0.0))
+            for f in q:
+                q[f] += e[f]
+    hs.hs_profile_enable(worker.ctx, 0)
+    kernels = {k: dict(launches_per_step=q["launches"] / args.profile_steps, ms_per_step=q["ms"] / args.profile_steps,
+                       tflops=q["flops"] / (q["ms"] * 1e-3) / 1e12, gbs=q["bytes"] / (q["ms"] * 1e-3) / 1e9)
+               for k, q in prof.items() if q["launches"] and q["ms"] > 0}
+    gemm = [k for k in ("gemm_fwd", "gemm_dx", "gemm_dw") if k in kernels]
+    dominant = max(gemm, key=lambda k: kernels[k]["ms_per_step"])
+    dp = prof[dominant]
+    achieved = dp["flops"] / (dp["ms"] * 1e-3) / 1e12
+    flops = pair_flops(model, mb)
+    tokens = mb["n_src_tokens"] + mb["n_tgt_tokens"]
+    out = dict(metric="trained tokens/sec on 1 MI355X (Transformer-base translation step) + % peak bf16 MFMA",
+               value=tokens * args.steps / dt, unit="tokens/s", n_gpus=1, steps=args.steps, warmup=args.warmup, ms_per_step=ms,
+               higher_is_better=True, scaling="weak", vs_baseline=None, dtype="bf16", data="synthetic",
+               config=dict(workload="Transformer-base translation step: 6 + 6 post-LN layers, hidden 512, 8 heads, FFN 2048, shared "
+                                    "vocabulary 37000, label smoothing 0.1, Adam 0.9/0.98/1e-9; 128 sentence pairs in 32-position "
+                                    "buffers per side (max-tokens 4096), Zipf(1.1) ids, bf16 compute with fp32 master weights",
+                           tokens_per_step=tokens, source_tokens=mb["n_src_tokens"], target_tokens=mb["n_tgt_tokens"], params=worker.P,
+                           dropout=args.dropout),
+               whole_step_tflops=flops / (ms * 1e-3) / 1e12, whole_step_mfma_frac=flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+               loss=loss, nll=nll,
+               roofline=dict(bound="mfma", kernel=dominant, achieved=achieved, peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
+                             frac=achieved / PEAK_BF16_TFLOPS, traffic=None,
+                             algorithmic_bytes_per_launch=dp["bytes"] / dp["launches"], avg_launch_us=1e3 * dp["ms"] / dp["launches"],
+                             launches_per_step=dp["launches"] / args.profile_steps,
+                             measured=f"HIP events around every launch, on the launch stream, in {args.profile_steps} extra passes"),
+               kernels=kernels)
+    if not args.no_cpu_baseline:
+        from threadpoolctl import threadpool_info
+        from oracle import hetseq_oracle as O
+        from oracle import seq2seq_oracle as S
+        ocfg = S.S2SCfg(**model)
+        n = 128
+        sample = {k: (v[:n] if isinstance(v, np.ndarray) else v) for k, v in mb.items()}
+        th = theta.copy()
+        t0 = time.perf_counter()
+        l, _, g, _, n_tok = S.micro_batch_grad(ocfg, th, sample, 0.1)
+        O.normalize(g, n_tok)
+        O.adam_step(th, np.zeros_like(th), np.zeros_like(th), g, 1, **adam)
+        cdt = time.perf_counter() - t0
+        stok = int(sample["src_lens"].sum() + sample["tgt_lens"].sum())
+        threads = max([q.get("num_threads", 1) for q in threadpool_info()] + [1])
+        out["cpu_baseline"] = dict(value=stok / cdt, unit="tokens/s", cores=int(threads), kind="oracle",
+                                   sample=f"all {n} sentence pairs of the batch ({stok} tokens), full model, one whole step in fp32 "
+                                          f"NumPy: {cdt:.1f} s", host_cores_available=len(os.sched_getaffinity(0)))
+    worker.close()
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -96,11 +209,16 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--dropout", type=float, default=0.0,
                     help="dropout rate at the model's four kinds of sites (the headline figure is taken without: 0)")
+    ap.add_argument("--workload", choices=["bert_base", "transformer_base"], default="bert_base",
+                    help="bert_base: the headline workload; transformer_base: the translation model's step")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus must be 1 (no collectives, no sharding in this path)",
               file=sys.stderr)
         sys.exit(2)
+
+    if args.workload == "transformer_base":
+        return main_pairs(args)
 
     import torch
     from paper_2009_14783_amd import binding as hs

@@ -235,8 +235,9 @@ hs_status launch_attention_general_bwd(hs_ctx* ctx, int dtype, const AttnOperand
                                        const void* d_out, void* dq, int64_t lddq, void* dk, void* dv, int64_t lddkv, float* dvec,
                                        hipStream_t s);
 // translation workload (seq2seq_ops.hip)
-hs_status launch_embed_scale_pos(hs_ctx* ctx, int dtype, const void* emb, const int32_t* ids, void* x, int B, int L, int H, int V, float scale,
-                                 const DropCfg* drop, uint32_t site, hipStream_t s);
+hs_status launch_position_table(hs_ctx* ctx, float* pe, int L, int H, hipStream_t s);     // pe [L, H] fp32
+hs_status launch_embed_scale_pos(hs_ctx* ctx, int dtype, const void* emb, const int32_t* ids, const float* pe, void* x, int B, int L, int H, int V,
+                                 float scale, const DropCfg* drop, uint32_t site, hipStream_t s);
 hs_status launch_mask_scale(hs_ctx* ctx, int dtype, const void* x, void* y, size_t n, float alpha, const DropCfg* drop, uint32_t site,
                             hipStream_t s);
 hs_status launch_relu(hs_ctx* ctx, int dtype, void* x, size_t n, hipStream_t s);

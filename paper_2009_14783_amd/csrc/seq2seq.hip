@@ -87,12 +87,13 @@ bool s2s_cfg_valid(const hs_s2s_cfg* c, std::string* why) {
 // ---- saved activations ------------------------------------------------------------------------
 struct EncActs { void *qkv, *ctx, *y1, *x1, *h, *y2, *x2; float *lse, *st1, *st2; };
 struct DecActs { void *qkv, *ctx, *y1s, *y1, *cq, *ckv, *cctx, *ycs, *yc, *h, *y2s, *y2; float *lse, *clse, *st1, *stc, *st2; };
-struct Acts { void *x0, *t0; std::vector<EncActs> enc; std::vector<DecActs> dec; size_t total; };
+struct Acts { float* pe; void *x0, *t0; std::vector<EncActs> enc; std::vector<DecActs> dec; size_t total; };
 
 Acts carve_acts(const hs_s2s_cfg& c, int B, int Ls, int Lt, void* base) {
   const size_t Ts = (size_t)B * Ls, Tt = (size_t)B * Lt, H = c.hidden, F = c.ffn, es = esize(c.compute), A = c.n_heads;
   Carver cv(base);
   Acts a;
+  a.pe = (float*)cv.take((size_t)std::max(Ls, Lt) * H * sizeof(float));
   a.x0 = cv.take(Ts * H * es); a.t0 = cv.take(Tt * H * es);
   a.enc.resize(c.n_enc); a.dec.resize(c.n_dec);
   for (auto& l : a.enc) {
@@ -135,27 +136,53 @@ LossWs carve_loss(const hs_s2s_cfg& c, int B, int Lt, void* base) {
   return w;
 }
 
+// Backward workspace.  The buffers that the weight-gradient GEMMs and bias column sums read (they run on a second stream
+// beside the chain of activation gradients) exist once per layer and sub-layer, so that the chain never has to wait
+// before it overwrites anything; buffers that only the chain touches are shared by all layers.
+struct LayerGrads { void *s2, *m2, *sc, *mc, *s1, *m1, *dh, *dcq, *dckv, *dqkv; };
 struct BwdWs {
-  void *da, *db, *dsum, *dmask, *dh, *dctx, *dqkv, *dcq, *dckv, *denc[2], *ln_part, *cs_part, *emb, *gemm_ws;
+  void *da, *db, *dctx, *denc[2], *ln_part, *cs_part, *emb, *gemm_ws, *gemm_ws_side;
+  std::vector<LayerGrads> enc, dec;
   float* dvec;
   size_t gemm_ws_bytes, total;
 };
 BwdWs carve_bwd(const hs_s2s_cfg& c, int B, int Ls, int Lt, void* base) {
-  const size_t Tm = (size_t)B * std::max(Ls, Lt), Ts = (size_t)B * Ls, H = c.hidden, F = c.ffn, es = esize(c.compute);
+  const size_t Tm = (size_t)B * std::max(Ls, Lt), Ts = (size_t)B * Ls, Tt = (size_t)B * Lt, H = c.hidden, F = c.ffn, es = esize(c.compute);
   Carver cv(base);
   BwdWs w;
-  w.da = cv.take(Tm * H * es); w.db = cv.take(Tm * H * es); w.dsum = cv.take(Tm * H * es); w.dmask = cv.take(Tm * H * es);
-  w.dh = cv.take(Tm * F * es); w.dctx = cv.take(Tm * H * es); w.dqkv = cv.take(Tm * 3 * H * es);
-  w.dcq = cv.take(Tm * H * es); w.dckv = cv.take(Ts * 2 * H * es);
+  w.da = cv.take(Tm * H * es); w.db = cv.take(Tm * H * es); w.dctx = cv.take(Tm * H * es);
   w.denc[0] = cv.take(Ts * H * es); w.denc[1] = cv.take(Ts * H * es);
+  w.enc.resize(c.n_enc); w.dec.resize(c.n_dec);
+  for (auto& l : w.enc) {
+    l = LayerGrads{};
+    l.s2 = cv.take(Ts * H * es); l.m2 = cv.take(Ts * H * es); l.s1 = cv.take(Ts * H * es); l.m1 = cv.take(Ts * H * es);
+    l.dh = cv.take(Ts * F * es); l.dqkv = cv.take(Ts * 3 * H * es);
+  }
+  for (auto& l : w.dec) {
+    l.s2 = cv.take(Tt * H * es); l.m2 = cv.take(Tt * H * es); l.sc = cv.take(Tt * H * es); l.mc = cv.take(Tt * H * es);
+    l.s1 = cv.take(Tt * H * es); l.m1 = cv.take(Tt * H * es);
+    l.dh = cv.take(Tt * F * es); l.dcq = cv.take(Tt * H * es); l.dckv = cv.take(Ts * 2 * H * es); l.dqkv = cv.take(Tt * 3 * H * es);
+  }
   w.dvec = (float*)cv.take((size_t)B * c.n_heads * std::max(Ls, Lt) * sizeof(float));
   w.ln_part = cv.take(layernorm_bwd_scratch((int)Tm, (int)H));
   w.cs_part = cv.take(colsum_scratch((int)Tm, (int)std::max(F, 3 * H)));
   w.emb = cv.take(embed_bwd_scratch((int)Tm, (int)H));
   w.gemm_ws_bytes = gemm_scratch_bytes(c);
   w.gemm_ws = cv.take(w.gemm_ws_bytes);
+  w.gemm_ws_side = cv.take(w.gemm_ws_bytes);
   w.total = cv.off;
   return w;
+}
+
+// second stream + ordering events of a context, created on first use
+hs_status ensure_side_stream(hs_ctx* ctx, size_t n_events) {
+  if (!ctx->side) HS_HIP_CHECK(ctx, hipStreamCreateWithFlags(&ctx->side, hipStreamNonBlocking));
+  while (ctx->events.size() < n_events) {
+    hipEvent_t e;
+    HS_HIP_CHECK(ctx, hipEventCreateWithFlags(&e, hipEventDisableTiming));
+    ctx->events.push_back(e);
+  }
+  return HS_OK;
 }
 
 bool shape_ok(const hs_s2s_cfg& c, int B, int Ls, int Lt, std::string* why) {
@@ -193,12 +220,12 @@ hs_status linear(hs_ctx* ctx, int dt, int T, int N, int K, const void* x, const 
 }
 // sum = res + drop(x W^T + b) ; out = LN(sum)
 hs_status linear_res_ln(hs_ctx* ctx, int dt, int T, int H, int K, const void* x, const void* Wm, const void* b, const void* res, void* sum,
-                        const void* gain, const void* beta, void* out, float* stats, float eps, const DropCfg* drop, uint32_t site,
-                        hipStream_t s) {
+                        const void* gain, const void* beta, void* out, float* stats, int stat_ld, float eps, const DropCfg* drop,
+                        uint32_t site, hipStream_t s) {
   GemmArgs g = gemm_args(dt, 1, 1, T, H, K, x, K, Wm, K, sum, H);
   g.bias = b; g.epi = 1; g.aux = res; g.ldaux = H; g.drop = drop; g.drop_site = site;
   HS_TRY(launch_gemm(ctx, g, s));
-  return launch_layernorm_fwd(ctx, dt, sum, gain, beta, out, stats, T, H, eps, s);
+  return launch_layernorm_fwd(ctx, dt, sum, gain, beta, out, stats, T, H, eps, s, stat_ld);
 }
 
 }  // namespace
@@ -263,49 +290,98 @@ hs_status hs_s2s_fwd(hs_ctx* ctx, const void* w, const int32_t* src, const int32
   Acts a = carve_acts(c, B, Ls, Lt, acts);
   const DropCfg* drop = ctx->drop.thr ? &ctx->drop : nullptr;
   const float scale = sqrtf((float)H);
+  const int64_t es = (int64_t)esize(dt);
+
+  // Sentence pairs are independent in the forward pass.  A batch of some size runs as two halves on two streams (the
+  // caller's and the context's second one) over row ranges of the same buffers: one half's launch ramp-ups and tails
+  // fill with the other half's work, and the results are those of one pass.  Not with dropout (its element indices
+  // count rows of the whole batch) nor with per-launch timing.
+  const bool split = ctx->prof == nullptr && !drop && B >= 2 && std::min(Ts, Tt) >= 2048;
+  HS_TRY(launch_position_table(ctx, a.pe, std::max(Ls, Lt), H, s));
+  if (split) {
+    HS_TRY(ensure_side_stream(ctx, 2));
+    HS_HIP_CHECK(ctx, hipEventRecord(ctx->events[0], s));
+    HS_HIP_CHECK(ctx, hipStreamWaitEvent(ctx->side, ctx->events[0], 0));
+  }
+  struct Part { int b0, nb; hipStream_t st; };
+  const Part part[2] = {{0, split ? B / 2 : B, s}, {B / 2, B - B / 2, split ? ctx->side : s}};
+  const int nparts = split ? 2 : 1;
+  // rows of sequence b0 onwards in a buffer with L positions per sequence and `width` elements per position
+  auto src_rows = [&](const void* p, const Part& pt, int64_t width) { return (const void*)((const char*)p + (int64_t)pt.b0 * Ls * width * es); };
+  auto tgt_rows = [&](const void* p, const Part& pt, int64_t width) { return (const void*)((const char*)p + (int64_t)pt.b0 * Lt * width * es); };
+  auto mut = [](const void* p) { return const_cast<void*>(p); };
 
   // ---- encoder ----
-  HS_TRY(launch_embed_scale_pos(ctx, dt, W(dt, w, o.emb), src, a.x0, B, Ls, H, c.vocab, scale, drop, site_src(), s));
+  for (int k = 0; k < nparts; ++k) {
+    const Part& pt = part[k];
+    HS_TRY(launch_embed_scale_pos(ctx, dt, W(dt, w, o.emb), src + (size_t)pt.b0 * Ls, a.pe, mut(src_rows(a.x0, pt, H)), pt.nb, Ls, H, c.vocab, scale,
+                                  drop, site_src(), pt.st));
+  }
   const void* x = a.x0;
   for (int i = 0; i < c.n_enc; ++i) {
     const BlockOff& lo = o.enc[i];
     EncActs& la = a.enc[i];
-    HS_TRY(linear(ctx, dt, Ts, 3 * H, H, x, W(dt, w, lo.qkv_w), W(dt, w, lo.qkv_b), la.qkv, s));
-    HS_TRY(launch_attention_fwd(ctx, dt, la.qkv, src_lens, B, Ls, A, la.ctx, la.lse, s));
-    HS_TRY(linear_res_ln(ctx, dt, Ts, H, H, la.ctx, W(dt, w, lo.o_w), W(dt, w, lo.o_b), x, la.y1, W(dt, w, lo.ln1_g), W(dt, w, lo.ln1_b), la.x1,
-                         la.st1, c.ln_eps, drop, site_enc(i, 0), s));
-    HS_TRY(linear(ctx, dt, Ts, F, H, la.x1, W(dt, w, lo.ffn1_w), W(dt, w, lo.ffn1_b), la.h, s));
-    HS_TRY(launch_relu(ctx, dt, la.h, (size_t)Ts * F, s));
-    HS_TRY(linear_res_ln(ctx, dt, Ts, H, F, la.h, W(dt, w, lo.ffn2_w), W(dt, w, lo.ffn2_b), la.x1, la.y2, W(dt, w, lo.ln2_g), W(dt, w, lo.ln2_b),
-                         la.x2, la.st2, c.ln_eps, drop, site_enc(i, 1), s));
+    for (int k = 0; k < nparts; ++k) {
+      const Part& pt = part[k];
+      const int T = pt.nb * Ls;
+      hipStream_t st = pt.st;
+      auto R = [&](const void* p, int64_t width) { return src_rows(p, pt, width); };
+      HS_TRY(linear(ctx, dt, T, 3 * H, H, R(x, H), W(dt, w, lo.qkv_w), W(dt, w, lo.qkv_b), mut(R(la.qkv, 3 * H)), st));
+      HS_TRY(launch_attention_fwd(ctx, dt, R(la.qkv, 3 * H), src_lens + pt.b0, pt.nb, Ls, A, mut(R(la.ctx, H)), la.lse + (size_t)pt.b0 * A * Ls, st));
+      HS_TRY(linear_res_ln(ctx, dt, T, H, H, R(la.ctx, H), W(dt, w, lo.o_w), W(dt, w, lo.o_b), R(x, H), mut(R(la.y1, H)), W(dt, w, lo.ln1_g),
+                           W(dt, w, lo.ln1_b), mut(R(la.x1, H)), la.st1 + (size_t)pt.b0 * Ls, Ts, c.ln_eps, drop, site_enc(i, 0), st));
+      HS_TRY(linear(ctx, dt, T, F, H, R(la.x1, H), W(dt, w, lo.ffn1_w), W(dt, w, lo.ffn1_b), mut(R(la.h, F)), st));
+      HS_TRY(launch_relu(ctx, dt, mut(R(la.h, F)), (size_t)T * F, st));
+      HS_TRY(linear_res_ln(ctx, dt, T, H, F, R(la.h, F), W(dt, w, lo.ffn2_w), W(dt, w, lo.ffn2_b), R(la.x1, H), mut(R(la.y2, H)), W(dt, w, lo.ln2_g),
+                           W(dt, w, lo.ln2_b), mut(R(la.x2, H)), la.st2 + (size_t)pt.b0 * Ls, Ts, c.ln_eps, drop, site_enc(i, 1), st));
+    }
     x = la.x2;
   }
   const void* enc_out = x;
 
   // ---- decoder ----
-  HS_TRY(launch_embed_scale_pos(ctx, dt, W(dt, w, o.emb), tgt_in, a.t0, B, Lt, H, c.vocab, scale, drop, site_tgt(), s));
+  for (int k = 0; k < nparts; ++k) {
+    const Part& pt = part[k];
+    HS_TRY(launch_embed_scale_pos(ctx, dt, W(dt, w, o.emb), tgt_in + (size_t)pt.b0 * Lt, a.pe, mut(tgt_rows(a.t0, pt, H)), pt.nb, Lt, H, c.vocab,
+                                  scale, drop, site_tgt(), pt.st));
+  }
   const void* y = a.t0;
   for (int i = 0; i < c.n_dec; ++i) {
     const BlockOff& lo = o.dec[i];
     DecActs& la = a.dec[i];
     void* y2 = la.y2 ? la.y2 : dec_out;
-    HS_TRY(linear(ctx, dt, Tt, 3 * H, H, y, W(dt, w, lo.qkv_w), W(dt, w, lo.qkv_b), la.qkv, s));
-    AttnOperands self{la.qkv, at(dt, (const void*)la.qkv, H), at(dt, (const void*)la.qkv, 2 * H), 3 * (int64_t)H, 3 * (int64_t)H, tgt_lens, tgt_lens,
-                      Lt, Lt, A, 1};
-    HS_TRY(launch_attention_general_fwd(ctx, dt, self, B, la.ctx, la.lse, s));
-    HS_TRY(linear_res_ln(ctx, dt, Tt, H, H, la.ctx, W(dt, w, lo.o_w), W(dt, w, lo.o_b), y, la.y1s, W(dt, w, lo.ln1_g), W(dt, w, lo.ln1_b), la.y1,
-                         la.st1, c.ln_eps, drop, site_dec(c, i, 0), s));
-    HS_TRY(linear(ctx, dt, Tt, H, H, la.y1, W(dt, w, lo.cq_w), W(dt, w, lo.cq_b), la.cq, s));
-    HS_TRY(linear(ctx, dt, Ts, 2 * H, H, enc_out, W(dt, w, lo.ckv_w), W(dt, w, lo.ckv_b), la.ckv, s));
-    AttnOperands cross{la.cq, la.ckv, at(dt, (const void*)la.ckv, H), (int64_t)H, 2 * (int64_t)H, tgt_lens, src_lens, Lt, Ls, A, 0};
-    HS_TRY(launch_attention_general_fwd(ctx, dt, cross, B, la.cctx, la.clse, s));
-    HS_TRY(linear_res_ln(ctx, dt, Tt, H, H, la.cctx, W(dt, w, lo.co_w), W(dt, w, lo.co_b), la.y1, la.ycs, W(dt, w, lo.lnc_g), W(dt, w, lo.lnc_b),
-                         la.yc, la.stc, c.ln_eps, drop, site_dec(c, i, 1), s));
-    HS_TRY(linear(ctx, dt, Tt, F, H, la.yc, W(dt, w, lo.ffn1_w), W(dt, w, lo.ffn1_b), la.h, s));
-    HS_TRY(launch_relu(ctx, dt, la.h, (size_t)Tt * F, s));
-    HS_TRY(linear_res_ln(ctx, dt, Tt, H, F, la.h, W(dt, w, lo.ffn2_w), W(dt, w, lo.ffn2_b), la.yc, la.y2s, W(dt, w, lo.ln2_g), W(dt, w, lo.ln2_b),
-                         y2, la.st2, c.ln_eps, drop, site_dec(c, i, 2), s));
+    for (int k = 0; k < nparts; ++k) {
+      const Part& pt = part[k];
+      const int T = pt.nb * Lt, TS = pt.nb * Ls;
+      hipStream_t st = pt.st;
+      auto R = [&](const void* p, int64_t width) { return tgt_rows(p, pt, width); };
+      const int32_t* tl = tgt_lens + pt.b0;
+      const int32_t* sl = src_lens + pt.b0;
+      HS_TRY(linear(ctx, dt, T, 3 * H, H, R(y, H), W(dt, w, lo.qkv_w), W(dt, w, lo.qkv_b), mut(R(la.qkv, 3 * H)), st));
+      const void* qkv = R(la.qkv, 3 * H);
+      AttnOperands self{qkv, at(dt, qkv, H), at(dt, qkv, 2 * H), 3 * (int64_t)H, 3 * (int64_t)H, tl, tl, Lt, Lt, A, 1};
+      HS_TRY(launch_attention_general_fwd(ctx, dt, self, pt.nb, mut(R(la.ctx, H)), la.lse + (size_t)pt.b0 * A * Lt, st));
+      HS_TRY(linear_res_ln(ctx, dt, T, H, H, R(la.ctx, H), W(dt, w, lo.o_w), W(dt, w, lo.o_b), R(y, H), mut(R(la.y1s, H)), W(dt, w, lo.ln1_g),
+                           W(dt, w, lo.ln1_b), mut(R(la.y1, H)), la.st1 + (size_t)pt.b0 * Lt, Tt, c.ln_eps, drop, site_dec(c, i, 0), st));
+      HS_TRY(linear(ctx, dt, T, H, H, R(la.y1, H), W(dt, w, lo.cq_w), W(dt, w, lo.cq_b), mut(R(la.cq, H)), st));
+      const void* ckv = src_rows(la.ckv, pt, 2 * H);
+      HS_TRY(linear(ctx, dt, TS, 2 * H, H, src_rows(enc_out, pt, H), W(dt, w, lo.ckv_w), W(dt, w, lo.ckv_b), mut(ckv), st));
+      AttnOperands cross{R(la.cq, H), ckv, at(dt, ckv, H), (int64_t)H, 2 * (int64_t)H, tl, sl, Lt, Ls, A, 0};
+      HS_TRY(launch_attention_general_fwd(ctx, dt, cross, pt.nb, mut(R(la.cctx, H)), la.clse + (size_t)pt.b0 * A * Lt, st));
+      HS_TRY(linear_res_ln(ctx, dt, T, H, H, R(la.cctx, H), W(dt, w, lo.co_w), W(dt, w, lo.co_b), R(la.y1, H), mut(R(la.ycs, H)),
+                           W(dt, w, lo.lnc_g), W(dt, w, lo.lnc_b), mut(R(la.yc, H)), la.stc + (size_t)pt.b0 * Lt, Tt, c.ln_eps, drop,
+                           site_dec(c, i, 1), st));
+      HS_TRY(linear(ctx, dt, T, F, H, R(la.yc, H), W(dt, w, lo.ffn1_w), W(dt, w, lo.ffn1_b), mut(R(la.h, F)), st));
+      HS_TRY(launch_relu(ctx, dt, mut(R(la.h, F)), (size_t)T * F, st));
+      HS_TRY(linear_res_ln(ctx, dt, T, H, F, R(la.h, F), W(dt, w, lo.ffn2_w), W(dt, w, lo.ffn2_b), R(la.yc, H), mut(R(la.y2s, H)),
+                           W(dt, w, lo.ln2_g), W(dt, w, lo.ln2_b), mut(R(y2, H)), la.st2 + (size_t)pt.b0 * Lt, Tt, c.ln_eps, drop,
+                           site_dec(c, i, 2), st));
+    }
     y = y2;
+  }
+  if (split) {     // the second half is ordered before whatever the caller enqueues next
+    HS_HIP_CHECK(ctx, hipEventRecord(ctx->events[1], ctx->side));
+    HS_HIP_CHECK(ctx, hipStreamWaitEvent(s, ctx->events[1], 0));
   }
   return HS_OK;
 }
@@ -366,11 +442,27 @@ hs_status hs_s2s_bwd(hs_ctx* ctx, const void* w, const void* acts, const int32_t
   const DropCfg* drop = ctx->drop.thr ? &ctx->drop : nullptr;
   const float scale = sqrtf((float)H);
 
+  // The weight gradients and bias column sums only consume what the chain of activation gradients produces: they run on
+  // the context's second stream, each after the event that marks its operand ready, and the caller's stream waits for
+  // them once, at the end.  With per-launch timing enabled everything stays on the caller's stream.
+  const bool overlap = ctx->prof == nullptr;
+  const size_t n_events = (size_t)6 * c.n_dec + 4 * c.n_enc + 1;
+  if (overlap) HS_TRY(ensure_side_stream(ctx, n_events));
+  hipStream_t sd = overlap ? ctx->side : s;
+  size_t next_event = 0;
+  auto hand_over = [&]() -> hs_status {       // what the caller's stream has produced so far may now be read on the second one
+    if (!overlap) return HS_OK;
+    hipEvent_t e = ctx->events[next_event++];
+    HS_HIP_CHECK(ctx, hipEventRecord(e, s));
+    HS_HIP_CHECK(ctx, hipStreamWaitEvent(sd, e, 0));
+    return HS_OK;
+  };
   auto wgrad = [&](int M, int N, int K, const void* dy, int64_t ldd, const void* xin, int64_t ldx, float* dst) {   // dst [M,N] (+)= dy^T x
     GemmArgs ga = gemm_args(dt, 0, 0, M, N, K, dy, ldd, xin, ldx, dst, N);
-    ga.c_f32 = 1; ga.beta = beta; ga.ws = ws.gemm_ws; ga.ws_bytes = ws.gemm_ws_bytes;
-    return launch_gemm(ctx, ga, s);
+    ga.c_f32 = 1; ga.beta = beta; ga.ws = ws.gemm_ws_side; ga.ws_bytes = ws.gemm_ws_bytes;
+    return launch_gemm(ctx, ga, sd);
   };
+  auto bias_grad = [&](const void* dy, int T, int N, float* dst) { return launch_colsum(ctx, dt, dy, N, T, N, dst, beta, ws.cs_part, sd); };
   auto dgrad = [&](int T, int N, int K, const void* dy, const void* Wm, void* dx, const void* res) {   // dx [T,N] = dy [T,K] W [K,N] (+ res)
     GemmArgs ga = gemm_args(dt, 1, 0, T, N, K, dy, K, Wm, N, dx, N);
     if (res) { ga.epi = 1; ga.aux = res; ga.ldaux = N; }
@@ -378,22 +470,24 @@ hs_status hs_s2s_bwd(hs_ctx* ctx, const void* w, const void* acts, const int32_t
     return launch_gemm(ctx, ga, s);
   };
   // LayerNorm backward of a sub-layer: dsum = d(residual sum); the branch takes dsum through the sub-layer's dropout
-  // (returned in *branch: dsum itself without dropout); the column sums of the branch gradient are the bias gradient
-  // of the sub-layer's last linear map.
+  // (dmask; dsum itself without dropout); the column sums of the branch gradient are the bias gradient of the
+  // sub-layer's last linear map.  Returns the branch gradient.
   auto ln_bwd = [&](int T, const void* dy, const void* sum, const float* stats, int64_t gain, int64_t lnb, int64_t last_bias, uint32_t site,
-                    const void** branch) {
-    *branch = drop ? ws.dmask : ws.dsum;
-    return launch_layernorm_bwd(ctx, dt, dy, sum, stats, W(dt, w, gain), ws.dsum, g + gain, g + lnb, g + last_bias, beta, T, H, ws.ln_part, s,
-                                drop, site, drop ? 2 : 0, drop ? ws.dmask : nullptr);
+                    void* dsum, void* dmask, const void** branch) {
+    *branch = drop ? dmask : dsum;
+    return launch_layernorm_bwd(ctx, dt, dy, sum, stats, W(dt, w, gain), dsum, g + gain, g + lnb, g + last_bias, beta, T, H, ws.ln_part, s,
+                                drop, site, drop ? 2 : 0, drop ? dmask : nullptr);
   };
   // feed-forward backward: from the branch gradient to d(input of the sub-layer) = dsum + dh W1, written to out
-  auto ffn_bwd = [&](int T, const BlockOff& lo, const void* branch, const void* xin, const void* h, void* out) -> hs_status {
+  auto ffn_bwd = [&](int T, const BlockOff& lo, const LayerGrads& lg, const void* branch, const void* xin, const void* h, void* out) -> hs_status {
+    HS_TRY(hand_over());
     HS_TRY(wgrad(H, F, T, branch, H, h, F, g + lo.ffn2_w));
-    HS_TRY(dgrad(T, F, H, branch, W(dt, w, lo.ffn2_w), ws.dh, nullptr));
-    HS_TRY(launch_relu_bwd(ctx, dt, ws.dh, h, (size_t)T * F, s));
-    HS_TRY(launch_colsum(ctx, dt, ws.dh, F, T, F, g + lo.ffn1_b, beta, ws.cs_part, s));
-    HS_TRY(wgrad(F, H, T, ws.dh, F, xin, H, g + lo.ffn1_w));
-    return dgrad(T, H, F, ws.dh, W(dt, w, lo.ffn1_w), out, ws.dsum);
+    HS_TRY(dgrad(T, F, H, branch, W(dt, w, lo.ffn2_w), lg.dh, nullptr));
+    HS_TRY(launch_relu_bwd(ctx, dt, lg.dh, h, (size_t)T * F, s));
+    HS_TRY(hand_over());
+    HS_TRY(bias_grad(lg.dh, T, F, g + lo.ffn1_b));
+    HS_TRY(wgrad(F, H, T, lg.dh, F, xin, H, g + lo.ffn1_w));
+    return dgrad(T, H, F, lg.dh, W(dt, w, lo.ffn1_w), out, lg.s2);
   };
 
   // ---- decoder ----
@@ -404,36 +498,41 @@ hs_status hs_s2s_bwd(hs_ctx* ctx, const void* w, const void* acts, const int32_t
   for (int i = c.n_dec - 1; i >= 0; --i) {
     const BlockOff& lo = o.dec[i];
     DecActs& la = a.dec[i];
+    const LayerGrads& lg = ws.dec[i];
     const void* y_in = (i == 0) ? a.t0 : a.dec[i - 1].y2;
     const void* br;
     // feed-forward sub-layer
-    HS_TRY(ln_bwd(Tt, dcur, la.y2s, la.st2, lo.ln2_g, lo.ln2_b, lo.ffn2_b, site_dec(c, i, 2), &br));
-    HS_TRY(ffn_bwd(Tt, lo, br, la.yc, la.h, ws.da));
+    HS_TRY(ln_bwd(Tt, dcur, la.y2s, la.st2, lo.ln2_g, lo.ln2_b, lo.ffn2_b, site_dec(c, i, 2), lg.s2, lg.m2, &br));
+    HS_TRY(ffn_bwd(Tt, lo, lg, br, la.yc, la.h, ws.da));
     // attention over the encoder output
-    HS_TRY(ln_bwd(Tt, ws.da, la.ycs, la.stc, lo.lnc_g, lo.lnc_b, lo.co_b, site_dec(c, i, 1), &br));
+    HS_TRY(ln_bwd(Tt, ws.da, la.ycs, la.stc, lo.lnc_g, lo.lnc_b, lo.co_b, site_dec(c, i, 1), lg.sc, lg.mc, &br));
+    HS_TRY(hand_over());
     HS_TRY(wgrad(H, H, Tt, br, H, la.cctx, H, g + lo.co_w));
     HS_TRY(dgrad(Tt, H, H, br, W(dt, w, lo.co_w), ws.dctx, nullptr));
     AttnOperands cross{la.cq, la.ckv, at(dt, (const void*)la.ckv, H), (int64_t)H, 2 * (int64_t)H, tgt_lens, src_lens, Lt, Ls, A, 0};
-    HS_TRY(launch_attention_general_bwd(ctx, dt, cross, B, la.cctx, la.clse, ws.dctx, ws.dcq, H, ws.dckv, at(dt, ws.dckv, H), 2 * (int64_t)H,
+    HS_TRY(launch_attention_general_bwd(ctx, dt, cross, B, la.cctx, la.clse, ws.dctx, lg.dcq, H, lg.dckv, at(dt, lg.dckv, H), 2 * (int64_t)H,
                                         ws.dvec, s));
-    HS_TRY(launch_colsum(ctx, dt, ws.dckv, 2 * H, Ts, 2 * H, g + lo.ckv_b, beta, ws.cs_part, s));
-    HS_TRY(wgrad(2 * H, H, Ts, ws.dckv, 2 * H, enc_out, H, g + lo.ckv_w));
-    HS_TRY(dgrad(Ts, H, 2 * H, ws.dckv, W(dt, w, lo.ckv_w), ws.denc[pe ^ 1], have_denc ? ws.denc[pe] : nullptr));
+    HS_TRY(hand_over());
+    HS_TRY(bias_grad(lg.dckv, Ts, 2 * H, g + lo.ckv_b));
+    HS_TRY(wgrad(2 * H, H, Ts, lg.dckv, 2 * H, enc_out, H, g + lo.ckv_w));
+    HS_TRY(bias_grad(lg.dcq, Tt, H, g + lo.cq_b));
+    HS_TRY(wgrad(H, H, Tt, lg.dcq, H, la.y1, H, g + lo.cq_w));
+    HS_TRY(dgrad(Ts, H, 2 * H, lg.dckv, W(dt, w, lo.ckv_w), ws.denc[pe ^ 1], have_denc ? ws.denc[pe] : nullptr));
     pe ^= 1; have_denc = true;
-    HS_TRY(launch_colsum(ctx, dt, ws.dcq, H, Tt, H, g + lo.cq_b, beta, ws.cs_part, s));
-    HS_TRY(wgrad(H, H, Tt, ws.dcq, H, la.y1, H, g + lo.cq_w));
-    HS_TRY(dgrad(Tt, H, H, ws.dcq, W(dt, w, lo.cq_w), ws.db, ws.dsum));
+    HS_TRY(dgrad(Tt, H, H, lg.dcq, W(dt, w, lo.cq_w), ws.db, lg.sc));
     // causal self-attention
-    HS_TRY(ln_bwd(Tt, ws.db, la.y1s, la.st1, lo.ln1_g, lo.ln1_b, lo.o_b, site_dec(c, i, 0), &br));
+    HS_TRY(ln_bwd(Tt, ws.db, la.y1s, la.st1, lo.ln1_g, lo.ln1_b, lo.o_b, site_dec(c, i, 0), lg.s1, lg.m1, &br));
+    HS_TRY(hand_over());
     HS_TRY(wgrad(H, H, Tt, br, H, la.ctx, H, g + lo.o_w));
     HS_TRY(dgrad(Tt, H, H, br, W(dt, w, lo.o_w), ws.dctx, nullptr));
     AttnOperands self{la.qkv, at(dt, (const void*)la.qkv, H), at(dt, (const void*)la.qkv, 2 * H), 3 * (int64_t)H, 3 * (int64_t)H, tgt_lens, tgt_lens,
                       Lt, Lt, A, 1};
-    HS_TRY(launch_attention_general_bwd(ctx, dt, self, B, la.ctx, la.lse, ws.dctx, ws.dqkv, 3 * (int64_t)H, at(dt, ws.dqkv, H),
-                                        at(dt, ws.dqkv, 2 * H), 3 * (int64_t)H, ws.dvec, s));
-    HS_TRY(launch_colsum(ctx, dt, ws.dqkv, 3 * H, Tt, 3 * H, g + lo.qkv_b, beta, ws.cs_part, s));
-    HS_TRY(wgrad(3 * H, H, Tt, ws.dqkv, 3 * H, y_in, H, g + lo.qkv_w));
-    HS_TRY(dgrad(Tt, H, 3 * H, ws.dqkv, W(dt, w, lo.qkv_w), ws.da, ws.dsum));
+    HS_TRY(launch_attention_general_bwd(ctx, dt, self, B, la.ctx, la.lse, ws.dctx, lg.dqkv, 3 * (int64_t)H, at(dt, lg.dqkv, H),
+                                        at(dt, lg.dqkv, 2 * H), 3 * (int64_t)H, ws.dvec, s));
+    HS_TRY(hand_over());
+    HS_TRY(bias_grad(lg.dqkv, Tt, 3 * H, g + lo.qkv_b));
+    HS_TRY(wgrad(3 * H, H, Tt, lg.dqkv, 3 * H, y_in, H, g + lo.qkv_w));
+    HS_TRY(dgrad(Tt, H, 3 * H, lg.dqkv, W(dt, w, lo.qkv_w), ws.da, lg.s1));
     dcur = ws.da;
   }
   // target embedding: d E[id] += sqrt(H) * (gradient through the embedding dropout)
@@ -445,21 +544,30 @@ hs_status hs_s2s_bwd(hs_ctx* ctx, const void* w, const void* acts, const int32_t
   for (int i = c.n_enc - 1; i >= 0; --i) {
     const BlockOff& lo = o.enc[i];
     EncActs& la = a.enc[i];
+    const LayerGrads& lg = ws.enc[i];
     const void* x_in = (i == 0) ? a.x0 : a.enc[i - 1].x2;
     const void* br;
-    HS_TRY(ln_bwd(Ts, dcur, la.y2, la.st2, lo.ln2_g, lo.ln2_b, lo.ffn2_b, site_enc(i, 1), &br));
-    HS_TRY(ffn_bwd(Ts, lo, br, la.x1, la.h, ws.da));
-    HS_TRY(ln_bwd(Ts, ws.da, la.y1, la.st1, lo.ln1_g, lo.ln1_b, lo.o_b, site_enc(i, 0), &br));
+    HS_TRY(ln_bwd(Ts, dcur, la.y2, la.st2, lo.ln2_g, lo.ln2_b, lo.ffn2_b, site_enc(i, 1), lg.s2, lg.m2, &br));
+    HS_TRY(ffn_bwd(Ts, lo, lg, br, la.x1, la.h, ws.da));
+    HS_TRY(ln_bwd(Ts, ws.da, la.y1, la.st1, lo.ln1_g, lo.ln1_b, lo.o_b, site_enc(i, 0), lg.s1, lg.m1, &br));
+    HS_TRY(hand_over());
     HS_TRY(wgrad(H, H, Ts, br, H, la.ctx, H, g + lo.o_w));
     HS_TRY(dgrad(Ts, H, H, br, W(dt, w, lo.o_w), ws.dctx, nullptr));
-    HS_TRY(launch_attention_bwd(ctx, dt, la.qkv, la.ctx, la.lse, ws.dctx, src_lens, B, Ls, A, ws.dqkv, ws.dvec, s));
-    HS_TRY(launch_colsum(ctx, dt, ws.dqkv, 3 * H, Ts, 3 * H, g + lo.qkv_b, beta, ws.cs_part, s));
-    HS_TRY(wgrad(3 * H, H, Ts, ws.dqkv, 3 * H, x_in, H, g + lo.qkv_w));
-    HS_TRY(dgrad(Ts, H, 3 * H, ws.dqkv, W(dt, w, lo.qkv_w), ws.db, ws.dsum));
+    HS_TRY(launch_attention_bwd(ctx, dt, la.qkv, la.ctx, la.lse, ws.dctx, src_lens, B, Ls, A, lg.dqkv, ws.dvec, s));
+    HS_TRY(hand_over());
+    HS_TRY(bias_grad(lg.dqkv, Ts, 3 * H, g + lo.qkv_b));
+    HS_TRY(wgrad(3 * H, H, Ts, lg.dqkv, 3 * H, x_in, H, g + lo.qkv_w));
+    HS_TRY(dgrad(Ts, H, 3 * H, lg.dqkv, W(dt, w, lo.qkv_w), ws.db, lg.s1));
     dcur = ws.db;
   }
   HS_TRY(launch_mask_scale(ctx, dt, dcur, ws.da, (size_t)Ts * H, scale, drop, site_src(), s));
-  return launch_embed_bwd(ctx, dt, ws.da, src, B, Ls, H, c.vocab, 0, g + o.emb, nullptr, 0.f, ws.emb, s);
+  HS_TRY(launch_embed_bwd(ctx, dt, ws.da, src, B, Ls, H, c.vocab, 0, g + o.emb, nullptr, 0.f, ws.emb, s));
+  if (overlap) {     // everything the second stream did is ordered before whatever the caller enqueues next
+    hipEvent_t e = ctx->events[n_events - 1];
+    HS_HIP_CHECK(ctx, hipEventRecord(e, sd));
+    HS_HIP_CHECK(ctx, hipStreamWaitEvent(s, e, 0));
+  }
+  return HS_OK;
 }
 
 hs_status hs_op_attention_general_fwd(int32_t dtype, const void* q, int64_t ldq, const void* k, const void* v, int64_t ldkv,

@@ -28,25 +28,34 @@ template <> struct V4<bf16> {
   }
 };
 
-// x[b, l, c] = drop(scale * E[ids[b, l], c] + PE[l, c]);  PE[l, 2i] = sin(l / 10000^(2i/H)), PE[l, 2i+1] = cos(same),
-// evaluated in double once per (l, c) and reused for the 16 sequences of the block.
-constexpr int EMB_SEQ = 16;
+// PE[l, 2i] = sin(l / 10000^(2i/H)), PE[l, 2i+1] = cos(same), evaluated in double
+__global__ __launch_bounds__(256) void position_table_kernel(float* __restrict__ pe, int L, int H) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= L * H) return;
+  const int l = i / H, c = i - l * H;
+  const double angle = (double)l * exp(-(double)(2 * (c >> 1)) / (double)H * 9.210340371976184 /* ln 10000 */);
+  pe[i] = (float)((c & 1) ? cos(angle) : sin(angle));
+}
+
+// x[b, l, c] = drop(scale * E[ids[b, l], c] + PE[l, c]); one block per token, four columns per thread
 template <class T>
-__global__ __launch_bounds__(256) void embed_scale_pos_kernel(const T* __restrict__ emb, const int32_t* __restrict__ ids, T* __restrict__ x,
-                                                              int B, int L, int H, int V, float scale, DropCfg drop, uint32_t site) {
-  const int l = blockIdx.x, b0 = blockIdx.y * EMB_SEQ;
-  const int b1 = min(B, b0 + EMB_SEQ);
-  for (int c = threadIdx.x; c < H; c += 256) {
-    const double angle = (double)l * exp(-(double)(2 * (c >> 1)) / (double)H * 9.210340371976184 /* ln 10000 */);
-    const float pe = (float)((c & 1) ? cos(angle) : sin(angle));
-    for (int b = b0; b < b1; ++b) {
-      const int64_t row = (int64_t)b * L + l;
-      int id = ids[row];
-      id = id < 0 ? 0 : (id >= V ? V - 1 : id);
-      float v = fmaf(scale, to_f(emb[(int64_t)id * H + c]), pe);
-      if (drop.thr) v *= drop_factor1(drop, site, (uint64_t)row * H + c);
-      x[row * H + c] = from_f<T>(v);
+__global__ __launch_bounds__(128) void embed_scale_pos_kernel(const T* __restrict__ emb, const int32_t* __restrict__ ids,
+                                                              const float* __restrict__ pe, T* __restrict__ x, int L, int H, int V, float scale,
+                                                              DropCfg drop, uint32_t site) {
+  const int64_t row = blockIdx.x;
+  const int l = (int)(row % L);
+  int id = ids[row];
+  id = id < 0 ? 0 : (id >= V ? V - 1 : id);
+  for (int c = 4 * threadIdx.x; c < H; c += 512) {
+    const float4 e = V4<T>::ld(emb + (int64_t)id * H + c);
+    const float4 p = *(const float4*)(pe + (int64_t)l * H + c);
+    float4 v = make_float4(fmaf(scale, e.x, p.x), fmaf(scale, e.y, p.y), fmaf(scale, e.z, p.z), fmaf(scale, e.w, p.w));
+    if (drop.thr) {
+      float f[4];
+      drop_factors4(drop, site, ((uint64_t)row * H + c) >> 2, f);
+      v.x *= f[0]; v.y *= f[1]; v.z *= f[2]; v.w *= f[3];
     }
+    V4<T>::st(x + row * H + c, v);
   }
 }
 
@@ -134,6 +143,80 @@ __global__ __launch_bounds__(256) void smoothed_ce_kernel(const float* __restric
   }
 }
 
+// The same with the whole row held in registers (one read of the logits): 1024 threads, up to ten 4-element chunks per
+// thread, so rows of up to 40960 padded columns; row stride a multiple of 4, 16-byte aligned rows.
+constexpr int SCE_NT = 1024, SCE_MAXCH = 10;
+__device__ __forceinline__ float block_reduce1024(float v, bool is_max, float* sh) {
+  v = is_max ? wave_max(v) : wave_sum(v);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  __syncthreads();
+  if (lane == 0) sh[wave] = v;
+  __syncthreads();
+  float r = sh[0];
+  for (int w = 1; w < SCE_NT / 64; ++w) r = is_max ? fmaxf(r, sh[w]) : r + sh[w];
+  return r;
+}
+template <class T>
+__global__ __launch_bounds__(SCE_NT) void smoothed_ce_row_kernel(const float* __restrict__ logits, int64_t ldl, const int32_t* __restrict__ labels,
+                                                                const int32_t* __restrict__ lens, int L, int V, float eps,
+                                                                T* __restrict__ dlogits, float* __restrict__ row_loss, float* __restrict__ row_nll) {
+  __shared__ float sh[SCE_NT / 64];
+  const int m = blockIdx.x;
+  const int b = m / L, l = m - b * L;
+  const int nch = (int)(ldl / 4);
+  T* d = dlogits + (int64_t)m * ldl;
+  if (l >= lens[b]) {       // block-uniform
+    for (int ch = threadIdx.x; ch < nch; ch += SCE_NT) V4<T>::st(d + 4 * ch, make_float4(0.f, 0.f, 0.f, 0.f));
+    if (threadIdx.x == 0) { row_loss[m] = 0.f; row_nll[m] = 0.f; }
+    return;
+  }
+  const float* z = logits + (int64_t)m * ldl;
+  float4 x[SCE_MAXCH];
+  float mx = -3.0e38f, sz = 0.f;
+#pragma unroll
+  for (int c = 0; c < SCE_MAXCH; ++c) {
+    const int ch = threadIdx.x + c * SCE_NT, v = ch * 4;
+    x[c] = make_float4(-3.0e38f, -3.0e38f, -3.0e38f, -3.0e38f);
+    if (ch < nch) {
+      if (v + 3 < V) { x[c] = *(const float4*)(z + v); sz += (x[c].x + x[c].y) + (x[c].z + x[c].w); }
+      else {
+        if (v < V) { x[c].x = z[v]; sz += x[c].x; }
+        if (v + 1 < V) { x[c].y = z[v + 1]; sz += x[c].y; }
+        if (v + 2 < V) { x[c].z = z[v + 2]; sz += x[c].z; }
+      }
+    }
+    mx = fmaxf(mx, fmaxf(fmaxf(x[c].x, x[c].y), fmaxf(x[c].z, x[c].w)));
+  }
+  mx = block_reduce1024(mx, true, sh);
+  sz = block_reduce1024(sz, false, sh);
+  float se = 0.f;
+#pragma unroll
+  for (int c = 0; c < SCE_MAXCH; ++c)     // excluded positions hold -3e38: their exponential is exactly 0
+    se += (__expf(x[c].x - mx) + __expf(x[c].y - mx)) + (__expf(x[c].z - mx) + __expf(x[c].w - mx));
+  se = block_reduce1024(se, false, sh);
+  const float lse = mx + logf(se);
+  int lab = labels[m];
+  lab = lab < 0 ? 0 : (lab >= V ? V - 1 : lab);
+  if (threadIdx.x == 0) {
+    const float nll = lse - z[lab];
+    row_nll[m] = nll;
+    row_loss[m] = (1.0f - eps) * nll + eps * (lse - sz / (float)V);
+  }
+  const float u = eps / (float)V, on = 1.0f - eps;
+#pragma unroll
+  for (int c = 0; c < SCE_MAXCH; ++c) {
+    const int ch = threadIdx.x + c * SCE_NT, v = ch * 4;
+    if (ch < nch) {
+      float4 p;      // columns at or beyond V hold -3e38: exp gives exactly 0, and they get 0, not -u
+      p.x = (v < V) ? __expf(x[c].x - lse) - u - (v == lab ? on : 0.0f) : 0.f;
+      p.y = (v + 1 < V) ? __expf(x[c].y - lse) - u - (v + 1 == lab ? on : 0.0f) : 0.f;
+      p.z = (v + 2 < V) ? __expf(x[c].z - lse) - u - (v + 2 == lab ? on : 0.0f) : 0.f;
+      p.w = (v + 3 < V) ? __expf(x[c].w - lse) - u - (v + 3 == lab ? on : 0.0f) : 0.f;
+      V4<T>::st(d + v, p);
+    }
+  }
+}
+
 // fixed-order sums of two vectors of n floats by one block
 __global__ __launch_bounds__(256) void sum_two_kernel(const float* __restrict__ a, const float* __restrict__ b, int n, float* __restrict__ out_a,
                                                       float* __restrict__ out_b) {
@@ -147,14 +230,22 @@ __global__ __launch_bounds__(256) void sum_two_kernel(const float* __restrict__ 
 
 }  // namespace
 
-hs_status launch_embed_scale_pos(hs_ctx* ctx, int dtype, const void* emb, const int32_t* ids, void* x, int B, int L, int H, int V, float scale,
-                                 const DropCfg* drop_in, uint32_t site, hipStream_t s) {
+hs_status launch_position_table(hs_ctx* ctx, float* pe, int L, int H, hipStream_t s) {
+  if (L <= 0) return HS_OK;
+  KScope scope(ctx ? ctx->prof : nullptr, KC_EMBED, 0.0, 4.0 * L * H, s);
+  hipLaunchKernelGGL(position_table_kernel, dim3((L * H + 255) / 256), dim3(256), 0, s, pe, L, H);
+  S2S_LAUNCH_CHECK(ctx, "position_table");
+  return HS_OK;
+}
+
+hs_status launch_embed_scale_pos(hs_ctx* ctx, int dtype, const void* emb, const int32_t* ids, const float* pe, void* x, int B, int L, int H, int V,
+                                 float scale, const DropCfg* drop_in, uint32_t site, hipStream_t s) {
   if (B <= 0 || L <= 0) return HS_OK;
   const DropCfg drop = (drop_in && drop_in->thr) ? *drop_in : DropCfg{0u, 1.0f, 0u, 0u, 0u};
   KScope scope(ctx ? ctx->prof : nullptr, KC_EMBED, 2.0 * B * L * H, 2.0 * B * L * H * esize(dtype), s);
-  dim3 grid(L, (B + EMB_SEQ - 1) / EMB_SEQ);
-  if (dtype == HS_BF16) hipLaunchKernelGGL(embed_scale_pos_kernel<bf16>, grid, dim3(256), 0, s, (const bf16*)emb, ids, (bf16*)x, B, L, H, V, scale, drop, site);
-  else hipLaunchKernelGGL(embed_scale_pos_kernel<float>, grid, dim3(256), 0, s, (const float*)emb, ids, (float*)x, B, L, H, V, scale, drop, site);
+  dim3 grid((unsigned)(B * L));
+  if (dtype == HS_BF16) hipLaunchKernelGGL(embed_scale_pos_kernel<bf16>, grid, dim3(128), 0, s, (const bf16*)emb, ids, pe, (bf16*)x, L, H, V, scale, drop, site);
+  else hipLaunchKernelGGL(embed_scale_pos_kernel<float>, grid, dim3(128), 0, s, (const float*)emb, ids, pe, (float*)x, L, H, V, scale, drop, site);
   S2S_LAUNCH_CHECK(ctx, "embed_scale_pos");
   return HS_OK;
 }
@@ -202,7 +293,11 @@ hs_status launch_smoothed_ce(hs_ctx* ctx, int dtype, const float* logits, int64_
   const int M = B * L;
   if (M <= 0) return HS_OK;
   KScope scope(ctx ? ctx->prof : nullptr, KC_LOSS, 5.0 * M * V, (double)M * V * (8.0 + esize(dtype)), s);
-  if (dtype == HS_BF16) hipLaunchKernelGGL(smoothed_ce_kernel<bf16>, dim3(M), dim3(256), 0, s, logits, ldl, labels, lens, L, V, eps, (bf16*)dlogits, row_loss, row_nll);
+  const bool in_regs = (ldl % 4) == 0 && ldl <= (int64_t)4 * SCE_NT * SCE_MAXCH && ((uintptr_t)logits % 16) == 0 && ((uintptr_t)dlogits % 16) == 0;
+  if (in_regs) {
+    if (dtype == HS_BF16) hipLaunchKernelGGL(smoothed_ce_row_kernel<bf16>, dim3(M), dim3(SCE_NT), 0, s, logits, ldl, labels, lens, L, V, eps, (bf16*)dlogits, row_loss, row_nll);
+    else hipLaunchKernelGGL(smoothed_ce_row_kernel<float>, dim3(M), dim3(SCE_NT), 0, s, logits, ldl, labels, lens, L, V, eps, (float*)dlogits, row_loss, row_nll);
+  } else if (dtype == HS_BF16) hipLaunchKernelGGL(smoothed_ce_kernel<bf16>, dim3(M), dim3(256), 0, s, logits, ldl, labels, lens, L, V, eps, (bf16*)dlogits, row_loss, row_nll);
   else hipLaunchKernelGGL(smoothed_ce_kernel<float>, dim3(M), dim3(256), 0, s, logits, ldl, labels, lens, L, V, eps, (float*)dlogits, row_loss, row_nll);
   S2S_LAUNCH_CHECK(ctx, "smoothed_ce");
   hipLaunchKernelGGL(sum_two_kernel, dim3(1), dim3(256), 0, s, (const float*)row_loss, (const float*)row_nll, M, loss_sum, nll_sum);

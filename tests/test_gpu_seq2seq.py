@@ -203,3 +203,26 @@ def test_bad_arguments_are_refused(hs):
     with pytest.raises(hs.HsError):      # a context of the encoder-only model
         hs.hs_s2s_fwd(enc.ctx, wk.w, d["src"], d["src_lens"], d["tgt_in"], d["tgt_lens"], 1, 8, 8, wk._acts, wk._out)
     enc.close(); wk.close()
+
+
+def test_full_size_translation_batch_matches_oracle_bf16(hs):
+    """The batch and launch configuration that bench.py --workload transformer_base times (Transformer-base, 128 sentence
+    pairs, 4096 positions per side), against the oracle in fp32: both losses, and the gradient tensors of the first and
+    last layer of each stack and of the shared embedding (the oracle takes about half a minute)."""
+    import bench
+    model = synth.S2S_MODELS["transformer_base"]
+    ocfg = S.S2SCfg(**model)
+    theta = synth.init_params(S.param_layout(ocfg), 1240)
+    mb = bench.pair_workload(synth)
+    assert mb["src"].shape == (128, 32) and mb["tgt_in"].shape == (128, 32)
+    from paper_2009_14783_amd.step import PairWorker
+    wk = PairWorker(model, "bf16", theta)
+    loss, nll, g = _gpu_grad(wk, mb)
+    wk.close()
+    ol, on, og, n_seq, n_tok = S.micro_batch_grad(ocfg, theta, mb, 0.1)
+    assert n_seq == 128 and n_tok == mb["n_tgt_tokens"]
+    assert abs(loss - ol) / abs(ol) < 2e-2 and abs(nll - on) / abs(on) < 2e-2
+    gated = rounded_weights_grad(ocfg, theta, mb)
+    keep = [e for e in S.param_layout(ocfg) if e[0] == "emb" or e[0].startswith(("enc0.", "enc5.", "dec0.", "dec5."))]
+    worst = compare_flat(keep, g, og, 2e-2, "grad", gated)
+    print(f"full size: loss {loss:.1f} (oracle {ol:.1f}), {n_tok} target tokens, worst tensor {worst[0]} at {worst[1]:.2f} of its bound")
