@@ -141,7 +141,7 @@ LossWs carve_loss(const hs_s2s_cfg& c, int B, int Lt, void* base) {
 // before it overwrites anything; buffers that only the chain touches are shared by all layers.
 struct LayerGrads { void *s2, *m2, *sc, *mc, *s1, *m1, *dh, *dcq, *dckv, *dqkv; };
 struct BwdWs {
-  void *da, *db, *dctx, *denc[2], *ln_part, *cs_part, *emb, *gemm_ws, *gemm_ws_side;
+  void *da, *db, *dctx, *denc[2], *ln_part, *cs_part, *emb, *gemm_ws_side;
   std::vector<LayerGrads> enc, dec;
   float* dvec;
   size_t gemm_ws_bytes, total;
@@ -168,8 +168,7 @@ BwdWs carve_bwd(const hs_s2s_cfg& c, int B, int Ls, int Lt, void* base) {
   w.cs_part = cv.take(colsum_scratch((int)Tm, (int)std::max(F, 3 * H)));
   w.emb = cv.take(embed_bwd_scratch((int)Tm, (int)H));
   w.gemm_ws_bytes = gemm_scratch_bytes(c);
-  w.gemm_ws = cv.take(w.gemm_ws_bytes);
-  w.gemm_ws_side = cv.take(w.gemm_ws_bytes);
+  w.gemm_ws_side = cv.take(w.gemm_ws_bytes);      // split-K partial sums of the weight-gradient GEMMs (second stream)
   w.total = cv.off;
   return w;
 }

@@ -52,6 +52,35 @@ def test_sizes_and_invalid_configs():
     hs.hs_ctx_destroy(ctx)
 
 
+@pytest.mark.parametrize("model", ["s2s_tiny", "transformer_base"])
+def test_pair_model_layout_matches_oracle_layout(model):
+    from oracle import seq2seq_oracle as S
+    m = synth.S2S_MODELS[model]
+    cfg = hs.make_s2s_cfg(**m)
+    assert hs.hs_s2s_param_layout(cfg) == S.param_layout(S.S2SCfg(**m))
+    assert hs.hs_s2s_param_count(cfg) == S.param_count(S.S2SCfg(**m))
+    for _, off, r, c in hs.hs_s2s_param_layout(cfg):
+        if r > 1:
+            assert off % 8 == 0                            # 16-byte aligned rows in bf16
+
+
+def test_pair_model_sizes_and_invalid_configs():
+    cfg = hs.make_s2s_cfg(**synth.S2S_MODELS["transformer_base"])
+    small, big = hs.hs_s2s_acts_bytes(cfg, 16, 32, 32), hs.hs_s2s_acts_bytes(cfg, 128, 32, 32)
+    assert 0 < small < big and hs.hs_s2s_acts_bytes(cfg, 128, 64, 32) > big
+    assert hs.hs_s2s_workspace_bytes(cfg, 128, 32, 32) >= 128 * 32 * 37056 * 6      # fp32 logits and their bf16 gradient
+    bad = hs.make_s2s_cfg(n_enc=1, n_dec=0, hidden=128, n_heads=2, ffn=256, vocab=100, max_pos=64)
+    assert hs.hs_s2s_param_count(bad) == 0
+    with pytest.raises(hs.HsError) as e:
+        hs.hs_s2s_ctx_create(bad)
+    assert e.value.status == 2 and "n_dec" in str(e.value)
+    bad = hs.make_s2s_cfg(n_enc=1, n_dec=1, hidden=128, n_heads=4, ffn=256, vocab=100, max_pos=64)
+    with pytest.raises(hs.HsError):
+        hs.hs_s2s_ctx_create(bad)                          # hidden / n_heads must be 64
+    ctx = hs.hs_s2s_ctx_create(cfg)
+    hs.hs_ctx_destroy(ctx)
+
+
 @pytest.mark.parametrize("mode", [0, 1])
 def test_batcher_bit_exact_against_oracle(mode):
     rng = synth.rng_for(1236)
