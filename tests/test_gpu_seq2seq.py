@@ -226,3 +226,21 @@ def test_full_size_translation_batch_matches_oracle_bf16(hs):
     keep = [e for e in S.param_layout(ocfg) if e[0] == "emb" or e[0].startswith(("enc0.", "enc5.", "dec0.", "dec5."))]
     worst = compare_flat(keep, g, og, 2e-2, "grad", gated)
     print(f"full size: loss {loss:.1f} (oracle {ol:.1f}), {n_tok} target tokens, worst tensor {worst[0]} at {worst[1]:.2f} of its bound")
+
+
+@pytest.mark.parametrize("dropout", [0.0, 0.1])
+def test_pair_step_is_bit_reproducible(hs, dropout):
+    """Every reduction has a fixed order and the work on the second stream is ordered by events: repeating a pass on the
+    same inputs gives the same bits, also at a size where the two streams really run side by side."""
+    model, ocfg, theta, wk = _setup("s2s_tiny", "bf16", 27, dict(hidden=512, n_heads=8, ffn=2048, vocab=8000, max_pos=64, n_enc=2, n_dec=2))
+    rng = synth.rng_for(28)
+    sl, tl = synth.draw_pair_lengths(rng, 96, 16, 32)
+    mb = synth.make_pair_batch(rng, sl, tl, 32, 32, model["vocab"], "zipf")
+    if dropout:
+        mb["drop"] = dict(p=dropout, seed=3, stream=9)
+    runs = [_gpu_grad(wk, mb) for _ in range(4)]
+    for loss, nll, g in runs[1:]:
+        assert loss == runs[0][0] and nll == runs[0][1]
+        assert np.array_equal(g.view(np.uint32), runs[0][2].view(np.uint32))
+    assert np.all(np.isfinite(runs[0][2]))
+    wk.close()
