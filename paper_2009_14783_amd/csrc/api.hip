@@ -176,8 +176,9 @@ hs_status hs_encoder_fwd(hs_ctx* ctx, const void* w, const int32_t* ids, const i
   // Sequences are independent in the forward pass.  A large batch is run as two halves on two streams (the
   // caller's and the context's second one): one half's launch ramp-ups, epilogues and tails fill with the
   // other half's work.  Every kernel sees a row range of the same buffers, so the results are those of one
-  // pass.  Not with dropout (its element indices count rows of the whole batch) nor with per-launch timing.
-  const bool split = ctx->prof == nullptr && !drop && B >= 2 && T >= 4096;
+  // pass (dropout numbers the elements of the whole batch: each half gets the state with its offset).  Not with
+  // per-launch timing.
+  const bool split = ctx->prof == nullptr && B >= 2 && T >= 4096;
   const int nparts = split ? 2 : 1;
   if (split) HS_TRY(ensure_side_stream(ctx, 2));
   if (split) {
@@ -189,11 +190,17 @@ hs_status hs_encoder_fwd(hs_ctx* ctx, const void* w, const int32_t* ids, const i
   auto rows = [&](const void* p, const Part& pt, size_t width) { return (const void*)((const char*)p + (size_t)pt.b0 * L * width * es); };
   auto rows_w = [&](void* p, const Part& pt, size_t width) { return (void*)((char*)p + (size_t)pt.b0 * L * width * es); };
 
+  // dropout state of a half for tensors of [T, H] elements and for the attention probabilities [B, A, L, L]
+  DropCfg drop_rows[2], drop_prob[2];
+  for (int k = 0; k < 2; ++k) {
+    drop_rows[k] = drop_at(ctx->drop, (uint64_t)part[k].b0 * L * H);
+    drop_prob[k] = drop_at(ctx->drop, (uint64_t)part[k].b0 * c.n_heads * L * L);
+  }
   for (int k = 0; k < nparts; ++k) {
     const Part& pt = part[k];
     HS_TRY(launch_embed_ln_fwd(ctx, dt, W(ctx, w, o.emb_word), W(ctx, w, o.emb_pos), W(ctx, w, o.emb_ln_g), W(ctx, w, o.emb_ln_b),
                                ids + (size_t)pt.b0 * L, rows_w(a.e_pre, pt, H), rows_w(a.x0, pt, H), a.emb_stats + (size_t)pt.b0 * L, pt.nb, L, H,
-                               c.vocab, c.ln_eps, pt.st, &ctx->drop, T));
+                               c.vocab, c.ln_eps, pt.st, &drop_rows[k], T));
   }
   const void* x = a.x0;
   for (int i = 0; i < c.n_layers; ++i) {
@@ -209,11 +216,11 @@ hs_status hs_encoder_fwd(hs_ctx* ctx, const void* w, const int32_t* ids, const i
       g.bias = W(ctx, w, lo.qkv_b);
       HS_TRY(launch_gemm(ctx, g, st));
       HS_TRY(launch_attention_fwd(ctx, dt, rows(la.qkv, pt, 3 * H), lens + pt.b0, pt.nb, L, c.n_heads, rows_w(la.ctx, pt, H),
-                                  la.lse + (size_t)pt.b0 * c.n_heads * L, st, drop, site_attention_prob(i)));
+                                  la.lse + (size_t)pt.b0 * c.n_heads * L, st, drop ? &drop_prob[k] : nullptr, site_attention_prob(i)));
       // y1 = x + ctx Wo^T + bo ; x1 = LN(y1)
       g = gemm_args(dt, 1, 1, Tp, H, H, rows(la.ctx, pt, H), H, W(ctx, w, lo.o_w), H, rows_w(la.y1, pt, H), H);
       g.bias = W(ctx, w, lo.o_b); g.epi = 1; g.aux = rows(x, pt, H); g.ldaux = H;
-      g.drop = drop; g.drop_site = site_attention_out(i);
+      g.drop = drop ? &drop_rows[k] : nullptr; g.drop_site = site_attention_out(i);
       HS_TRY(launch_gemm(ctx, g, st));
       HS_TRY(launch_layernorm_fwd(ctx, dt, rows(la.y1, pt, H), W(ctx, w, lo.ln1_g), W(ctx, w, lo.ln1_b), rows_w(la.x1, pt, H),
                                   la.st1 + (size_t)pt.b0 * L, Tp, H, c.ln_eps, st, T));
@@ -224,7 +231,7 @@ hs_status hs_encoder_fwd(hs_ctx* ctx, const void* w, const int32_t* ids, const i
       // y2 = x1 + h W2^T + b2 ; x2 = LN(y2)
       g = gemm_args(dt, 1, 1, Tp, H, F, rows(la.h, pt, F), F, W(ctx, w, lo.ffn2_w), F, rows_w(la.y2, pt, H), H);
       g.bias = W(ctx, w, lo.ffn2_b); g.epi = 1; g.aux = rows(la.x1, pt, H); g.ldaux = H;
-      g.drop = drop; g.drop_site = site_ffn_out(i);
+      g.drop = drop ? &drop_rows[k] : nullptr; g.drop_site = site_ffn_out(i);
       HS_TRY(launch_gemm(ctx, g, st));
       HS_TRY(launch_layernorm_fwd(ctx, dt, rows(la.y2, pt, H), W(ctx, w, lo.ln2_g), W(ctx, w, lo.ln2_b), rows_w(x2, pt, H),
                                   la.st2 + (size_t)pt.b0 * L, Tp, H, c.ln_eps, st, T));

@@ -65,7 +65,17 @@ struct DropCfg {
   float scale;
   uint32_t k0, k1;
   uint32_t stream;
+  // Offset, in groups of four elements, added to every element index: a kernel that works on a row range of a
+  // tensor (pointers already advanced) still numbers the elements of the whole tensor.
+  uint32_t g0, g1;
 };
+// the same dropout state for a kernel whose pointers start `elems` elements (a multiple of 4) into the tensor
+static inline DropCfg drop_at(const DropCfg& d, uint64_t elems) {
+  DropCfg r = d;
+  const uint64_t g = (((uint64_t)d.g1 << 32) | d.g0) + (elems >> 2);
+  r.g0 = (uint32_t)g; r.g1 = (uint32_t)(g >> 32);
+  return r;
+}
 __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0, uint32_t k1,
                                               uint32_t (&out)[4]) {
 #pragma unroll
@@ -80,6 +90,7 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
 // factors (0 or scale) of the four elements 4*group .. 4*group + 3 of a site
 __device__ __forceinline__ void drop_factors4(const DropCfg& d, uint32_t site, uint64_t group, float (&f)[4]) {
   uint32_t w[4];
+  group += ((uint64_t)d.g1 << 32) | d.g0;
   philox4x32_10((uint32_t)group, (uint32_t)(group >> 32), site, d.stream, d.k0, d.k1, w);
 #pragma unroll
   for (int t = 0; t < 4; ++t) f[t] = (w[t] >= d.thr) ? d.scale : 0.0f;
@@ -87,7 +98,8 @@ __device__ __forceinline__ void drop_factors4(const DropCfg& d, uint32_t site, u
 // factor of the single element e
 __device__ __forceinline__ float drop_factor1(const DropCfg& d, uint32_t site, uint64_t e) {
   uint32_t w[4];
-  philox4x32_10((uint32_t)(e >> 2), (uint32_t)(e >> 34), site, d.stream, d.k0, d.k1, w);
+  const uint64_t group = (e >> 2) + (((uint64_t)d.g1 << 32) | d.g0);
+  philox4x32_10((uint32_t)group, (uint32_t)(group >> 32), site, d.stream, d.k0, d.k1, w);
   const uint32_t x = (e & 3) == 0 ? w[0] : ((e & 3) == 1 ? w[1] : ((e & 3) == 2 ? w[2] : w[3]));
   return (x >= d.thr) ? d.scale : 0.0f;
 }

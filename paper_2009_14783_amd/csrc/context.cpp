@@ -352,5 +352,6 @@ extern "C" hs_status hs_set_dropout(hs_ctx* ctx, double p, uint64_t seed, uint32
   ctx->drop.k0 = (uint32_t)(seed & 0xffffffffull);
   ctx->drop.k1 = (uint32_t)(seed >> 32);
   ctx->drop.stream = stream;
+  ctx->drop.g0 = ctx->drop.g1 = 0;
   return HS_OK;
 }

@@ -293,9 +293,9 @@ hs_status hs_s2s_fwd(hs_ctx* ctx, const void* w, const int32_t* src, const int32
 
   // Sentence pairs are independent in the forward pass.  A batch of some size runs as two halves on two streams (the
   // caller's and the context's second one) over row ranges of the same buffers: one half's launch ramp-ups and tails
-  // fill with the other half's work, and the results are those of one pass.  Not with dropout (its element indices
-  // count rows of the whole batch) nor with per-launch timing.
-  const bool split = ctx->prof == nullptr && !drop && B >= 2 && std::min(Ts, Tt) >= 2048;
+  // fill with the other half's work, and the results are those of one pass (dropout numbers the elements of the whole
+  // batch: each half gets the state with its offset).  Not with per-launch timing.
+  const bool split = ctx->prof == nullptr && B >= 2 && std::min(Ts, Tt) >= 2048;
   HS_TRY(launch_position_table(ctx, a.pe, std::max(Ls, Lt), H, s));
   if (split) {
     HS_TRY(ensure_side_stream(ctx, 2));
@@ -305,6 +305,11 @@ hs_status hs_s2s_fwd(hs_ctx* ctx, const void* w, const int32_t* src, const int32
   struct Part { int b0, nb; hipStream_t st; };
   const Part part[2] = {{0, split ? B / 2 : B, s}, {B / 2, B - B / 2, split ? ctx->side : s}};
   const int nparts = split ? 2 : 1;
+  DropCfg drop_src[2], drop_tgt[2];      // dropout state of a half for tensors of [Ts, H] and [Tt, H] elements
+  for (int k = 0; k < 2; ++k) {
+    drop_src[k] = drop_at(ctx->drop, (uint64_t)part[k].b0 * Ls * H);
+    drop_tgt[k] = drop_at(ctx->drop, (uint64_t)part[k].b0 * Lt * H);
+  }
   // rows of sequence b0 onwards in a buffer with L positions per sequence and `width` elements per position
   auto src_rows = [&](const void* p, const Part& pt, int64_t width) { return (const void*)((const char*)p + (int64_t)pt.b0 * Ls * width * es); };
   auto tgt_rows = [&](const void* p, const Part& pt, int64_t width) { return (const void*)((const char*)p + (int64_t)pt.b0 * Lt * width * es); };
@@ -314,7 +319,7 @@ hs_status hs_s2s_fwd(hs_ctx* ctx, const void* w, const int32_t* src, const int32
   for (int k = 0; k < nparts; ++k) {
     const Part& pt = part[k];
     HS_TRY(launch_embed_scale_pos(ctx, dt, W(dt, w, o.emb), src + (size_t)pt.b0 * Ls, a.pe, mut(src_rows(a.x0, pt, H)), pt.nb, Ls, H, c.vocab, scale,
-                                  drop, site_src(), pt.st));
+                                  drop ? &drop_src[k] : nullptr, site_src(), pt.st));
   }
   const void* x = a.x0;
   for (int i = 0; i < c.n_enc; ++i) {
@@ -328,11 +333,11 @@ hs_status hs_s2s_fwd(hs_ctx* ctx, const void* w, const int32_t* src, const int32
       HS_TRY(linear(ctx, dt, T, 3 * H, H, R(x, H), W(dt, w, lo.qkv_w), W(dt, w, lo.qkv_b), mut(R(la.qkv, 3 * H)), st));
       HS_TRY(launch_attention_fwd(ctx, dt, R(la.qkv, 3 * H), src_lens + pt.b0, pt.nb, Ls, A, mut(R(la.ctx, H)), la.lse + (size_t)pt.b0 * A * Ls, st));
       HS_TRY(linear_res_ln(ctx, dt, T, H, H, R(la.ctx, H), W(dt, w, lo.o_w), W(dt, w, lo.o_b), R(x, H), mut(R(la.y1, H)), W(dt, w, lo.ln1_g),
-                           W(dt, w, lo.ln1_b), mut(R(la.x1, H)), la.st1 + (size_t)pt.b0 * Ls, Ts, c.ln_eps, drop, site_enc(i, 0), st));
+                           W(dt, w, lo.ln1_b), mut(R(la.x1, H)), la.st1 + (size_t)pt.b0 * Ls, Ts, c.ln_eps, drop ? &drop_src[k] : nullptr, site_enc(i, 0), st));
       HS_TRY(linear(ctx, dt, T, F, H, R(la.x1, H), W(dt, w, lo.ffn1_w), W(dt, w, lo.ffn1_b), mut(R(la.h, F)), st));
       HS_TRY(launch_relu(ctx, dt, mut(R(la.h, F)), (size_t)T * F, st));
       HS_TRY(linear_res_ln(ctx, dt, T, H, F, R(la.h, F), W(dt, w, lo.ffn2_w), W(dt, w, lo.ffn2_b), R(la.x1, H), mut(R(la.y2, H)), W(dt, w, lo.ln2_g),
-                           W(dt, w, lo.ln2_b), mut(R(la.x2, H)), la.st2 + (size_t)pt.b0 * Ls, Ts, c.ln_eps, drop, site_enc(i, 1), st));
+                           W(dt, w, lo.ln2_b), mut(R(la.x2, H)), la.st2 + (size_t)pt.b0 * Ls, Ts, c.ln_eps, drop ? &drop_src[k] : nullptr, site_enc(i, 1), st));
     }
     x = la.x2;
   }
@@ -342,7 +347,7 @@ hs_status hs_s2s_fwd(hs_ctx* ctx, const void* w, const int32_t* src, const int32
   for (int k = 0; k < nparts; ++k) {
     const Part& pt = part[k];
     HS_TRY(launch_embed_scale_pos(ctx, dt, W(dt, w, o.emb), tgt_in + (size_t)pt.b0 * Lt, a.pe, mut(tgt_rows(a.t0, pt, H)), pt.nb, Lt, H, c.vocab,
-                                  scale, drop, site_tgt(), pt.st));
+                                  scale, drop ? &drop_tgt[k] : nullptr, site_tgt(), pt.st));
   }
   const void* y = a.t0;
   for (int i = 0; i < c.n_dec; ++i) {
@@ -361,19 +366,19 @@ hs_status hs_s2s_fwd(hs_ctx* ctx, const void* w, const int32_t* src, const int32
       AttnOperands self{qkv, at(dt, qkv, H), at(dt, qkv, 2 * H), 3 * (int64_t)H, 3 * (int64_t)H, tl, tl, Lt, Lt, A, 1};
       HS_TRY(launch_attention_general_fwd(ctx, dt, self, pt.nb, mut(R(la.ctx, H)), la.lse + (size_t)pt.b0 * A * Lt, st));
       HS_TRY(linear_res_ln(ctx, dt, T, H, H, R(la.ctx, H), W(dt, w, lo.o_w), W(dt, w, lo.o_b), R(y, H), mut(R(la.y1s, H)), W(dt, w, lo.ln1_g),
-                           W(dt, w, lo.ln1_b), mut(R(la.y1, H)), la.st1 + (size_t)pt.b0 * Lt, Tt, c.ln_eps, drop, site_dec(c, i, 0), st));
+                           W(dt, w, lo.ln1_b), mut(R(la.y1, H)), la.st1 + (size_t)pt.b0 * Lt, Tt, c.ln_eps, drop ? &drop_tgt[k] : nullptr, site_dec(c, i, 0), st));
       HS_TRY(linear(ctx, dt, T, H, H, R(la.y1, H), W(dt, w, lo.cq_w), W(dt, w, lo.cq_b), mut(R(la.cq, H)), st));
       const void* ckv = src_rows(la.ckv, pt, 2 * H);
       HS_TRY(linear(ctx, dt, TS, 2 * H, H, src_rows(enc_out, pt, H), W(dt, w, lo.ckv_w), W(dt, w, lo.ckv_b), mut(ckv), st));
       AttnOperands cross{R(la.cq, H), ckv, at(dt, ckv, H), (int64_t)H, 2 * (int64_t)H, tl, sl, Lt, Ls, A, 0};
       HS_TRY(launch_attention_general_fwd(ctx, dt, cross, pt.nb, mut(R(la.cctx, H)), la.clse + (size_t)pt.b0 * A * Lt, st));
       HS_TRY(linear_res_ln(ctx, dt, T, H, H, R(la.cctx, H), W(dt, w, lo.co_w), W(dt, w, lo.co_b), R(la.y1, H), mut(R(la.ycs, H)),
-                           W(dt, w, lo.lnc_g), W(dt, w, lo.lnc_b), mut(R(la.yc, H)), la.stc + (size_t)pt.b0 * Lt, Tt, c.ln_eps, drop,
+                           W(dt, w, lo.lnc_g), W(dt, w, lo.lnc_b), mut(R(la.yc, H)), la.stc + (size_t)pt.b0 * Lt, Tt, c.ln_eps, drop ? &drop_tgt[k] : nullptr,
                            site_dec(c, i, 1), st));
       HS_TRY(linear(ctx, dt, T, F, H, R(la.yc, H), W(dt, w, lo.ffn1_w), W(dt, w, lo.ffn1_b), mut(R(la.h, F)), st));
       HS_TRY(launch_relu(ctx, dt, mut(R(la.h, F)), (size_t)T * F, st));
       HS_TRY(linear_res_ln(ctx, dt, T, H, F, R(la.h, F), W(dt, w, lo.ffn2_w), W(dt, w, lo.ffn2_b), R(la.yc, H), mut(R(la.y2s, H)),
-                           W(dt, w, lo.ln2_g), W(dt, w, lo.ln2_b), mut(R(y2, H)), la.st2 + (size_t)pt.b0 * Lt, Tt, c.ln_eps, drop,
+                           W(dt, w, lo.ln2_g), W(dt, w, lo.ln2_b), mut(R(y2, H)), la.st2 + (size_t)pt.b0 * Lt, Tt, c.ln_eps, drop ? &drop_tgt[k] : nullptr,
                            site_dec(c, i, 2), st));
     }
     y = y2;

@@ -100,3 +100,10 @@ def test_two_layer_bf16_long_sequences_two_kernel_backward():
 def test_bert_base_width_bf16():
     model = dict(synth.MODELS["bert_base"], n_layers=2)
     run_case(model, "bf16", [128] * 4 + [90, 128, 64, 128], 128, dict(p=0.1, seed=1234, stream=9), 15, 2e-2, ids="zipf")
+
+
+def test_large_batch_runs_as_two_halves_with_the_masks_of_the_whole_batch():
+    """4096 positions: the forward pass runs as two half-batches on two streams, each numbering its dropout elements
+    from its offset in the whole batch; the oracle knows nothing of halves."""
+    lens = [int(x) for x in synth.draw_lengths(synth.rng_for(40), 64, 5, 64)]
+    run_case(synth.MODELS["tiny"], "fp32", lens, 64, dict(p=0.1, seed=77, stream=4), 16, 1e-4)
