@@ -330,7 +330,9 @@ hs_status hs_s2s_loss(hs_ctx* ctx, const void* w, const void* dec_out, const int
                       void* workspace, size_t workspace_bytes, void* stream);
 
 /* Backward through decoder and encoder down to the embedding.  Gradients of enc*. and dec*. go to g (overwritten when
- * accumulate == 0, added when 1); emb is ALWAYS added to (call hs_s2s_loss first). */
+ * accumulate == 0, added when 1); emb is ALWAYS added to (call hs_s2s_loss first).  An update armed with hs_arm_update is
+ * consumed by this call as by hs_encoder_bwd: each layer's slice of the flat buffers is normalised and updated as soon as
+ * its gradient is final, the shared embedding last. */
 hs_status hs_s2s_bwd(hs_ctx* ctx, const void* w, const void* acts, const int32_t* src, const int32_t* src_lens, const int32_t* tgt_in,
                      const int32_t* tgt_lens, int32_t B, int32_t Ls, int32_t Lt, const void* d_dec_out, float* g, int32_t accumulate,
                      void* workspace, size_t workspace_bytes, void* stream);

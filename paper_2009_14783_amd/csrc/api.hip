@@ -328,8 +328,10 @@ hs_status hs_arm_update(hs_ctx* ctx, float* w, float* m, float* v, float* G, voi
   return HS_OK;
 }
 
+}  // extern "C"
+
 // normalise + Adam on the parameters [begin, end) of an armed update
-static hs_status update_slice(hs_ctx* ctx, const hs_ctx::Armed& u, int64_t begin, int64_t end, hipStream_t s) {
+hs_status update_slice(hs_ctx* ctx, const hs_ctx::Armed& u, int64_t begin, int64_t end, hipStream_t s) {
   const size_t n = (size_t)(end - begin);
   if (n == 0) return HS_OK;
   hs_status st = hs_grad_accum_normalize(u.G + begin, nullptr, n, 0, u.denom, s);
@@ -339,6 +341,8 @@ static hs_status update_slice(hs_ctx* ctx, const hs_ctx::Armed& u, int64_t begin
   if (st != HS_OK) return hs_fail(ctx, st, hs_last_error(nullptr));
   return HS_OK;
 }
+
+extern "C" {
 
 static hs_status encoder_bwd_impl(hs_ctx* ctx, const hs_ctx::Armed& upd, const void* w, const void* acts, const int32_t* ids,
                                   const int32_t* lens, int32_t B, int32_t L, const void* d_hidden, float* g, int32_t accumulate,

@@ -172,6 +172,8 @@ struct hs_ctx {
 };
 
 hs_status hs_fail(hs_ctx* ctx, hs_status st, const std::string& msg);  // records msg, returns st
+// normalise + Adam on the parameters [begin, end) of an armed update (api.hip)
+hs_status update_slice(hs_ctx* ctx, const hs_ctx::Armed& u, int64_t begin, int64_t end, hipStream_t s);
 #define HS_HIP_CHECK(ctx, expr)                                                              \
   do {                                                                                       \
     hipError_t e_ = (expr);                                                                  \

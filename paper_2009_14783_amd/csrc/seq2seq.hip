@@ -429,11 +429,17 @@ hs_status hs_s2s_bwd(hs_ctx* ctx, const void* w, const void* acts, const int32_t
                      const int32_t* tgt_lens, int32_t B, int32_t Ls, int32_t Lt, const void* d_dec_out, float* g, int32_t accumulate,
                      void* workspace, size_t workspace_bytes, void* stream) {
   if (!ctx) return HS_ERR_INVALID_ARG;
+  const hs_ctx::Armed upd = ctx->armed;       // an update armed with hs_arm_update is consumed by this call, whatever its outcome
+  ctx->armed.on = false;
   if (!ctx->is_s2s) return hs_fail(ctx, HS_ERR_STATE, "hs_s2s_bwd: the context was not made by hs_s2s_ctx_create");
+  if (upd.on && upd.G != g) return hs_fail(ctx, HS_ERR_STATE, "hs_s2s_bwd: an update is armed for another gradient buffer");
   const hs_s2s_cfg& c = ctx->s2s;
   std::string why;
   if (!shape_ok(c, B, Ls, Lt, &why)) return hs_fail(ctx, HS_ERR_SHAPE, "hs_s2s_bwd: " + why);
-  if (B == 0) return HS_OK;
+  if (B == 0) {      // nothing to back-propagate: an armed update still takes place, on the caller's stream
+    if (upd.on) return update_slice(ctx, upd, 0, s2s_offsets(c).total, (hipStream_t)stream);
+    return HS_OK;
+  }
   if (!w || !acts || !src || !src_lens || !tgt_in || !tgt_lens || !d_dec_out || !g || !workspace)
     return hs_fail(ctx, HS_ERR_INVALID_ARG, "hs_s2s_bwd: NULL buffer");
   if (workspace_bytes < carve_bwd(c, B, Ls, Lt, nullptr).total) return hs_fail(ctx, HS_ERR_WORKSPACE, "hs_s2s_bwd: workspace too small");
@@ -450,10 +456,25 @@ hs_status hs_s2s_bwd(hs_ctx* ctx, const void* w, const void* acts, const int32_t
   // the context's second stream, each after the event that marks its operand ready, and the caller's stream waits for
   // them once, at the end.  With per-launch timing enabled everything stays on the caller's stream.
   const bool overlap = ctx->prof == nullptr;
-  const size_t n_events = (size_t)6 * c.n_dec + 4 * c.n_enc + 1;
+  const size_t n_events = (size_t)6 * c.n_dec + 4 * c.n_enc + 1 + (upd.on ? (size_t)2 * (c.n_dec + c.n_enc) + 2 : 0);
   if (overlap) HS_TRY(ensure_side_stream(ctx, n_events));
   hipStream_t sd = overlap ? ctx->side : s;
   size_t next_event = 0;
+  // An armed optimizer update runs on a third stream: the slice of a layer is normalised and updated as soon as both
+  // streams have finished that layer (its gradient is final and its weights are no longer read), the shared embedding last.
+  if (overlap && upd.on && !ctx->upd) HS_HIP_CHECK(ctx, hipStreamCreateWithFlags(&ctx->upd, hipStreamNonBlocking));
+  hipStream_t su = (overlap && upd.on) ? ctx->upd : s;
+  auto update_after_both = [&](int64_t begin, int64_t end) -> hs_status {
+    if (!upd.on) return HS_OK;
+    if (overlap) {
+      hipEvent_t e1 = ctx->events[next_event++], e2 = ctx->events[next_event++];
+      HS_HIP_CHECK(ctx, hipEventRecord(e1, sd));
+      HS_HIP_CHECK(ctx, hipStreamWaitEvent(su, e1, 0));
+      HS_HIP_CHECK(ctx, hipEventRecord(e2, s));
+      HS_HIP_CHECK(ctx, hipStreamWaitEvent(su, e2, 0));
+    }
+    return update_slice(ctx, upd, begin, end, su);
+  };
   auto hand_over = [&]() -> hs_status {       // what the caller's stream has produced so far may now be read on the second one
     if (!overlap) return HS_OK;
     hipEvent_t e = ctx->events[next_event++];
@@ -541,6 +562,7 @@ hs_status hs_s2s_bwd(hs_ctx* ctx, const void* w, const void* acts, const int32_t
     HS_TRY(wgrad(3 * H, H, Tt, lg.dqkv, 3 * H, y_in, H, g + lo.qkv_w));
     HS_TRY(dgrad(Tt, H, 3 * H, lg.dqkv, W(dt, w, lo.qkv_w), ws.da, lg.s1));
     dcur = ws.da;
+    HS_TRY(update_after_both(lo.qkv_w, i + 1 < c.n_dec ? o.dec[i + 1].qkv_w : o.total));
   }
   // target embedding: d E[id] += sqrt(H) * (gradient through the embedding dropout)
   HS_TRY(launch_mask_scale(ctx, dt, dcur, ws.db, (size_t)Tt * H, scale, drop, site_tgt(), s));
@@ -566,9 +588,23 @@ hs_status hs_s2s_bwd(hs_ctx* ctx, const void* w, const void* acts, const int32_t
     HS_TRY(wgrad(3 * H, H, Ts, lg.dqkv, 3 * H, x_in, H, g + lo.qkv_w));
     HS_TRY(dgrad(Ts, H, 3 * H, lg.dqkv, W(dt, w, lo.qkv_w), ws.db, lg.s1));
     dcur = ws.db;
+    HS_TRY(update_after_both(lo.qkv_w, i + 1 < c.n_enc ? o.enc[i + 1].qkv_w : o.dec[0].qkv_w));
   }
   HS_TRY(launch_mask_scale(ctx, dt, dcur, ws.da, (size_t)Ts * H, scale, drop, site_src(), s));
   HS_TRY(launch_embed_bwd(ctx, dt, ws.da, src, B, Ls, H, c.vocab, 0, g + o.emb, nullptr, 0.f, ws.emb, s));
+  if (upd.on) {      // the shared embedding: its gradient is complete only now
+    if (overlap) {
+      hipEvent_t e = ctx->events[next_event++];
+      HS_HIP_CHECK(ctx, hipEventRecord(e, s));
+      HS_HIP_CHECK(ctx, hipStreamWaitEvent(su, e, 0));
+    }
+    HS_TRY(update_slice(ctx, upd, o.emb, o.enc[0].qkv_w, su));
+    if (overlap) {
+      hipEvent_t e = ctx->events[next_event++];
+      HS_HIP_CHECK(ctx, hipEventRecord(e, su));
+      HS_HIP_CHECK(ctx, hipStreamWaitEvent(s, e, 0));
+    }
+  }
   if (overlap) {     // everything the second stream did is ordered before whatever the caller enqueues next
     hipEvent_t e = ctx->events[n_events - 1];
     HS_HIP_CHECK(ctx, hipEventRecord(e, sd));

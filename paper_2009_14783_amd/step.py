@@ -275,26 +275,33 @@ class PairWorker:
         hs.hs_s2s_bwd(self.ctx, w, self._acts, d["src"], d["src_lens"], d["tgt_in"], d["tgt_lens"], B, Ls, Lt, self._dout, g, accumulate,
                       self._ws, self._ws_bytes)
 
-    def train_step(self, batches: list, adam: dict, denom=None):
+    def train_step(self, batches: list, adam: dict, denom=None, update_in_backward: bool = False):
         """One optimizer step over the uploaded micro-batches (None = a pass without data).  Returns the weight D used
-        (the number of real target tokens by default)."""
+        (the number of real target tokens by default).  update_in_backward: normalisation and Adam are armed for the last
+        micro-batch's backward pass, which applies them layer by layer as soon as a layer's gradient is final (same
+        arithmetic, same bits as the two separate calls).  Off by default: at this model's sizes the update's memory
+        traffic beside the small GEMMs of the backward pass costs more than it hides (6.58 against 6.49 ms per step)."""
         assert len(batches) <= 64
         self.loss_buf.zero_()
-        n_tok, first = 0, True
+        real = [i for i, d in enumerate(batches) if d is not None]
+        D = float(denom if denom is not None else max(sum(batches[i]["n_tok"] for i in real), 1))
+        self.t += 1
+        first = True
         for i, d in enumerate(batches):
             if d is None:
                 hs.hs_grad_accum_normalize(self.G, None, self.P, 1, 0.0)
                 continue
+            if update_in_backward and i == real[-1]:
+                hs.hs_arm_update(self.ctx, self.w, self.m, self.v, self.G, self.w_lowp, D, adam["lr"], adam["beta1"], adam["beta2"],
+                                 adam["eps"], adam.get("weight_decay", 0.0), self.t)
             self.forward_backward(d, self.G, 0 if first else 1, i)
             first = False
-            n_tok += d["n_tok"]
         if first:
             self.G.zero_()
-        D = float(denom if denom is not None else max(n_tok, 1))
-        self.t += 1
-        hs.hs_grad_accum_normalize(self.G, None, self.P, 0, D)
-        hs.hs_adam_step(self.w, self.m, self.v, self.G, self.w_lowp, self.P, adam["lr"], adam["beta1"], adam["beta2"], adam["eps"],
-                        adam.get("weight_decay", 0.0), self.t)
+        if first or not update_in_backward:
+            hs.hs_grad_accum_normalize(self.G, None, self.P, 0, D)
+            hs.hs_adam_step(self.w, self.m, self.v, self.G, self.w_lowp, self.P, adam["lr"], adam["beta1"], adam["beta2"], adam["eps"],
+                            adam.get("weight_decay", 0.0), self.t)
         return D
 
     def reported_loss(self, D):

@@ -296,3 +296,26 @@ def test_large_pair_batch_runs_as_two_halves_with_the_masks_of_the_whole_batch(h
     print(f"halves with dropout: {sum(int(u.sum()) for u in und.values())} undecided ReLU units left out; "
           f"worst tensor {worst[0]} at {worst[1]:.2f} of its bound")
     wk.close()
+
+
+@pytest.mark.parametrize("compute", ["fp32", "bf16"])
+def test_update_inside_backward_gives_the_bits_of_the_separate_calls(hs, compute):
+    """Two workers from the same state take three updates over unequal micro-batches: one with normalisation and Adam armed
+    for the last backward pass (layer slices on the third stream), one with the two separate calls afterwards."""
+    model, ocfg, theta, a = _setup("s2s_tiny", compute, 33, dict(hidden=256, n_heads=4, ffn=512, vocab=3000))
+    from paper_2009_14783_amd.step import PairWorker
+    b = PairWorker(model, compute, theta)
+    for t in range(3):
+        rng = synth.rng_for(200 + t)
+        sl, tl = synth.draw_pair_lengths(rng, 72, 4, 32)
+        mbs = [synth.make_pair_batch(rng, sl[:48], tl[:48], 32, 32, model["vocab"], "zipf"),
+               synth.make_pair_batch(rng, sl[48:], tl[48:], 32, 32, model["vocab"], "zipf")]
+        Da = a.train_step([a.upload(m) for m in mbs] + [None], ADAM, update_in_backward=True)
+        Db = b.train_step([b.upload(m) for m in mbs] + [None], ADAM, update_in_backward=False)
+        torch.cuda.synchronize()
+        assert Da == Db
+        for x, y in ((a.w, b.w), (a.m, b.m), (a.v, b.v), (a.G, b.G), (a.loss_buf, b.loss_buf)):
+            assert torch.equal(x, y)
+        if compute == "bf16":
+            assert torch.equal(a.w_lowp, b.w_lowp)
+    a.close(); b.close()
