@@ -63,12 +63,27 @@ __device__ __forceinline__ void drop_tile_keys(const DropCfg& d, uint32_t site, 
     f[4 * a] = t[0]; f[4 * a + 1] = t[1]; f[4 * a + 2] = t[2]; f[4 * a + 3] = t[3];
   }
 }
-// ... and of a tile whose STREAMED index is the query (the lane owns one key): one element per block.
-// head_base = (b*A + h) * L; element = (head_base + query) * L + key.
+// ... and of a tile whose STREAMED index is the query (the lane owns one key).  head_base = (b*A + h) * L; element =
+// (head_base + query) * L + key.  The four lanes of a quad own the four keys of one aligned group (key % 4 == lane % 4),
+// i.e. the four words of ONE generator block per query: for each group of four result registers (four consecutive
+// queries) lane i of the quad evaluates the block of query i and the quad exchanges the keep bits, so a lane runs
+// the generator 4 times per tile instead of 16.
+template <int I>
+__device__ __forceinline__ int quad_broadcast(int x) { return __builtin_amdgcn_mov_dpp(x, I * 0x55, 0xF, 0xF, true); }
 __device__ __forceinline__ void drop_tile_queries(const DropCfg& d, uint32_t site, uint64_t head_base, int L, int query0, int key, int lane,
                                                   f32x16& f) {
+  const int word = lane & 3;
 #pragma unroll
-  for (int r = 0; r < 16; ++r) f[r] = drop_factor1(d, site, (head_base + (uint64_t)(query0 + tile_row(r, lane))) * (uint64_t)L + (uint64_t)key);
+  for (int a = 0; a < 4; ++a) {
+    const int query = query0 + 8 * a + 4 * (lane >> 5) + word;        // = query0 + tile_row(4a + word, lane)
+    const uint64_t e = (head_base + (uint64_t)query) * (uint64_t)L + (uint64_t)(key & ~3);
+    const int mine = drop_keep4(d, site, e >> 2);
+    const int k0 = quad_broadcast<0>(mine), k1 = quad_broadcast<1>(mine), k2 = quad_broadcast<2>(mine), k3 = quad_broadcast<3>(mine);
+    f[4 * a + 0] = ((k0 >> word) & 1) ? d.scale : 0.0f;
+    f[4 * a + 1] = ((k1 >> word) & 1) ? d.scale : 0.0f;
+    f[4 * a + 2] = ((k2 >> word) & 1) ? d.scale : 0.0f;
+    f[4 * a + 3] = ((k3 >> word) & 1) ? d.scale : 0.0f;
+  }
 }
 
 __device__ __forceinline__ bf16x8 pack8(const f32x16& v, int step) {

@@ -95,6 +95,13 @@ __device__ __forceinline__ void drop_factors4(const DropCfg& d, uint32_t site, u
 #pragma unroll
   for (int t = 0; t < 4; ++t) f[t] = (w[t] >= d.thr) ? d.scale : 0.0f;
 }
+// keep bits of the four elements 4*group .. 4*group + 3 of a site (bit t set: element 4*group + t survives)
+__device__ __forceinline__ int drop_keep4(const DropCfg& d, uint32_t site, uint64_t group) {
+  uint32_t w[4];
+  group += ((uint64_t)d.g1 << 32) | d.g0;
+  philox4x32_10((uint32_t)group, (uint32_t)(group >> 32), site, d.stream, d.k0, d.k1, w);
+  return (w[0] >= d.thr ? 1 : 0) | (w[1] >= d.thr ? 2 : 0) | (w[2] >= d.thr ? 4 : 0) | (w[3] >= d.thr ? 8 : 0);
+}
 // factor of the single element e
 __device__ __forceinline__ float drop_factor1(const DropCfg& d, uint32_t site, uint64_t e) {
   uint32_t w[4];
