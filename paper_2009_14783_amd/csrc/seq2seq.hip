@@ -141,7 +141,7 @@ LossWs carve_loss(const hs_s2s_cfg& c, int B, int Lt, void* base) {
 // before it overwrites anything; buffers that only the chain touches are shared by all layers.
 struct LayerGrads { void *s2, *m2, *sc, *mc, *s1, *m1, *dh, *dcq, *dckv, *dqkv; };
 struct BwdWs {
-  void *da, *db, *dctx, *denc[2], *ln_part, *cs_part, *emb, *gemm_ws_side;
+  void *da, *db, *dctx, *denc[2], *de_tgt, *de_src, *ln_part, *cs_part, *emb, *gemm_ws_side;
   std::vector<LayerGrads> enc, dec;
   float* dvec;
   size_t gemm_ws_bytes, total;
@@ -152,6 +152,7 @@ BwdWs carve_bwd(const hs_s2s_cfg& c, int B, int Ls, int Lt, void* base) {
   BwdWs w;
   w.da = cv.take(Tm * H * es); w.db = cv.take(Tm * H * es); w.dctx = cv.take(Tm * H * es);
   w.denc[0] = cv.take(Ts * H * es); w.denc[1] = cv.take(Ts * H * es);
+  w.de_tgt = cv.take(Tt * H * es); w.de_src = cv.take(Ts * H * es);      // scaled, masked embedding gradients (read on the second stream)
   w.enc.resize(c.n_enc); w.dec.resize(c.n_dec);
   for (auto& l : w.enc) {
     l = LayerGrads{};
@@ -456,7 +457,7 @@ hs_status hs_s2s_bwd(hs_ctx* ctx, const void* w, const void* acts, const int32_t
   // the context's second stream, each after the event that marks its operand ready, and the caller's stream waits for
   // them once, at the end.  With per-launch timing enabled everything stays on the caller's stream.
   const bool overlap = ctx->prof == nullptr;
-  const size_t n_events = (size_t)6 * c.n_dec + 4 * c.n_enc + 1 + (upd.on ? (size_t)2 * (c.n_dec + c.n_enc) + 2 : 0);
+  const size_t n_events = (size_t)6 * c.n_dec + 4 * c.n_enc + 2 + 1 + (upd.on ? (size_t)2 * (c.n_dec + c.n_enc) + 2 : 0);
   if (overlap) HS_TRY(ensure_side_stream(ctx, n_events));
   hipStream_t sd = overlap ? ctx->side : s;
   size_t next_event = 0;
@@ -564,9 +565,11 @@ hs_status hs_s2s_bwd(hs_ctx* ctx, const void* w, const void* acts, const int32_t
     dcur = ws.da;
     HS_TRY(update_after_both(lo.qkv_w, i + 1 < c.n_dec ? o.dec[i + 1].qkv_w : o.total));
   }
-  // target embedding: d E[id] += sqrt(H) * (gradient through the embedding dropout)
-  HS_TRY(launch_mask_scale(ctx, dt, dcur, ws.db, (size_t)Tt * H, scale, drop, site_tgt(), s));
-  HS_TRY(launch_embed_bwd(ctx, dt, ws.db, tgt_in, B, Lt, H, c.vocab, 0, g + o.emb, nullptr, 0.f, ws.emb, s));
+  // target embedding: d E[id] += sqrt(H) * (gradient through the embedding dropout).  The scatter (sort of the ids, segment
+  // sums) runs on the second stream like the weight gradients; both embedding scatters add into the same slice, in this order.
+  HS_TRY(launch_mask_scale(ctx, dt, dcur, ws.de_tgt, (size_t)Tt * H, scale, drop, site_tgt(), s));
+  HS_TRY(hand_over());
+  HS_TRY(launch_embed_bwd(ctx, dt, ws.de_tgt, tgt_in, B, Lt, H, c.vocab, 0, g + o.emb, nullptr, 0.f, ws.emb, sd));
 
   // ---- encoder ----
   dcur = ws.denc[pe];
@@ -590,12 +593,13 @@ hs_status hs_s2s_bwd(hs_ctx* ctx, const void* w, const void* acts, const int32_t
     dcur = ws.db;
     HS_TRY(update_after_both(lo.qkv_w, i + 1 < c.n_enc ? o.enc[i + 1].qkv_w : o.dec[0].qkv_w));
   }
-  HS_TRY(launch_mask_scale(ctx, dt, dcur, ws.da, (size_t)Ts * H, scale, drop, site_src(), s));
-  HS_TRY(launch_embed_bwd(ctx, dt, ws.da, src, B, Ls, H, c.vocab, 0, g + o.emb, nullptr, 0.f, ws.emb, s));
+  HS_TRY(launch_mask_scale(ctx, dt, dcur, ws.de_src, (size_t)Ts * H, scale, drop, site_src(), s));
+  HS_TRY(hand_over());
+  HS_TRY(launch_embed_bwd(ctx, dt, ws.de_src, src, B, Ls, H, c.vocab, 0, g + o.emb, nullptr, 0.f, ws.emb, sd));
   if (upd.on) {      // the shared embedding: its gradient is complete only now
     if (overlap) {
       hipEvent_t e = ctx->events[next_event++];
-      HS_HIP_CHECK(ctx, hipEventRecord(e, s));
+      HS_HIP_CHECK(ctx, hipEventRecord(e, sd));
       HS_HIP_CHECK(ctx, hipStreamWaitEvent(su, e, 0));
     }
     HS_TRY(update_slice(ctx, upd, o.emb, o.enc[0].qkv_w, su));
