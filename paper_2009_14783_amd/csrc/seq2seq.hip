@@ -139,9 +139,9 @@ LossWs carve_loss(const hs_s2s_cfg& c, int B, int Lt, void* base) {
 // Backward workspace.  The buffers that the weight-gradient GEMMs and bias column sums read (they run on a second stream
 // beside the chain of activation gradients) exist once per layer and sub-layer, so that the chain never has to wait
 // before it overwrites anything; buffers that only the chain touches are shared by all layers.
-struct LayerGrads { void *s2, *m2, *sc, *mc, *s1, *m1, *dh, *dcq, *dckv, *dqkv; };
+struct LayerGrads { void *s2, *m2, *sc, *mc, *s1, *m1, *dh, *dcq, *dckv, *dqkv, *p2, *pc, *p1; };   // p*: LayerNorm column partials
 struct BwdWs {
-  void *da, *db, *dctx, *denc[2], *de_tgt, *de_src, *ln_part, *cs_part, *emb, *gemm_ws_side;
+  void *da, *db, *dctx, *denc[2], *de_tgt, *de_src, *cs_part, *emb, *gemm_ws_side;
   std::vector<LayerGrads> enc, dec;
   float* dvec;
   size_t gemm_ws_bytes, total;
@@ -158,14 +158,16 @@ BwdWs carve_bwd(const hs_s2s_cfg& c, int B, int Ls, int Lt, void* base) {
     l = LayerGrads{};
     l.s2 = cv.take(Ts * H * es); l.m2 = cv.take(Ts * H * es); l.s1 = cv.take(Ts * H * es); l.m1 = cv.take(Ts * H * es);
     l.dh = cv.take(Ts * F * es); l.dqkv = cv.take(Ts * 3 * H * es);
+    l.p2 = cv.take(layernorm_bwd_scratch((int)Ts, (int)H)); l.p1 = cv.take(layernorm_bwd_scratch((int)Ts, (int)H));
   }
   for (auto& l : w.dec) {
     l.s2 = cv.take(Tt * H * es); l.m2 = cv.take(Tt * H * es); l.sc = cv.take(Tt * H * es); l.mc = cv.take(Tt * H * es);
     l.s1 = cv.take(Tt * H * es); l.m1 = cv.take(Tt * H * es);
     l.dh = cv.take(Tt * F * es); l.dcq = cv.take(Tt * H * es); l.dckv = cv.take(Ts * 2 * H * es); l.dqkv = cv.take(Tt * 3 * H * es);
+    l.p2 = cv.take(layernorm_bwd_scratch((int)Tt, (int)H)); l.pc = cv.take(layernorm_bwd_scratch((int)Tt, (int)H));
+    l.p1 = cv.take(layernorm_bwd_scratch((int)Tt, (int)H));
   }
   w.dvec = (float*)cv.take((size_t)B * c.n_heads * std::max(Ls, Lt) * sizeof(float));
-  w.ln_part = cv.take(layernorm_bwd_scratch((int)Tm, (int)H));
   w.cs_part = cv.take(colsum_scratch((int)Tm, (int)std::max(F, 3 * H)));
   w.emb = cv.take(embed_bwd_scratch((int)Tm, (int)H));
   w.gemm_ws_bytes = gemm_scratch_bytes(c);
@@ -499,17 +501,19 @@ hs_status hs_s2s_bwd(hs_ctx* ctx, const void* w, const void* acts, const int32_t
                                          // (7.13 -> 6.78 ms per step)
   };
   // LayerNorm backward of a sub-layer: dsum = d(residual sum); the branch takes dsum through the sub-layer's dropout
-  // (dmask; dsum itself without dropout); the column sums of the branch gradient are the bias gradient of the
-  // sub-layer's last linear map.  Returns the branch gradient.
+  // (dmask; dsum itself without dropout).  The rows go on the chain; the column sums of its partials (gain and bias
+  // gradients, and the bias gradient of the sub-layer's last linear map = column sums of the branch gradient) on the
+  // second stream, which from here on may read what the chain has produced.  Returns the branch gradient.
   auto ln_bwd = [&](int T, const void* dy, const void* sum, const float* stats, int64_t gain, int64_t lnb, int64_t last_bias, uint32_t site,
-                    void* dsum, void* dmask, const void** branch) {
+                    void* dsum, void* dmask, void* partials, const void** branch) -> hs_status {
     *branch = drop ? dmask : dsum;
-    return launch_layernorm_bwd(ctx, dt, dy, sum, stats, W(dt, w, gain), dsum, g + gain, g + lnb, g + last_bias, beta, T, H, ws.ln_part, s,
-                                drop, site, drop ? 2 : 0, drop ? dmask : nullptr);
+    HS_TRY(launch_layernorm_bwd_rows(ctx, dt, dy, sum, stats, W(dt, w, gain), dsum, T, H, partials, s, drop, site, drop ? 2 : 0,
+                                     drop ? dmask : nullptr));
+    HS_TRY(hand_over());
+    return launch_layernorm_bwd_cols(ctx, partials, g + gain, g + lnb, g + last_bias, beta, T, H, sd);
   };
   // feed-forward backward: from the branch gradient to d(input of the sub-layer) = dsum + dh W1, written to out
   auto ffn_bwd = [&](int T, const BlockOff& lo, const LayerGrads& lg, const void* branch, const void* xin, const void* h, void* out) -> hs_status {
-    HS_TRY(hand_over());
     HS_TRY(wgrad(H, F, T, branch, H, h, F, g + lo.ffn2_w));
     HS_TRY(dgrad(T, F, H, branch, W(dt, w, lo.ffn2_w), lg.dh, nullptr));
     HS_TRY(launch_relu_bwd(ctx, dt, lg.dh, h, (size_t)T * F, s));
@@ -531,11 +535,10 @@ hs_status hs_s2s_bwd(hs_ctx* ctx, const void* w, const void* acts, const int32_t
     const void* y_in = (i == 0) ? a.t0 : a.dec[i - 1].y2;
     const void* br;
     // feed-forward sub-layer
-    HS_TRY(ln_bwd(Tt, dcur, la.y2s, la.st2, lo.ln2_g, lo.ln2_b, lo.ffn2_b, site_dec(c, i, 2), lg.s2, lg.m2, &br));
+    HS_TRY(ln_bwd(Tt, dcur, la.y2s, la.st2, lo.ln2_g, lo.ln2_b, lo.ffn2_b, site_dec(c, i, 2), lg.s2, lg.m2, lg.p2, &br));
     HS_TRY(ffn_bwd(Tt, lo, lg, br, la.yc, la.h, ws.da));
     // attention over the encoder output
-    HS_TRY(ln_bwd(Tt, ws.da, la.ycs, la.stc, lo.lnc_g, lo.lnc_b, lo.co_b, site_dec(c, i, 1), lg.sc, lg.mc, &br));
-    HS_TRY(hand_over());
+    HS_TRY(ln_bwd(Tt, ws.da, la.ycs, la.stc, lo.lnc_g, lo.lnc_b, lo.co_b, site_dec(c, i, 1), lg.sc, lg.mc, lg.pc, &br));
     HS_TRY(wgrad(H, H, Tt, br, H, la.cctx, H, g + lo.co_w));
     HS_TRY(dgrad(Tt, H, H, br, W(dt, w, lo.co_w), ws.dctx, nullptr));
     AttnOperands cross{la.cq, la.ckv, at(dt, (const void*)la.ckv, H), (int64_t)H, 2 * (int64_t)H, tgt_lens, src_lens, Lt, Ls, A, 0};
@@ -550,8 +553,7 @@ hs_status hs_s2s_bwd(hs_ctx* ctx, const void* w, const void* acts, const int32_t
     pe ^= 1; have_denc = true;
     HS_TRY(dgrad(Tt, H, H, lg.dcq, W(dt, w, lo.cq_w), ws.db, lg.sc));
     // causal self-attention
-    HS_TRY(ln_bwd(Tt, ws.db, la.y1s, la.st1, lo.ln1_g, lo.ln1_b, lo.o_b, site_dec(c, i, 0), lg.s1, lg.m1, &br));
-    HS_TRY(hand_over());
+    HS_TRY(ln_bwd(Tt, ws.db, la.y1s, la.st1, lo.ln1_g, lo.ln1_b, lo.o_b, site_dec(c, i, 0), lg.s1, lg.m1, lg.p1, &br));
     HS_TRY(wgrad(H, H, Tt, br, H, la.ctx, H, g + lo.o_w));
     HS_TRY(dgrad(Tt, H, H, br, W(dt, w, lo.o_w), ws.dctx, nullptr));
     AttnOperands self{la.qkv, at(dt, (const void*)la.qkv, H), at(dt, (const void*)la.qkv, 2 * H), 3 * (int64_t)H, 3 * (int64_t)H, tgt_lens, tgt_lens,
@@ -579,10 +581,9 @@ hs_status hs_s2s_bwd(hs_ctx* ctx, const void* w, const void* acts, const int32_t
     const LayerGrads& lg = ws.enc[i];
     const void* x_in = (i == 0) ? a.x0 : a.enc[i - 1].x2;
     const void* br;
-    HS_TRY(ln_bwd(Ts, dcur, la.y2, la.st2, lo.ln2_g, lo.ln2_b, lo.ffn2_b, site_enc(i, 1), lg.s2, lg.m2, &br));
+    HS_TRY(ln_bwd(Ts, dcur, la.y2, la.st2, lo.ln2_g, lo.ln2_b, lo.ffn2_b, site_enc(i, 1), lg.s2, lg.m2, lg.p2, &br));
     HS_TRY(ffn_bwd(Ts, lo, lg, br, la.x1, la.h, ws.da));
-    HS_TRY(ln_bwd(Ts, ws.da, la.y1, la.st1, lo.ln1_g, lo.ln1_b, lo.o_b, site_enc(i, 0), lg.s1, lg.m1, &br));
-    HS_TRY(hand_over());
+    HS_TRY(ln_bwd(Ts, ws.da, la.y1, la.st1, lo.ln1_g, lo.ln1_b, lo.o_b, site_enc(i, 0), lg.s1, lg.m1, lg.p1, &br));
     HS_TRY(wgrad(H, H, Ts, br, H, la.ctx, H, g + lo.o_w));
     HS_TRY(dgrad(Ts, H, H, br, W(dt, w, lo.o_w), ws.dctx, nullptr));
     HS_TRY(launch_attention_bwd(ctx, dt, la.qkv, la.ctx, la.lse, ws.dctx, src_lens, B, Ls, A, lg.dqkv, ws.dvec, s));
