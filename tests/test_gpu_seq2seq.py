@@ -319,3 +319,25 @@ def test_update_inside_backward_gives_the_bits_of_the_separate_calls(hs, compute
         if compute == "bf16":
             assert torch.equal(a.w_lowp, b.w_lowp)
     a.close(); b.close()
+
+
+def test_edge_cases_empty_batch_and_longest_buffers(hs):
+    """B = 0 is defined (zero losses, nothing else touched); buffers as long as the position table (64) with one full-length
+    pair, one single-token pair and a pair of unequal sides."""
+    model, ocfg, theta, wk = _setup("s2s_tiny", "fp32", 35)
+    wk._reserve(1, 64, 64)
+    wk.loss_buf.fill_(7.0)
+    wk.G.fill_(3.0)
+    e = torch.zeros(8, dtype=torch.int32, device="cuda")
+    hs.hs_s2s_fwd(wk.ctx, wk.w, e, e, e, e, 0, 64, 64, wk._acts, wk._out)
+    hs.hs_s2s_loss(wk.ctx, wk.w, wk._out, e, e, 0, 64, 0.1, wk.loss_buf.data_ptr(), wk.loss_buf.data_ptr() + 4, wk._dout, wk.G, 0, wk._ws, wk._ws_bytes)
+    hs.hs_s2s_bwd(wk.ctx, wk.w, wk._acts, e, e, e, e, 0, 64, 64, wk._dout, wk.G, 0, wk._ws, wk._ws_bytes)
+    torch.cuda.synchronize()
+    assert wk.loss_buf[0].item() == 0.0 and wk.loss_buf[1].item() == 0.0 and wk.loss_buf[2].item() == 7.0
+    assert torch.all(wk.G == 3.0)
+    mb = synth.make_pair_batch(synth.rng_for(36), [64, 1, 40], [64, 1, 9], 64, 64, model["vocab"], "uniform")
+    loss, nll, g = _gpu_grad(wk, mb)
+    ol, on, og, _, n_tok = S.micro_batch_grad(ocfg, theta.astype(np.float64), mb, 0.1)
+    assert n_tok == 74 and abs(loss - ol) / abs(ol) < 1e-4 and abs(nll - on) / abs(on) < 1e-4
+    compare_flat_decided(ocfg, g, og, 1e-4, "grad", undecided_units(ocfg, theta, mb))
+    wk.close()
