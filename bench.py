@@ -211,8 +211,10 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--dropout", type=float, default=0.0,
                     help="dropout rate at the model's four kinds of sites (the headline figure is taken without: 0)")
-    ap.add_argument("--workload", choices=["bert_base", "transformer_base"], default="bert_base",
-                    help="bert_base: the headline workload; transformer_base: the translation model's step")
+    ap.add_argument("--workload", choices=["bert_base", "bert_varlen", "bert_hetero", "bert_large", "transformer_base"], default="bert_base",
+                    help="bert_base: the headline workload (64 x 128 tokens); bert_varlen: 4096 sequences of 64..512 tokens batched under a "
+                         "16384-token cap, one step per batch; bert_hetero: micro-batches of 8, 24 and 56 sequences x 256 per step; "
+                         "bert_large: BERT-large, four micro-batches of 32 x 512 per step; transformer_base: the translation model's step")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus must be 1 (no collectives, no sharding in this path)",
@@ -231,27 +233,45 @@ def main():
         sys.exit(1)
     hs.lib()                                             # fail loudly if the HIP library is missing
 
-    widx = 1
+    widx = {"bert_base": 1, "bert_varlen": 2, "bert_hetero": 3, "bert_large": 4}[args.workload]
     wl = synth.WORKLOADS[widx]
     model = synth.MODELS[wl["model"]]
     cfg = hs.make_cfg(**model)
     theta = synth.init_params(hs.hs_param_layout(cfg), wl["seed"])
-    mbs = synth.workload_micro_batches(widx)
-    lengths = np.concatenate([mb["lens"] for mb in mbs]).astype(np.int32)
+    # step_mbs[i]: the micro-batches of step i (steps cycle through the list)
+    if widx == 2:      # one step per batch of the corpus, batches formed by the library's batcher
+        corpus = synth.draw_lengths(synth.rng_for(wl["seed"]), 4096, 64, 512)
+        seq, offs, pads = hs.hs_make_batches(corpus, 64, 16384, 0)
+        step_mbs = [[synth.make_micro_batch(synth.rng_for(wl["seed"] + 100 + j), corpus[seq[offs[j]:offs[j + 1]]], int(pads[j]), model["vocab"],
+                                            wl["ids"])] for j in range(len(pads))]
+        lengths, cap = corpus, 16384
+        if args.steps == 20:
+            args.steps = len(step_mbs)        # the default run is one pass over the batch list
+    else:
+        step_mbs = [synth.workload_micro_batches(widx)]
+        lengths = np.concatenate([mb["lens"] for mb in step_mbs[0]]).astype(np.int32)
+        cap = {1: 8192, 3: 256 * 88, 4: 16384 * 4}[widx]
+    mbs = step_mbs[0]
     worker = Worker(model, wl["compute"], theta)
     if args.dropout > 0.0:
-        for i, mb in enumerate(mbs):
-            mb["drop"] = dict(p=args.dropout, seed=wl["seed"], stream=i)
-    dev_batches = [worker.upload(mb) for mb in mbs]      # inputs resident in HBM before timing
-    tokens_per_step = int(sum(mb["n_real_tokens"] for mb in mbs))
-    flops_per_step = algorithmic_flops(model, mbs)
+        for sm in step_mbs:
+            for i, mb in enumerate(sm):
+                mb["drop"] = dict(p=args.dropout, seed=wl["seed"], stream=i)
+    step_dev = [[worker.upload(mb) for mb in sm] for sm in step_mbs]      # inputs resident in HBM before timing
+    dev_batches = step_dev[0]
+    n_list = len(step_dev)
+    tokens_of = [int(sum(mb["n_real_tokens"] for mb in sm)) for sm in step_mbs]
+    flops_of = [algorithmic_flops(model, sm) for sm in step_mbs]
+    tokens_per_step = sum(tokens_of[i % n_list] for i in range(args.steps)) / args.steps
+    flops_per_step = sum(flops_of[i % n_list] for i in range(args.steps)) / args.steps
+    step_no = [0]
 
     def one_step():
-        # a0: batch formation under the max-tokens cap (host, integer); the batch it yields is the
-        # one already uploaded
-        seq, offs, pads = hs.hs_make_batches(lengths, 64, 8192, 0)
-        assert len(pads) == len(dev_batches)
-        worker.train_step(dev_batches, wl["adam"])
+        # a0: batch formation under the max-tokens cap (host, integer); the batches it yields are the
+        # ones already uploaded
+        hs.hs_make_batches(lengths, 64, cap, 0)
+        worker.train_step(step_dev[step_no[0] % n_list], wl["adam"])
+        step_no[0] += 1
 
     # One plain elementwise copy of known size (256 MiB read, 256 MiB written) before anything is timed:
     # under a counter-collecting profiler it gives the scale of the HBM byte counters.
@@ -264,22 +284,24 @@ def main():
     for _ in range(args.warmup):
         one_step()
     torch.cuda.synchronize()
+    step_no[0] = 0
     t0 = time.perf_counter()
     for _ in range(args.steps):
         one_step()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     ms_per_step = 1e3 * dt / args.steps
-    D = sum(d["n_seq"] for d in dev_batches)
+    last = step_dev[(args.steps - 1) % n_list]
+    D = sum(d["n_seq"] for d in last)
     loss = worker.reported_loss(D)
 
     # per-kernel timing with HIP events on the launch stream, in extra steps of the same loop
     hs.hs_profile_enable(worker.ctx, 1)
     prof = {}
     adam_ms = []
-    for _ in range(args.profile_steps):
+    for ps in range(args.profile_steps):
         ev0, ev1, ev2 = (torch.cuda.Event(enable_timing=True) for _ in range(3))
-        n_total = worker.accumulate_micro_batches(dev_batches)
+        n_total = worker.accumulate_micro_batches(step_dev[ps % n_list])
         ev0.record()
         hs.hs_grad_accum_normalize(worker.G, None, worker.P, 0, float(n_total))
         ev1.record()
@@ -315,7 +337,7 @@ def main():
         gemm_flops = sum(prof[k]["flops"] for k in gemm_classes)
         gemm_ms = sum(prof[k]["ms"] for k in gemm_classes)
         roofline = dict(bound="mfma", kernel=dominant, achieved=achieved, peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
-                        frac=achieved / PEAK_BF16_TFLOPS, traffic=recorded_traffic(dominant),
+                        frac=achieved / PEAK_BF16_TFLOPS, traffic=recorded_traffic(dominant) if widx == 1 else None,
                         algorithmic_bytes_per_launch=dp["bytes"] / dp["launches"],
                         avg_launch_us=1e3 * dp["ms"] / dp["launches"],
                         launches_per_step=dp["launches"] / args.profile_steps,
@@ -324,19 +346,27 @@ def main():
                         measured="HIP events around every launch, on the launch stream, in "
                                  f"{args.profile_steps} extra steps after the timed region")
 
-    out = dict(metric="trained tokens/sec on 1 MI355X (BERT-base step) + % peak bf16 MFMA",
+    shape_text = {
+        1: "BERT-base-shaped step: 12 post-LN layers, hidden 768, 12 heads, FFN 3072, vocab 30522, tied MLM head; 64 sequences x 128 "
+           "tokens (max-tokens cap 8192)",
+        2: f"BERT-base-shaped model; 4096 sequences of 64..512 tokens in buckets of 64 under a cap of 16384 real tokens: {n_list} batches, "
+           "one step per batch",
+        3: "BERT-base-shaped model; per step three micro-batches of 8, 24 and 56 sequences x 256 tokens accumulated and normalised by 88",
+        4: "BERT-large-shaped model (24 layers, hidden 1024, 16 heads, FFN 4096); per step four micro-batches of 32 sequences x 512 tokens "
+           "accumulated and normalised by 128",
+    }[widx]
+    out = dict(metric="trained tokens/sec on 1 MI355X (BERT-base step) + % peak bf16 MFMA" if widx == 1 else
+                      f"trained tokens/sec on 1 MI355X ({args.workload} step) + % peak bf16 MFMA",
                value=tokens_per_step * args.steps / dt, unit="tokens/s", n_gpus=1, steps=args.steps, warmup=args.warmup,
                ms_per_step=ms_per_step, higher_is_better=True, scaling="weak", vs_baseline=None, dtype="bf16",
                data="synthetic",
-               config=dict(workload="BERT-base-shaped step: 12 post-LN layers, hidden 768, 12 heads, FFN 3072, vocab 30522, "
-                                    "tied MLM head; 64 sequences x 128 tokens (max-tokens cap 8192), Zipf(1.1) ids, 15% MLM "
-                                    "targets, bf16 compute with fp32 master weights and accumulation",
-                           tokens_per_step=tokens_per_step, mlm_targets=int(sum(d["M"] for d in dev_batches)),
-                           global_batch=D, seq_len=128, params=P, dropout=args.dropout),
+               config=dict(workload=shape_text + ", Zipf(1.1) ids, 15% MLM targets, bf16 compute with fp32 master weights and accumulation",
+                           tokens_per_step=tokens_per_step, mlm_targets=int(sum(d["M"] for d in last)),
+                           global_batch=D, seq_len=int(last[0]["L"]), params=P, dropout=args.dropout),
                whole_step_tflops=flops_per_step / (ms_per_step * 1e-3) / 1e12,
                whole_step_mfma_frac=flops_per_step / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
                loss=loss, roofline=roofline, kernels=kernels)
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and widx == 1:
         out["cpu_baseline"] = cpu_baseline(model, wl, theta, mbs)
     worker.close()
     print(json.dumps(out))
