@@ -217,7 +217,7 @@ def main():
                          "bert_large: BERT-large, four micro-batches of 32 x 512 per step; transformer_base: the translation model's step")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU; --gpus must be 1 (no collectives, no sharding in this path)",
+        print("bench.py: the path runs on ONE GPU; --gpus must be 1 (no collectives, no sharding)",
               file=sys.stderr)
         sys.exit(2)
 
