@@ -323,11 +323,13 @@ hs_status hs_s2s_fwd(hs_ctx* ctx, const void* w, const int32_t* src, const int32
  * Per real position with label y: nll = logsumexp(z) - z_y; loss = (1 - eps) nll + eps (logsumexp(z) - mean_v z_v), i.e.
  * the cross-entropy to the target (1 - eps) onehot(y) + eps / V.  *loss_sum and *nll_sum (dev scalars, nll_sum may be
  * NULL) are overwritten; nothing is divided (the weight, normally the number of real target tokens, travels beside the sum).
- * tgt_out [B, Lt] dev int32 labels.  d_dec_out [B, Lt, H] dev is fully written (zero rows at padding); the projection's
+ * tgt_out [B, Lt] dev int32 labels.  tgt_lens_host: the same lengths on the host, or NULL; when given they are validated
+ * (1 <= len <= Lt) and the padding rows are left out of the projection (the real rows are gathered first), which changes
+ * nothing but the order of the fp32 loss sums.  d_dec_out [B, Lt, H] dev is fully written (zero rows at padding); the projection's
  * share of the emb gradient goes to g (flat fp32 [P] dev): overwritten when accumulate == 0, added when 1. */
-hs_status hs_s2s_loss(hs_ctx* ctx, const void* w, const void* dec_out, const int32_t* tgt_out, const int32_t* tgt_lens, int32_t B,
-                      int32_t Lt, double eps, float* loss_sum, float* nll_sum, void* d_dec_out, float* g, int32_t accumulate,
-                      void* workspace, size_t workspace_bytes, void* stream);
+hs_status hs_s2s_loss(hs_ctx* ctx, const void* w, const void* dec_out, const int32_t* tgt_out, const int32_t* tgt_lens,
+                      const int32_t* tgt_lens_host, int32_t B, int32_t Lt, double eps, float* loss_sum, float* nll_sum, void* d_dec_out,
+                      float* g, int32_t accumulate, void* workspace, size_t workspace_bytes, void* stream);
 
 /* Backward through decoder and encoder down to the embedding.  Gradients of enc*. and dec*. go to g (overwritten when
  * accumulate == 0, added when 1); emb is ALWAYS added to (call hs_s2s_loss first).  An update armed with hs_arm_update is

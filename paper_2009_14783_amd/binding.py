@@ -97,7 +97,7 @@ _SIGNATURES = {
     "hs_s2s_acts_bytes": (_SZ, [C.POINTER(hs_s2s_cfg), _I32, _I32, _I32]),
     "hs_s2s_workspace_bytes": (_SZ, [C.POINTER(hs_s2s_cfg), _I32, _I32, _I32]),
     "hs_s2s_fwd": (_I32, [_P, _P, _P, _P, _P, _P, _I32, _I32, _I32, _P, _P, _P]),
-    "hs_s2s_loss": (_I32, [_P, _P, _P, _P, _P, _I32, _I32, _D, _P, _P, _P, _P, _I32, _P, _SZ, _P]),
+    "hs_s2s_loss": (_I32, [_P, _P, _P, _P, _P, _P, _I32, _I32, _D, _P, _P, _P, _P, _I32, _P, _SZ, _P]),
     "hs_s2s_bwd": (_I32, [_P, _P, _P, _P, _P, _P, _P, _I32, _I32, _I32, _P, _P, _I32, _P, _SZ, _P]),
     "hs_op_attention_general_fwd": (_I32, [_I32, _P, _I64, _P, _P, _I64, _P, _P, _I32, _I32, _I32, _I32, _I32, _P, _P, _P]),
     "hs_op_attention_general_bwd": (_I32, [_I32, _P, _I64, _P, _P, _I64, _P, _P, _I32, _I32, _I32, _I32, _I32, _P, _P, _P, _P, _I64, _P,
@@ -415,9 +415,10 @@ def hs_s2s_fwd(ctx, w, src, src_lens, tgt_in, tgt_lens, B, Ls, Lt, acts, dec_out
                             _stream(stream)), ctx)
 
 
-def hs_s2s_loss(ctx, w, dec_out, tgt_out, tgt_lens, B, Lt, eps, loss_sum, nll_sum, d_dec_out, g, accumulate, workspace, workspace_bytes,
-                stream=None):
-    _check(lib().hs_s2s_loss(ctx, _ptr(w), _ptr(dec_out), _ptr(tgt_out), _ptr(tgt_lens), B, Lt, float(eps), _ptr(loss_sum), _ptr(nll_sum),
+def hs_s2s_loss(ctx, w, dec_out, tgt_out, tgt_lens, tgt_lens_host, B, Lt, eps, loss_sum, nll_sum, d_dec_out, g, accumulate, workspace,
+                workspace_bytes, stream=None):
+    _check(lib().hs_s2s_loss(ctx, _ptr(w), _ptr(dec_out), _ptr(tgt_out), _ptr(tgt_lens), _ptr(tgt_lens_host), B, Lt, float(eps), _ptr(loss_sum),
+                             _ptr(nll_sum),
                              _ptr(d_dec_out), _ptr(g), accumulate, _ptr(workspace), workspace_bytes, _stream(stream)), ctx)
 
 

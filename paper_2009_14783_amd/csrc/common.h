@@ -263,7 +263,9 @@ hs_status launch_mask_scale(hs_ctx* ctx, int dtype, const void* x, void* y, size
                             hipStream_t s);
 hs_status launch_relu(hs_ctx* ctx, int dtype, void* x, size_t n, hipStream_t s);
 hs_status launch_relu_bwd(hs_ctx* ctx, int dtype, void* dx, const void* h, size_t n, hipStream_t s);
-hs_status launch_smoothed_ce(hs_ctx* ctx, int dtype, const float* logits, int64_t ldl, const int32_t* labels, const int32_t* lens, int B, int L,
-                             int V, float eps, void* dlogits, float* row_loss, float* row_nll, float* loss_sum, float* nll_sum, hipStream_t s);
+hs_status launch_real_rows(hs_ctx* ctx, const int32_t* lens, int B, int L, int32_t* rows, int capacity, hipStream_t s);
+hs_status launch_smoothed_ce(hs_ctx* ctx, int dtype, const float* logits, int64_t ldl, const int32_t* labels, const int32_t* lens, int M, int L,
+                             int V, float eps, void* dlogits, float* row_loss, float* row_nll, float* loss_sum, float* nll_sum,
+                             const int32_t* rows, hipStream_t s);
 hs_status launch_ce_loss(hs_ctx* ctx, int dtype, const float* logits, int64_t ldl, const int32_t* labels, int M, int V, void* dlogits,
                          float* row_loss, float* loss_sum, hipStream_t s);

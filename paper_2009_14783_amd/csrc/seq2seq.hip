@@ -122,7 +122,7 @@ size_t gemm_scratch_bytes(const hs_s2s_cfg& c) {
   return std::max<size_t>((size_t)32 << 20, (size_t)8 * c.hidden * std::max(c.ffn, 3 * c.hidden) * sizeof(float));
 }
 
-struct LossWs { float *logits, *row_loss, *row_nll; void *dlogits, *gemm_ws; size_t gemm_ws_bytes, total; };
+struct LossWs { float *logits, *row_loss, *row_nll; void *dlogits, *gemm_ws, *xc, *dxc; int32_t* rows; size_t gemm_ws_bytes, total; };
 LossWs carve_loss(const hs_s2s_cfg& c, int B, int Lt, void* base) {
   const size_t Tt = (size_t)B * Lt, Vp = padded_vocab(c.vocab), es = esize(c.compute);
   Carver cv(base);
@@ -130,6 +130,8 @@ LossWs carve_loss(const hs_s2s_cfg& c, int B, int Lt, void* base) {
   w.logits = (float*)cv.take(Tt * Vp * sizeof(float));
   w.dlogits = cv.take(Tt * Vp * es);
   w.row_loss = (float*)cv.take(Tt * sizeof(float)); w.row_nll = (float*)cv.take(Tt * sizeof(float));
+  // compaction of the real target rows: their positions, the gathered decoder outputs and their gradients
+  w.rows = (int32_t*)cv.take(Tt * sizeof(int32_t)); w.xc = cv.take(Tt * c.hidden * es); w.dxc = cv.take(Tt * c.hidden * es);
   w.gemm_ws_bytes = gemm_scratch_bytes(c);
   w.gemm_ws = cv.take(w.gemm_ws_bytes);
   w.total = cv.off;
@@ -393,9 +395,9 @@ hs_status hs_s2s_fwd(hs_ctx* ctx, const void* w, const int32_t* src, const int32
   return HS_OK;
 }
 
-hs_status hs_s2s_loss(hs_ctx* ctx, const void* w, const void* dec_out, const int32_t* tgt_out, const int32_t* tgt_lens, int32_t B, int32_t Lt,
-                      double eps, float* loss_sum, float* nll_sum, void* d_dec_out, float* g, int32_t accumulate, void* workspace,
-                      size_t workspace_bytes, void* stream) {
+hs_status hs_s2s_loss(hs_ctx* ctx, const void* w, const void* dec_out, const int32_t* tgt_out, const int32_t* tgt_lens,
+                      const int32_t* tgt_lens_host, int32_t B, int32_t Lt, double eps, float* loss_sum, float* nll_sum, void* d_dec_out, float* g,
+                      int32_t accumulate, void* workspace, size_t workspace_bytes, void* stream) {
   if (!ctx) return HS_ERR_INVALID_ARG;
   if (!ctx->is_s2s) return hs_fail(ctx, HS_ERR_STATE, "hs_s2s_loss: the context was not made by hs_s2s_ctx_create");
   const hs_s2s_cfg& c = ctx->s2s;
@@ -413,19 +415,44 @@ hs_status hs_s2s_loss(hs_ctx* ctx, const void* w, const void* dec_out, const int
   const S2SOff o = s2s_offsets(c);
   const int dt = c.compute, H = c.hidden, V = c.vocab, Vp = padded_vocab(V), Tt = B * Lt;
   LossWs h = carve_loss(c, B, Lt, workspace);
-  // logits = dec_out E^T, fp32, row stride Vp
-  GemmArgs ga = gemm_args(dt, 1, 1, Tt, V, H, dec_out, H, W(dt, w, o.emb), H, h.logits, Vp);
+  // With the lengths known on the host the padding rows are left out of the vocabulary projection: the real rows are
+  // gathered, projected and scored, and their gradient rows scattered back into a zeroed d dec_out.
+  int M = Tt;
+  if (tgt_lens_host) {
+    int64_t n_real = 0;
+    for (int b = 0; b < B; ++b) {
+      if (tgt_lens_host[b] < 1 || tgt_lens_host[b] > Lt) return hs_fail(ctx, HS_ERR_INVALID_ARG, "hs_s2s_loss: tgt_lens[b] outside [1, Lt]");
+      n_real += tgt_lens_host[b];
+    }
+    M = (int)n_real;
+  }
+  const bool compact = M < Tt;
+  const void* X = dec_out;
+  void* dX = d_dec_out;
+  const int32_t* rows = nullptr;
+  if (compact) {
+    HS_TRY(launch_real_rows(ctx, tgt_lens, B, Lt, h.rows, M, s));
+    HS_TRY(launch_gather_rows(ctx, dt, dec_out, h.rows, M, H, h.xc, s));
+    X = h.xc; dX = h.dxc; rows = h.rows;
+  }
+  // logits = x E^T, fp32, row stride Vp
+  GemmArgs ga = gemm_args(dt, 1, 1, M, V, H, X, H, W(dt, w, o.emb), H, h.logits, Vp);
   ga.c_f32 = 1; ga.ws = h.gemm_ws; ga.ws_bytes = h.gemm_ws_bytes;
   HS_TRY(launch_gemm(ctx, ga, s));
-  HS_TRY(launch_smoothed_ce(ctx, dt, h.logits, Vp, tgt_out, tgt_lens, B, Lt, V, (float)eps, h.dlogits, h.row_loss, h.row_nll, loss_sum,
-                            nll_sum, s));
-  // dE [V,H] (+)= dlogits^T dec_out ; d dec_out = dlogits E
-  ga = gemm_args(dt, 0, 0, V, H, Tt, h.dlogits, Vp, dec_out, H, g + o.emb, H);
+  HS_TRY(launch_smoothed_ce(ctx, dt, h.logits, Vp, tgt_out, tgt_lens, M, Lt, V, (float)eps, h.dlogits, h.row_loss, h.row_nll, loss_sum, nll_sum,
+                            rows, s));
+  // dE [V,H] (+)= dlogits^T x ; dx = dlogits E
+  ga = gemm_args(dt, 0, 0, V, H, M, h.dlogits, Vp, X, H, g + o.emb, H);
   ga.c_f32 = 1; ga.beta = accumulate ? 1.f : 0.f; ga.ws = h.gemm_ws; ga.ws_bytes = h.gemm_ws_bytes;
   HS_TRY(launch_gemm(ctx, ga, s));
-  ga = gemm_args(dt, 1, 0, Tt, H, V, h.dlogits, Vp, W(dt, w, o.emb), H, d_dec_out, H);
+  ga = gemm_args(dt, 1, 0, M, H, V, h.dlogits, Vp, W(dt, w, o.emb), H, dX, H);
   ga.ws = h.gemm_ws; ga.ws_bytes = h.gemm_ws_bytes;
-  return launch_gemm(ctx, ga, s);
+  HS_TRY(launch_gemm(ctx, ga, s));
+  if (compact) {
+    HS_TRY(launch_fill_zero(ctx, d_dec_out, (size_t)Tt * H * esize(dt), s));
+    HS_TRY(launch_scatter_rows(ctx, dt, h.dxc, h.rows, M, H, d_dec_out, s));
+  }
+  return HS_OK;
 }
 
 hs_status hs_s2s_bwd(hs_ctx* ctx, const void* w, const void* acts, const int32_t* src, const int32_t* src_lens, const int32_t* tgt_in,

@@ -109,10 +109,12 @@ __device__ __forceinline__ float block_reduce256(float v, bool is_max, float* sh
 template <class T>
 __global__ __launch_bounds__(256) void smoothed_ce_kernel(const float* __restrict__ logits, int64_t ldl, const int32_t* __restrict__ labels,
                                                           const int32_t* __restrict__ lens, int L, int V, float eps,
-                                                          T* __restrict__ dlogits, float* __restrict__ row_loss, float* __restrict__ row_nll) {
+                                                          T* __restrict__ dlogits, float* __restrict__ row_loss, float* __restrict__ row_nll,
+                                                          const int32_t* __restrict__ rows) {
   __shared__ float sh[4];
   const int m = blockIdx.x;
-  const int b = m / L, l = m - b * L;
+  const int pos = rows ? rows[m] : m;          // position b*L + l of this row of logits
+  const int b = pos / L, l = pos - b * L;
   T* d = dlogits + (int64_t)m * ldl;
   if (l >= lens[b]) {       // block-uniform
     for (int v = threadIdx.x; v < (int)ldl; v += 256) d[v] = from_f<T>(0.f);
@@ -128,7 +130,7 @@ __global__ __launch_bounds__(256) void smoothed_ce_kernel(const float* __restric
   for (int v = threadIdx.x; v < V; v += 256) se += __expf(z[v] - mx);
   se = block_reduce256(se, false, sh);
   const float lse = mx + logf(se);
-  int lab = labels[m];
+  int lab = labels[pos];
   lab = lab < 0 ? 0 : (lab >= V ? V - 1 : lab);
   if (threadIdx.x == 0) {
     const float nll = lse - z[lab];
@@ -159,10 +161,12 @@ __device__ __forceinline__ float block_reduce1024(float v, bool is_max, float* s
 template <class T>
 __global__ __launch_bounds__(SCE_NT) void smoothed_ce_row_kernel(const float* __restrict__ logits, int64_t ldl, const int32_t* __restrict__ labels,
                                                                 const int32_t* __restrict__ lens, int L, int V, float eps,
-                                                                T* __restrict__ dlogits, float* __restrict__ row_loss, float* __restrict__ row_nll) {
+                                                                T* __restrict__ dlogits, float* __restrict__ row_loss, float* __restrict__ row_nll,
+                                                                const int32_t* __restrict__ rows) {
   __shared__ float sh[SCE_NT / 64];
   const int m = blockIdx.x;
-  const int b = m / L, l = m - b * L;
+  const int pos = rows ? rows[m] : m;          // position b*L + l of this row of logits
+  const int b = pos / L, l = pos - b * L;
   const int nch = (int)(ldl / 4);
   T* d = dlogits + (int64_t)m * ldl;
   if (l >= lens[b]) {       // block-uniform
@@ -195,7 +199,7 @@ __global__ __launch_bounds__(SCE_NT) void smoothed_ce_row_kernel(const float* __
     se += (__expf(x[c].x - mx) + __expf(x[c].y - mx)) + (__expf(x[c].z - mx) + __expf(x[c].w - mx));
   se = block_reduce1024(se, false, sh);
   const float lse = mx + logf(se);
-  int lab = labels[m];
+  int lab = labels[pos];
   lab = lab < 0 ? 0 : (lab >= V ? V - 1 : lab);
   if (threadIdx.x == 0) {
     const float nll = lse - z[lab];
@@ -215,6 +219,35 @@ __global__ __launch_bounds__(SCE_NT) void smoothed_ce_row_kernel(const float* __
       V4<T>::st(d + v, p);
     }
   }
+}
+
+// rows[k] = b*L + l for the real positions (l < lens[b]) in ascending order: one block walks the sequences in chunks
+// of 1024 with a running offset (a block-wide exclusive scan of the clamped lengths per chunk)
+__global__ __launch_bounds__(1024) void real_rows_kernel(const int32_t* __restrict__ lens, int B, int L, int32_t* __restrict__ rows, int capacity) {
+  __shared__ int scan[1024];
+  __shared__ int base_s;
+  if (threadIdx.x == 0) base_s = 0;
+  __syncthreads();
+  for (int b0 = 0; b0 < B; b0 += 1024) {
+    const int b = b0 + threadIdx.x;
+    int n = 0;
+    if (b < B) { n = lens[b]; n = n < 0 ? 0 : (n > L ? L : n); }
+    scan[threadIdx.x] = n;
+    __syncthreads();
+    for (int o = 1; o < 1024; o <<= 1) {          // inclusive scan
+      const int v = threadIdx.x >= o ? scan[threadIdx.x - o] : 0;
+      __syncthreads();
+      scan[threadIdx.x] += v;
+      __syncthreads();
+    }
+    const int start = base_s + scan[threadIdx.x] - n;
+    for (int l = 0; l < n; ++l) if (start + l < capacity) rows[start + l] = b * L + l;
+    __syncthreads();
+    if (threadIdx.x == 1023) base_s += scan[1023];
+    __syncthreads();
+  }
+  // a caller whose count exceeds the real one still gets valid positions (position 0) in the tail
+  for (int k = base_s + threadIdx.x; k < capacity; k += 1024) rows[k] = 0;
 }
 
 // fixed-order sums of two vectors of n floats by one block
@@ -288,17 +321,27 @@ hs_status launch_relu_bwd(hs_ctx* ctx, int dtype, void* dx, const void* h, size_
   return HS_OK;
 }
 
-hs_status launch_smoothed_ce(hs_ctx* ctx, int dtype, const float* logits, int64_t ldl, const int32_t* labels, const int32_t* lens, int B, int L,
-                             int V, float eps, void* dlogits, float* row_loss, float* row_nll, float* loss_sum, float* nll_sum, hipStream_t s) {
-  const int M = B * L;
+hs_status launch_real_rows(hs_ctx* ctx, const int32_t* lens, int B, int L, int32_t* rows, int capacity, hipStream_t s) {
+  if (B <= 0) return HS_OK;
+  KScope scope(ctx ? ctx->prof : nullptr, KC_ELEMWISE, 0.0, 4.0 * capacity, s);
+  hipLaunchKernelGGL(real_rows_kernel, dim3(1), dim3(1024), 0, s, lens, B, L, rows, capacity);
+  S2S_LAUNCH_CHECK(ctx, "real_rows");
+  return HS_OK;
+}
+
+// M rows of logits; rows == NULL: row m is position m of the [B, L] batch (padding rows give zero loss and gradient);
+// otherwise row m is position rows[m], which must be real.
+hs_status launch_smoothed_ce(hs_ctx* ctx, int dtype, const float* logits, int64_t ldl, const int32_t* labels, const int32_t* lens, int M, int L,
+                             int V, float eps, void* dlogits, float* row_loss, float* row_nll, float* loss_sum, float* nll_sum,
+                             const int32_t* rows, hipStream_t s) {
   if (M <= 0) return HS_OK;
-  KScope scope(ctx ? ctx->prof : nullptr, KC_LOSS, 5.0 * M * V, (double)M * V * (8.0 + esize(dtype)), s);
+  KScope scope(ctx ? ctx->prof : nullptr, KC_LOSS, 5.0 * M * V, (double)M * V * (4.0 + esize(dtype)), s);
   const bool in_regs = (ldl % 4) == 0 && ldl <= (int64_t)4 * SCE_NT * SCE_MAXCH && ((uintptr_t)logits % 16) == 0 && ((uintptr_t)dlogits % 16) == 0;
   if (in_regs) {
-    if (dtype == HS_BF16) hipLaunchKernelGGL(smoothed_ce_row_kernel<bf16>, dim3(M), dim3(SCE_NT), 0, s, logits, ldl, labels, lens, L, V, eps, (bf16*)dlogits, row_loss, row_nll);
-    else hipLaunchKernelGGL(smoothed_ce_row_kernel<float>, dim3(M), dim3(SCE_NT), 0, s, logits, ldl, labels, lens, L, V, eps, (float*)dlogits, row_loss, row_nll);
-  } else if (dtype == HS_BF16) hipLaunchKernelGGL(smoothed_ce_kernel<bf16>, dim3(M), dim3(256), 0, s, logits, ldl, labels, lens, L, V, eps, (bf16*)dlogits, row_loss, row_nll);
-  else hipLaunchKernelGGL(smoothed_ce_kernel<float>, dim3(M), dim3(256), 0, s, logits, ldl, labels, lens, L, V, eps, (float*)dlogits, row_loss, row_nll);
+    if (dtype == HS_BF16) hipLaunchKernelGGL(smoothed_ce_row_kernel<bf16>, dim3(M), dim3(SCE_NT), 0, s, logits, ldl, labels, lens, L, V, eps, (bf16*)dlogits, row_loss, row_nll, rows);
+    else hipLaunchKernelGGL(smoothed_ce_row_kernel<float>, dim3(M), dim3(SCE_NT), 0, s, logits, ldl, labels, lens, L, V, eps, (float*)dlogits, row_loss, row_nll, rows);
+  } else if (dtype == HS_BF16) hipLaunchKernelGGL(smoothed_ce_kernel<bf16>, dim3(M), dim3(256), 0, s, logits, ldl, labels, lens, L, V, eps, (bf16*)dlogits, row_loss, row_nll, rows);
+  else hipLaunchKernelGGL(smoothed_ce_kernel<float>, dim3(M), dim3(256), 0, s, logits, ldl, labels, lens, L, V, eps, (float*)dlogits, row_loss, row_nll, rows);
   S2S_LAUNCH_CHECK(ctx, "smoothed_ce");
   hipLaunchKernelGGL(sum_two_kernel, dim3(1), dim3(256), 0, s, (const float*)row_loss, (const float*)row_nll, M, loss_sum, nll_sum);
   S2S_LAUNCH_CHECK(ctx, "loss sums");

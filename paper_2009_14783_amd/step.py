@@ -255,7 +255,8 @@ class PairWorker:
         dev = self.device
         t = lambda k: torch.from_numpy(np.ascontiguousarray(mb[k], dtype=np.int32)).to(dev)
         out = dict(B=int(mb["src"].shape[0]), Ls=int(mb["src"].shape[1]), Lt=int(mb["tgt_in"].shape[1]), src=t("src"), src_lens=t("src_lens"),
-                   tgt_in=t("tgt_in"), tgt_out=t("tgt_out"), tgt_lens=t("tgt_lens"), n_seq=int(mb["src"].shape[0]),
+                   tgt_in=t("tgt_in"), tgt_out=t("tgt_out"), tgt_lens=t("tgt_lens"),
+                   tgt_lens_host=np.ascontiguousarray(mb["tgt_lens"], dtype=np.int32), n_seq=int(mb["src"].shape[0]),
                    n_tok=int(np.asarray(mb["tgt_lens"]).sum()), drop=mb.get("drop"))
         self._reserve(out["B"], out["Ls"], out["Lt"])
         return out
@@ -270,7 +271,8 @@ class PairWorker:
         w = self.w_compute
         hs.hs_s2s_fwd(self.ctx, w, d["src"], d["src_lens"], d["tgt_in"], d["tgt_lens"], B, Ls, Lt, self._acts, self._out)
         base = self.loss_buf.data_ptr()
-        hs.hs_s2s_loss(self.ctx, w, self._out, d["tgt_out"], d["tgt_lens"], B, Lt, self.eps_ls, base + 4 * slot, base + 4 * (64 + slot),
+        hs.hs_s2s_loss(self.ctx, w, self._out, d["tgt_out"], d["tgt_lens"], d.get("tgt_lens_host"), B, Lt, self.eps_ls, base + 4 * slot,
+                       base + 4 * (64 + slot),
                        self._dout, g, accumulate, self._ws, self._ws_bytes)
         hs.hs_s2s_bwd(self.ctx, w, self._acts, d["src"], d["src_lens"], d["tgt_in"], d["tgt_lens"], B, Ls, Lt, self._dout, g, accumulate,
                       self._ws, self._ws_bytes)

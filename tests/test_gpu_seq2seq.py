@@ -231,7 +231,7 @@ def test_bad_arguments_are_refused(hs):
     with pytest.raises(hs.HsError):      # longer than the position table
         hs.hs_s2s_fwd(wk.ctx, wk.w, d["src"], d["src_lens"], d["tgt_in"], d["tgt_lens"], 1, 8, 128, wk._acts, wk._out)
     with pytest.raises(hs.HsError):      # workspace too small
-        hs.hs_s2s_loss(wk.ctx, wk.w, wk._out, d["tgt_out"], d["tgt_lens"], 1, 8, 0.1, wk.loss_buf, None, wk._dout, wk.G, 0, wk._ws, 16)
+        hs.hs_s2s_loss(wk.ctx, wk.w, wk._out, d["tgt_out"], d["tgt_lens"], None, 1, 8, 0.1, wk.loss_buf, None, wk._dout, wk.G, 0, wk._ws, 16)
     from paper_2009_14783_amd.step import Worker
     enc = Worker(synth.MODELS["tiny"], "fp32", synth.init_params(hs.hs_param_layout(hs.make_cfg(**synth.MODELS["tiny"])), 1))
     with pytest.raises(hs.HsError):      # a context of the encoder-only model
@@ -330,7 +330,7 @@ def test_edge_cases_empty_batch_and_longest_buffers(hs):
     wk.G.fill_(3.0)
     e = torch.zeros(8, dtype=torch.int32, device="cuda")
     hs.hs_s2s_fwd(wk.ctx, wk.w, e, e, e, e, 0, 64, 64, wk._acts, wk._out)
-    hs.hs_s2s_loss(wk.ctx, wk.w, wk._out, e, e, 0, 64, 0.1, wk.loss_buf.data_ptr(), wk.loss_buf.data_ptr() + 4, wk._dout, wk.G, 0, wk._ws, wk._ws_bytes)
+    hs.hs_s2s_loss(wk.ctx, wk.w, wk._out, e, e, None, 0, 64, 0.1, wk.loss_buf.data_ptr(), wk.loss_buf.data_ptr() + 4, wk._dout, wk.G, 0, wk._ws, wk._ws_bytes)
     hs.hs_s2s_bwd(wk.ctx, wk.w, wk._acts, e, e, e, e, 0, 64, 64, wk._dout, wk.G, 0, wk._ws, wk._ws_bytes)
     torch.cuda.synchronize()
     assert wk.loss_buf[0].item() == 0.0 and wk.loss_buf[1].item() == 0.0 and wk.loss_buf[2].item() == 7.0
@@ -340,4 +340,32 @@ def test_edge_cases_empty_batch_and_longest_buffers(hs):
     ol, on, og, _, n_tok = S.micro_batch_grad(ocfg, theta.astype(np.float64), mb, 0.1)
     assert n_tok == 74 and abs(loss - ol) / abs(ol) < 1e-4 and abs(nll - on) / abs(on) < 1e-4
     compare_flat_decided(ocfg, g, og, 1e-4, "grad", undecided_units(ocfg, theta, mb))
+    wk.close()
+
+
+@pytest.mark.parametrize("compute", ["fp32", "bf16"])
+def test_projection_over_real_rows_only_equals_projection_over_all_rows(hs, compute):
+    """With the target lengths on the host the padding rows are left out of the vocabulary projection; without them every
+    row is projected and padding rows get zero loss and gradient.  Same result (the loss sums differ in summation order)."""
+    model, ocfg, theta, wk = _setup("s2s_tiny", compute, 37)
+    mb = synth.make_pair_batch(synth.rng_for(38), [16, 9, 24, 1, 17, 8], [20, 32, 7, 3, 1, 32], 24, 32, model["vocab"], "uniform")
+    d = wk.upload(mb)
+    wk.G.fill_(float("nan"))
+    wk.forward_backward(d, wk.G, 0, 0)
+    torch.cuda.synchronize()
+    a_loss, a_nll, a_g = float(wk.loss_buf[0]), float(wk.loss_buf[64]), wk.G.cpu().numpy().copy()
+    d_all = dict(d, tgt_lens_host=None)
+    wk.G.fill_(float("nan"))
+    wk.forward_backward(d_all, wk.G, 0, 1)
+    torch.cuda.synchronize()
+    b_loss, b_nll, b_g = float(wk.loss_buf[1]), float(wk.loss_buf[65]), wk.G.cpu().numpy().copy()
+    assert abs(a_loss - b_loss) / abs(b_loss) < 1e-6 and abs(a_nll - b_nll) / abs(b_nll) < 1e-6
+    tol = 1e-6 if compute == "fp32" else 2e-3          # bf16: the weight-gradient GEMM of the projection splits K differently
+    compare_flat(S.param_layout(ocfg), a_g, b_g, tol, "real rows vs all rows")
+    ol, on, og, _, _ = S.micro_batch_grad(ocfg, theta.astype(np.float64), mb, 0.1)
+    assert abs(b_loss - ol) / abs(ol) < TOL[compute]
+    compare_flat(S.param_layout(ocfg), b_g, og, TOL[compute], "all rows vs oracle", rounded_weights_grad(ocfg, theta, mb) if compute == "bf16" else None)
+    with pytest.raises(hs.HsError):      # host lengths outside [1, Lt]
+        hs.hs_s2s_loss(wk.ctx, wk.w_compute, wk._out, d["tgt_out"], d["tgt_lens"], np.array([20, 33, 7, 3, 1, 32], np.int32), 6, 32, 0.1,
+                       wk.loss_buf, None, wk._dout, wk.G, 0, wk._ws, wk._ws_bytes)
     wk.close()
