@@ -14,9 +14,13 @@
  * Conventions (all calls):
  *  - "dev" pointers are device (HBM) addresses, "host" pointers are host addresses.
  *  - The caller owns every buffer and the stream.  The library allocates no device memory and
- *    keeps no pointer after a call returns; hs_ctx holds host state only.
+ *    keeps no pointer after a call returns; hs_ctx holds host state only: tables, the error text,
+ *    and the handles of up to two further HIP streams (default priority) with the events that
+ *    order them, created on first use and destroyed with the context.
  *  - Device calls enqueue on `stream` (a hipStream_t passed as void*; NULL = the default stream)
- *    and return without synchronising.  Results are valid once the caller synchronises.
+ *    and return without synchronising.  Results are valid once the caller synchronises that
+ *    stream: work a call puts on the context's own streams is joined to `stream` before it returns.
+ *    Calls on one context must not overlap in time from different host threads.
  *  - Errors are return codes.  Arguments and shapes are checked on the host before any launch;
  *    a call that fails launches nothing.  hs_last_error() gives the reason as text.
  *  - Matrices are row-major.  Weights are [out, in] (y = x W^T + b).  The flat parameter order
