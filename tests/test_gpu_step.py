@@ -190,6 +190,35 @@ def test_workload1_bert_base_full_size(W, base):
     worker.close()
 
 
+def test_workload1_three_updates_follow_oracle_bf16(W, base):
+    """Three whole steps at full size (forward, loss, backward with the update armed inside it, bf16 weight copy): the
+    reported loss of every step against the oracle's fp32 loop, and the weights after the third."""
+    model, ocfg, layout = base
+    wl = synth.WORKLOADS[1]
+    theta = synth.init_params(layout, wl["seed"])
+    adam = dict(wl["adam"], lr=1e-3)        # ten times the paper's rate, so that three updates move the loss visibly
+    worker = W(model, "bf16", theta)
+    th, m, v = theta.copy(), np.zeros_like(theta), np.zeros_like(theta)
+    got, want = [], []
+    for t in range(1, 4):
+        mbs = synth.step_micro_batches(wl["seed"], t, [128] * 64, 128, model["vocab"], "zipf")
+        D = worker.train_step([worker.upload(mb) for mb in mbs], adam)
+        got.append(worker.reported_loss(D))
+        oloss, oG, oD = O.train_step(ocfg, th, m, v, t, mbs, **adam)
+        want.append(float(oloss))
+        print(f"update {t}: loss {got[-1]:.4f} (oracle {want[-1]:.4f})", flush=True)
+        assert oD == D and abs(got[-1] - want[-1]) / abs(want[-1]) < TOL["bf16"]
+    assert want[2] < want[0] - 0.5                     # the updates do change the model
+    # Adam moves every weight by about lr per step whatever the size of its gradient, so where a gradient is within bf16
+    # noise of zero the two sides may step in opposite directions: the weights are compared on the scale of the movement
+    w_gpu = worker.w.cpu().numpy()
+    moved = float(np.linalg.norm(th.astype(np.float64) - theta))
+    apart = float(np.linalg.norm(w_gpu.astype(np.float64) - th))
+    print(f"weights moved {moved:.3f} (L2), the two sides are {apart:.3f} apart: {apart / moved:.3f} of the movement")
+    assert apart < 0.25 * moved
+    worker.close()
+
+
 def test_workload3_unequal_shares_equal_one_batch(W, base):
     """Micro-batches of 8, 24 and 56 sequences summed and divided by 88 against one batch of 88."""
     model, ocfg, layout = base
