@@ -369,3 +369,34 @@ def test_projection_over_real_rows_only_equals_projection_over_all_rows(hs, comp
         hs.hs_s2s_loss(wk.ctx, wk.w_compute, wk._out, d["tgt_out"], d["tgt_lens"], np.array([20, 33, 7, 3, 1, 32], np.int32), 6, 32, 0.1,
                        wk.loss_buf, None, wk._dout, wk.G, 0, wk._ws, wk._ws_bytes)
     wk.close()
+
+
+def test_full_size_three_updates_with_dropout_follow_oracle_bf16(hs):
+    """Three whole steps of the Transformer-base model on the benchmark batch with the paper's dropout of 0.1 (masks numbered
+    over the whole batch while the forward pass runs as two halves): the loss of every step against the oracle's loop."""
+    import bench
+    model = synth.S2S_MODELS["transformer_base"]
+    ocfg = S.S2SCfg(**model)
+    theta = synth.init_params(S.param_layout(ocfg), 1240)
+    from paper_2009_14783_amd.step import PairWorker
+    wk = PairWorker(model, "bf16", theta)
+    th, m, v = theta.copy(), np.zeros_like(theta), np.zeros_like(theta)
+    first = None
+    for t in range(1, 4):
+        mb = bench.pair_workload(synth, seed=1240 + t)
+        mb["drop"] = dict(p=0.1, seed=1240, stream=t)
+        D = wk.train_step([wk.upload(mb)], ADAM)
+        loss, nll = wk.reported_loss(D)
+        ol, on, g, _, n_tok = S.micro_batch_grad(ocfg, th, mb, 0.1)
+        assert D == n_tok
+        O.normalize(g, n_tok)
+        O.adam_step(th, m, v, g, t, **ADAM)
+        print(f"update {t}: loss per token {loss:.4f} (oracle {ol / n_tok:.4f}), nll {nll:.4f} (oracle {on / n_tok:.4f})", flush=True)
+        assert abs(loss - ol / n_tok) / abs(ol / n_tok) < 2e-2 and abs(nll - on / n_tok) / abs(on / n_tok) < 2e-2
+        first = first if first is not None else ol / n_tok
+    assert ol / n_tok < first - 0.3                    # the updates do change the model
+    w_gpu = wk.w.cpu().numpy().astype(np.float64)
+    moved, apart = float(np.linalg.norm(th - theta.astype(np.float64))), float(np.linalg.norm(w_gpu - th))
+    print(f"weights moved {moved:.3f} (L2), the two sides are {apart:.3f} apart: {apart / moved:.3f} of the movement")
+    assert apart < 0.25 * moved
+    wk.close()
