@@ -361,7 +361,8 @@ def main():
                ms_per_step=ms_per_step, higher_is_better=True, scaling="weak", vs_baseline=None, dtype="bf16",
                data="synthetic",
                config=dict(workload=shape_text + ", Zipf(1.1) ids, 15% MLM targets, bf16 compute with fp32 master weights and accumulation",
-                           tokens_per_step=tokens_per_step, mlm_targets=int(sum(d["M"] for d in last)),
+                           tokens_per_step=int(tokens_per_step) if float(tokens_per_step).is_integer() else tokens_per_step,
+                           mlm_targets=int(sum(d["M"] for d in last)),
                            global_batch=D, seq_len=int(last[0]["L"]), params=P, dropout=args.dropout),
                whole_step_tflops=flops_per_step / (ms_per_step * 1e-3) / 1e12,
                whole_step_mfma_frac=flops_per_step / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
