@@ -401,6 +401,17 @@ hs_status hs_op_layernorm_bwd(int32_t dtype, const void* dy, const void* x, cons
                               const void* gain, void* dx, float* d_gain, float* d_bias, float* d_colsum,
                               float beta, int32_t R, int32_t H, void* partials, void* stream);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc): hs_op_layernorm_bwd with the same arguments, results and kernels, except
+ * that the per-block partial column sums go to a 9437184-byte array built into the library (one copy per GPU,
+ * held until the process ends) instead of a caller buffer.  Allocates nothing.  Limits: H a multiple of 64 and
+ * <= 1024, R <= 2^24 (HS_ERR_SHAPE beyond).  Every call on one GPU uses that GPU's one array: calls that
+ * overlap in time on one GPU (different streams or threads) race; order them.  Nothing in the array has to
+ * start at zero: a call overwrites what it reads. */
+hs_status hs_op_layernorm_bwd_noalloc(int32_t dtype, const void* dy, const void* x, const float* stats,
+                                      const void* gain, void* dx, float* d_gain, float* d_bias, float* d_colsum,
+                                      float beta, int32_t R, int32_t H, void* stream);
+
 /* Attention over qkv [B*L, 3H] (per row: query | key | value, head h at columns h*64..h*64+63 of
  * each third): ctx [B*L, H], lse [B, A, L] float (log-sum-exp of the scaled, masked scores). */
 hs_status hs_op_attention_fwd(int32_t dtype, const void* qkv, const int32_t* lens, int32_t B, int32_t L,

@@ -89,6 +89,7 @@ _SIGNATURES = {
     "hs_op_layernorm_fwd": (_I32, [_I32, _P, _P, _P, _P, _P, _I32, _I32, _F, _P]),
     "hs_op_layernorm_bwd_scratch": (_SZ, [_I32, _I32]),
     "hs_op_layernorm_bwd": (_I32, [_I32, _P, _P, _P, _P, _P, _P, _P, _P, _F, _I32, _I32, _P, _P]),
+    "hs_op_layernorm_bwd_noalloc": (_I32, [_I32, _P, _P, _P, _P, _P, _P, _P, _P, _F, _I32, _I32, _P]),
     "hs_op_attention_fwd": (_I32, [_I32, _P, _P, _I32, _I32, _I32, _P, _P, _P]),
     "hs_op_attention_bwd": (_I32, [_I32, _P, _P, _P, _P, _P, _I32, _I32, _I32, _P, _P, _P]),
     "hs_s2s_ctx_create": (_I32, [C.POINTER(hs_s2s_cfg), C.POINTER(_P)]),
@@ -367,6 +368,11 @@ def hs_op_layernorm_bwd_scratch(R, H) -> int:
 def hs_op_layernorm_bwd(dtype, dy, x, stats, gain, dx, d_gain, d_bias, d_colsum, beta, R, H, partials, stream=None):
     _check(lib().hs_op_layernorm_bwd(dtype, _ptr(dy), _ptr(x), _ptr(stats), _ptr(gain), _ptr(dx), _ptr(d_gain), _ptr(d_bias),
                                      _ptr(d_colsum), beta, R, H, _ptr(partials), _stream(stream)))
+
+
+def hs_op_layernorm_bwd_noalloc(dtype, dy, x, stats, gain, dx, d_gain, d_bias, d_colsum, beta, R, H, stream=None):
+    _check(lib().hs_op_layernorm_bwd_noalloc(dtype, _ptr(dy), _ptr(x), _ptr(stats), _ptr(gain), _ptr(dx), _ptr(d_gain),
+                                             _ptr(d_bias), _ptr(d_colsum), beta, R, H, _stream(stream)))
 
 
 def hs_op_attention_fwd(dtype, qkv, lens, B, L, A, ctx_out, lse, stream=None):

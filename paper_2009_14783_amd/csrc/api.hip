@@ -2,6 +2,7 @@
 // head), encoder backward; plus the exported building blocks.  Host orchestration only: every
 // arithmetic step is a kernel in gemm.hip / attention.hip / rowops.hip.
 #include "common.h"
+#include <mutex>
 
 namespace {
 
@@ -525,6 +526,47 @@ hs_status hs_op_layernorm_bwd(int32_t dtype, const void* dy, const void* x, cons
   if (!ln_shape_ok(R, H)) return hs_fail(nullptr, HS_ERR_SHAPE, "hs_op_layernorm_bwd: H must be a multiple of 64, <= 1024");
   if (R > 0 && (!dy || !x || !stats || !gain || !dx || !partials)) return hs_fail(nullptr, HS_ERR_INVALID_ARG, "hs_op_layernorm_bwd: NULL buffer");
   return launch_layernorm_bwd(nullptr, dtype, dy, x, stats, gain, dx, d_gain, d_bias, d_colsum, beta, R, H, partials, (hipStream_t)stream);
+}
+
+// ---- LayerNorm backward for callers that cannot allocate ---------------------------------------------
+// Same kernels as hs_op_layernorm_bwd; the per-block partial column sums live in this file-scope array
+// instead of a caller buffer.  Each GPU holds its own copy at its own address, resolved once per device.
+namespace {
+constexpr int kNoAllocMaxRows = 1 << 24, kNoAllocMaxH = 1024;
+constexpr size_t kNoAllocFloats = (size_t)768 * 3 * kNoAllocMaxH;      // 768 = most blocks the row kernel ever uses
+static __device__ __align__(256) float scratch[kNoAllocFloats];        // 9 MiB per GPU, held until the process ends
+constexpr int kMaxDevices = 64;
+float* scratch_ptr[kMaxDevices] = {};                                    // device address of `scratch`, per device
+std::mutex scratch_mu;
+}  // namespace
+
+hs_status hs_op_layernorm_bwd_noalloc(int32_t dtype, const void* dy, const void* x, const float* stats, const void* gain, void* dx,
+                                      float* d_gain, float* d_bias, float* d_colsum, float beta, int32_t R, int32_t H, void* stream) {
+  if (dtype != HS_FP32 && dtype != HS_BF16) return hs_fail(nullptr, HS_ERR_INVALID_ARG, "hs_op_layernorm_bwd_noalloc: bad dtype");
+  if (!ln_shape_ok(R, H) || H > kNoAllocMaxH || R > kNoAllocMaxRows)
+    return hs_fail(nullptr, HS_ERR_SHAPE, "hs_op_layernorm_bwd_noalloc: needs H a multiple of 64 and <= 1024, R <= 2^24 (the built-in scratch is sized for that)");
+  if (layernorm_bwd_scratch(R, H) > sizeof(float) * kNoAllocFloats)
+    return hs_fail(nullptr, HS_ERR_SHAPE, "hs_op_layernorm_bwd_noalloc: (R, H) needs more than the built-in scratch of 9437184 bytes");
+  if (R > 0 && (!dy || !x || !stats || !gain || !dx)) return hs_fail(nullptr, HS_ERR_INVALID_ARG, "hs_op_layernorm_bwd_noalloc: NULL buffer");
+  if (R == 0) return HS_OK;
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return hs_fail(nullptr, HS_ERR_HIP, std::string("hs_op_layernorm_bwd_noalloc: hipGetDevice: ") + hipGetErrorString(e));
+  if (dev < 0 || dev >= kMaxDevices) return hs_fail(nullptr, HS_ERR_STATE, "hs_op_layernorm_bwd_noalloc: device index out of range");
+  float* part = nullptr;
+  {
+    std::lock_guard<std::mutex> lock(scratch_mu);
+    if (!scratch_ptr[dev]) {
+      void* p = nullptr;
+      e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+      if (e != hipSuccess || !p)
+        return hs_fail(nullptr, HS_ERR_HIP, std::string("hs_op_layernorm_bwd_noalloc: hipGetSymbolAddress: ") + hipGetErrorString(e));
+      scratch_ptr[dev] = (float*)p;
+    }
+    part = scratch_ptr[dev];
+  }
+  // The row kernel writes every partial that the column kernel reads, so nothing has to start at zero.
+  return launch_layernorm_bwd(nullptr, dtype, dy, x, stats, gain, dx, d_gain, d_bias, d_colsum, beta, R, H, part, (hipStream_t)stream);
 }
 
 hs_status hs_op_attention_fwd(int32_t dtype, const void* qkv, const int32_t* lens, int32_t B, int32_t L, int32_t A, void* ctx_out,
