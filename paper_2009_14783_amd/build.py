@@ -10,16 +10,21 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libhetseq_hip.so")
-SOURCES = ["context.cpp", "dataset.cpp", "gemm.hip", "attention.hip", "attention_mfma.hip", "attention_general.hip", "rowops.hip", "seq2seq_ops.hip", "seq2seq.hip", "optim.hip", "api.hip"]
+SOURCES = ["context.cpp", "dataset.cpp", "gemm.hip", "gemm_wide_kk.hip", "gemm_wide_kn.hip", "gemm_wide_nn.hip", "attention.hip", "attention_mfma.hip", "attention_general.hip", "rowops.hip", "seq2seq_ops.hip", "seq2seq.hip", "optim.hip", "api.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-x", "hip",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-result", "-I" + os.path.join(ROOT, "include"), "-I" + CSRC]
 
 
+# The wide-tile GEMM kernels unroll their epilogues over up to 16 accumulator tiles; above the compiler's default
+# budget for "#pragma unroll" the loop would stay rolled and the accumulators would live in scratch memory.
+EXTRA = {src: ["-mllvm", "-pragma-unroll-threshold=200000"] for src in ("gemm_wide_kk.hip", "gemm_wide_kn.hip", "gemm_wide_nn.hip")}
+
+
 def _compile(src: str, objdir: str) -> str:
     obj = os.path.join(objdir, os.path.splitext(src)[0] + ".o")
-    cmd = [HIPCC] + FLAGS + ["-c", os.path.join(CSRC, src), "-o", obj]
+    cmd = [HIPCC] + FLAGS + EXTRA.get(src, []) + ["-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"hipcc failed on {src}:\n{r.stdout}\n{r.stderr}")

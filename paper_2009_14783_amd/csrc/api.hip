@@ -73,7 +73,7 @@ HeadWs carve_head(const hs_model_cfg& c, int M, void* base) {
 struct BwdWs {
   // dy2, dy1, dh and dqkv exist twice (by layer parity): the weight-gradient GEMMs that read them run
   // on a second stream and may still be in flight while the next layer produces its own
-  void *dxa, *dxb, *dy2[2], *dy1[2], *dy2m[2], *dy1m[2], *dh[2], *dqkv[2], *dctx, *ln_part, *ln_part2[2], *ln_part1[2], *cs_part, *emb, *gemm_ws, *gemm_ws_side;
+  void *dxa, *dxb, *dy2[2], *dy1[2], *dy2m[2], *dy1m[2], *dh[2], *dqkv[2], *dctx, *ln_part, *ln_part2[2], *ln_part1[2], *cs_part, *emb, *gemm_ws, *gemm_ws_side, *ones;
   float* dvec;
   size_t total, gemm_ws_bytes;
 };
@@ -98,6 +98,7 @@ BwdWs carve_bwd(const hs_model_cfg& c, int B, int L, void* base) {
   w.gemm_ws_bytes = gemm_scratch_bytes(c);
   w.gemm_ws = cv.take(w.gemm_ws_bytes);
   w.gemm_ws_side = cv.take(w.gemm_ws_bytes);
+  w.ones = cv.take(T * 8 * es);          // [T, 8] of 1.0: bias gradients as products with a column of ones
   w.total = cv.off;
   return w;
 }
@@ -418,6 +419,9 @@ static hs_status encoder_bwd_impl(hs_ctx* ctx, const hs_ctx::Armed& upd, const v
   };
   auto side_gemm = [&](GemmArgs& a) { a.ws = ws.gemm_ws_side; a.ws_bytes = ws.gemm_ws_bytes; a.c_f32 = 1; a.beta = beta; return launch_gemm(ctx, a, sd); };
 
+  // bf16: the weight gradients of a layer go out as one grouped launch once the layer's last operand (d qkv) exists
+  const bool grouped = dt == HS_BF16;
+  if (grouped) HS_TRY(launch_fill_value(ctx, dt, ws.ones, (size_t)T * 8, 1.0f, s));
   const void* dcur = d_hidden;
   for (int i = NL - 1; i >= 0; --i) {
     const LayerOff& lo = o.layer[i];
@@ -433,20 +437,24 @@ static hs_status encoder_bwd_impl(hs_ctx* ctx, const hs_ctx::Armed& upd, const v
     // LN2 backward: dy2 on the main chain; d gain/bias and colsum(dy2) = d b2 from its partials beside it
     HS_TRY(launch_layernorm_bwd_rows(ctx, dt, dcur, la.y2, la.st2, W(ctx, w, lo.ln2_g), dy2, T, H, ws.ln_part2[par], s, drop,
                                      site_ffn_out(i), drop ? 2 : 0, dy2b));
-    HS_TRY(hand_over(i, 0));
-    HS_TRY(launch_layernorm_bwd_cols(ctx, ws.ln_part2[par], g + lo.ln2_g, g + lo.ln2_b, g + lo.ffn2_b, beta, T, H, sd));
+    if (!grouped) {
+      HS_TRY(hand_over(i, 0));
+      HS_TRY(launch_layernorm_bwd_cols(ctx, ws.ln_part2[par], g + lo.ln2_g, g + lo.ln2_b, g + lo.ffn2_b, beta, T, H, sd));
+    }
     // dW2 [H,F] = dy2^T h
-    GemmArgs ga = gemm_args(dt, 0, 0, H, F, T, dy2b, H, la.h, F, g + lo.ffn2_w, F);
-    HS_TRY(side_gemm(ga));
+    GemmArgs gw2 = gemm_args(dt, 0, 0, H, F, T, dy2b, H, la.h, F, g + lo.ffn2_w, F);
+    if (!grouped) HS_TRY(side_gemm(gw2));
     // dhpre [T,F] = (dy2 W2) * GELU'(hpre)
-    ga = gemm_args(dt, 1, 0, T, F, H, dy2b, H, W(ctx, w, lo.ffn2_w), F, dh, F);
+    GemmArgs ga = gemm_args(dt, 1, 0, T, F, H, dy2b, H, W(ctx, w, lo.ffn2_w), F, dh, F);
     ga.epi = 3; ga.aux = la.hpre; ga.ldaux = F;
     HS_TRY(run_gemm(ga));
-    HS_TRY(hand_over(i, 1));
-    HS_TRY(launch_colsum(ctx, dt, dh, F, T, F, g + lo.ffn1_b, beta, ws.cs_part, sd));
+    if (!grouped) {
+      HS_TRY(hand_over(i, 1));
+      HS_TRY(launch_colsum(ctx, dt, dh, F, T, F, g + lo.ffn1_b, beta, ws.cs_part, sd));
+    }
     // dW1 [F,H] = dhpre^T x1
-    ga = gemm_args(dt, 0, 0, F, H, T, dh, F, la.x1, H, g + lo.ffn1_w, H);
-    HS_TRY(side_gemm(ga));
+    GemmArgs gw1 = gemm_args(dt, 0, 0, F, H, T, dh, F, la.x1, H, g + lo.ffn1_w, H);
+    if (!grouped) HS_TRY(side_gemm(gw1));
     // dx1 [T,H] = dhpre W1 + dy2
     ga = gemm_args(dt, 1, 0, T, H, F, dh, F, W(ctx, w, lo.ffn1_w), H, ws.dxa, H);
     ga.epi = 1; ga.aux = dy2; ga.ldaux = H;
@@ -454,20 +462,35 @@ static hs_status encoder_bwd_impl(hs_ctx* ctx, const hs_ctx::Armed& upd, const v
     // LN1 backward: dy1, d gain/bias, colsum(dy1) = d bo
     HS_TRY(launch_layernorm_bwd_rows(ctx, dt, ws.dxa, la.y1, la.st1, W(ctx, w, lo.ln1_g), dy1, T, H, ws.ln_part1[par], s, drop,
                                      site_attention_out(i), drop ? 2 : 0, dy1b));
-    HS_TRY(hand_over(i, 2));
-    HS_TRY(launch_layernorm_bwd_cols(ctx, ws.ln_part1[par], g + lo.ln1_g, g + lo.ln1_b, g + lo.o_b, beta, T, H, sd));
+    if (!grouped) {
+      HS_TRY(hand_over(i, 2));
+      HS_TRY(launch_layernorm_bwd_cols(ctx, ws.ln_part1[par], g + lo.ln1_g, g + lo.ln1_b, g + lo.o_b, beta, T, H, sd));
+    }
     // dWo [H,H] = dy1^T ctx ; dctx = dy1 Wo
-    ga = gemm_args(dt, 0, 0, H, H, T, dy1b, H, la.ctx, H, g + lo.o_w, H);
-    HS_TRY(side_gemm(ga));
+    GemmArgs gwo = gemm_args(dt, 0, 0, H, H, T, dy1b, H, la.ctx, H, g + lo.o_w, H);
+    if (!grouped) HS_TRY(side_gemm(gwo));
     ga = gemm_args(dt, 1, 0, T, H, H, dy1b, H, W(ctx, w, lo.o_w), H, ws.dctx, H);
     HS_TRY(run_gemm(ga));
     HS_TRY(launch_attention_bwd(ctx, dt, la.qkv, la.ctx, la.lse, ws.dctx, lens, B, L, c.n_heads, dqkv, ws.dvec, s, drop,
                                 site_attention_prob(i)));
     HS_TRY(hand_over(i, 3));
-    HS_TRY(launch_colsum(ctx, dt, dqkv, 3 * H, T, 3 * H, g + lo.qkv_b, beta, ws.cs_part, sd));
     // dWqkv [3H,H] = dqkv^T x_in ; dx_in = dqkv Wqkv + dy1
-    ga = gemm_args(dt, 0, 0, 3 * H, H, T, dqkv, 3 * H, x_in, H, g + lo.qkv_w, H);
-    HS_TRY(side_gemm(ga));
+    GemmArgs gwq = gemm_args(dt, 0, 0, 3 * H, H, T, dqkv, 3 * H, x_in, H, g + lo.qkv_w, H);
+    if (!grouped) {
+      HS_TRY(launch_colsum(ctx, dt, dqkv, 3 * H, T, 3 * H, g + lo.qkv_b, beta, ws.cs_part, sd));
+      HS_TRY(side_gemm(gwq));
+    } else {
+      // Every weight gradient of the layer, and the two bias gradients that are not by-products of a LayerNorm
+      // backward (as products with a column of ones), in ONE launch on the second stream: 237 tiles of 256 x 128 for
+      // 256 CUs at BERT-base size, each over the whole contraction, so no partial sums travel through memory.
+      HS_TRY(launch_layernorm_bwd_cols(ctx, ws.ln_part2[par], g + lo.ln2_g, g + lo.ln2_b, g + lo.ffn2_b, beta, T, H, sd));
+      HS_TRY(launch_layernorm_bwd_cols(ctx, ws.ln_part1[par], g + lo.ln1_g, g + lo.ln1_b, g + lo.o_b, beta, T, H, sd));
+      GemmArgs gb1 = gemm_args(dt, 0, 0, F, 1, T, dh, F, ws.ones, 8, g + lo.ffn1_b, 1);
+      GemmArgs gbq = gemm_args(dt, 0, 0, 3 * H, 1, T, dqkv, 3 * H, ws.ones, 8, g + lo.qkv_b, 1);
+      GemmArgs group[6] = {gw2, gw1, gwq, gwo, gb1, gbq};
+      for (GemmArgs& a : group) { a.c_f32 = 1; a.beta = beta; }
+      HS_TRY(launch_gemm_group(ctx, group, 6, sd));
+    }
     if (overlap) HS_HIP_CHECK(ctx, hipEventRecord(ev(i, 4), sd));
     ga = gemm_args(dt, 1, 0, T, H, 3 * H, dqkv, 3 * H, W(ctx, w, lo.qkv_w), H, ws.dxb, H);
     ga.epi = 1; ga.aux = dy1; ga.ldaux = H;

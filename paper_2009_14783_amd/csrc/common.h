@@ -205,6 +205,9 @@ struct GemmArgs {
   const DropCfg* drop; uint32_t drop_site;   // optional (epi == 1): dropout of product + bias before the residual
 };
 hs_status launch_gemm(hs_ctx* ctx, const GemmArgs& g, hipStream_t s);
+// up to 8 weight-gradient products (A m-major, B n-major, fp32 C = beta C + product) in one launch; other argument
+// sets run one by one
+hs_status launch_gemm_group(hs_ctx* ctx, const GemmArgs* gs, int n, hipStream_t s);
 
 // stats: R means, then (stat_ld floats after the first mean; default R) R reciprocal standard deviations
 hs_status launch_layernorm_fwd(hs_ctx* ctx, int dtype, const void* x, const void* gain, const void* bias, void* y,
@@ -239,6 +242,7 @@ hs_status launch_colsum(hs_ctx* ctx, int dtype, const void* x, int64_t ldx, int 
 hs_status launch_gather_rows(hs_ctx* ctx, int dtype, const void* src, const int32_t* idx, int M, int H, void* dst, hipStream_t s);
 hs_status launch_scatter_rows(hs_ctx* ctx, int dtype, const void* src, const int32_t* idx, int M, int H, void* dst, hipStream_t s);
 hs_status launch_fill_zero(hs_ctx* ctx, void* p, size_t bytes, hipStream_t s);
+hs_status launch_fill_value(hs_ctx* ctx, int dtype, void* p, size_t n, float value, hipStream_t s);   // n elements of the activation type
 hs_status launch_gelu_fwd(hs_ctx* ctx, int dtype, const void* x, void* y, size_t n, hipStream_t s);
 hs_status launch_gelu_bwd(hs_ctx* ctx, int dtype, const void* dy, const void* pre, void* dx, size_t n, hipStream_t s);
 // Attention with separate query and key/value sequences (attention_general.hip).  Row b*Lq + i of q (stride ldq) is

@@ -3,298 +3,14 @@
 //         contraction index is NOT the contiguous one are staged in their natural layout and read
 //         with the LDS transpose read of gfx950, so every global and LDS access is 16/8 bytes wide.
 //   fp32: plain tiled SIMT kernel (small reference-precision configurations only).
-#include "common.h"
+#include "gemm_dev.h"
+
+hipError_t gemm_wide_launch_kk(int cfg, const GemmDev& p, int splits, hipStream_t s);
+hipError_t gemm_wide_launch_kn(int cfg, const GemmDev& p, int splits, hipStream_t s);
+hipError_t gemm_wide_launch_nn(int cfg, const GemmDev& p, int splits, hipStream_t s);
+hipError_t gemm_wide_group_launch_nn(const GemmGroupDev& g, hipStream_t s);
 
 namespace {
-
-struct GemmDev {
-  const void* A; const void* B; void* C; void* C2; const void* bias; const void* aux;
-  int64_t lda, ldb, ldc, ldaux;
-  int M, N, K;
-  int c_f32, epi;
-  float beta;
-  float* partial;      // split-K partial sums [splits][M][N], or null
-  int k_per_split;     // multiple of the k-tile
-  DropCfg drop;        // dropout of (product + bias) before the residual is added (epi == 1 only; thr == 0: off)
-  uint32_t drop_site;  // element index of the site = row * N + col
-};
-
-// dropout factors of n (4 or 8) consecutive output columns of one row, starting at a column that is a
-// multiple of 4: one generator block per four columns when the row length allows it
-template <int NV>
-__device__ __forceinline__ void drop_row_factors(const GemmDev& p, int row, int col, float (&f)[NV]) {
-  const uint64_t e = (uint64_t)row * (uint64_t)p.N + (uint64_t)col;
-  if ((p.N & 3) == 0) {
-#pragma unroll
-    for (int q = 0; q < NV / 4; ++q) {
-      float t[4];
-      drop_factors4(p.drop, p.drop_site, (e >> 2) + q, t);
-      f[4 * q] = t[0]; f[4 * q + 1] = t[1]; f[4 * q + 2] = t[2]; f[4 * q + 3] = t[3];
-    }
-  } else {
-#pragma unroll
-    for (int t = 0; t < NV; ++t) f[t] = drop_factor1(p.drop, p.drop_site, e + t);
-  }
-}
-__device__ __forceinline__ float drop_elem(const GemmDev& p, int row, int col) {
-  return drop_factor1(p.drop, p.drop_site, (uint64_t)row * (uint64_t)p.N + (uint64_t)col);
-}
-
-template <class T>
-__device__ __forceinline__ void epilogue_store(const GemmDev& p, int row, int col, float v) {
-  if (row >= p.M || col >= p.N) return;
-  if (p.bias) v += to_f(((const T*)p.bias)[col]);
-  if (p.epi == 1 && p.drop.thr) v *= drop_elem(p, row, col);
-  if (p.epi == 1) v += to_f(((const T*)p.aux)[(int64_t)row * p.ldaux + col]);
-  else if (p.epi == 3) v *= gelu_grad_f(to_f(((const T*)p.aux)[(int64_t)row * p.ldaux + col]));
-  const int64_t o = (int64_t)row * p.ldc + col;
-  if (p.c_f32) {
-    float* C = (float*)p.C;
-    C[o] = (p.beta != 0.0f) ? p.beta * C[o] + v : v;
-  } else {
-    ((T*)p.C)[o] = from_f<T>(v);
-    if (p.epi == 2) ((T*)p.C2)[o] = from_f<T>(gelu_f(v));
-  }
-}
-
-// ------------------------------------------------------------------------------------------
-// bf16 MFMA kernel
-// ------------------------------------------------------------------------------------------
-enum { EPI_PARTIAL = 0, EPI_F32, EPI_ACT, EPI_ACT_RES, EPI_ACT_GELU, EPI_ACT_DGELU };
-
-// One group of four consecutive output columns of one row: bias, epilogue, store.  `vec` says that
-// all four columns exist and every pointer involved is aligned for a 4-element access.
-template <int MODE>
-__device__ __forceinline__ void store_quad(const GemmDev& p, int row, int col, float4 v, bool vec, int split) {
-  const bf16* bias = (const bf16*)p.bias;
-  const bf16* aux = (const bf16*)p.aux;
-  if (vec) {
-    if (MODE != EPI_PARTIAL && bias) {
-      const bf16x4 b = *(const bf16x4*)(bias + col);
-      v.x += (float)b[0]; v.y += (float)b[1]; v.z += (float)b[2]; v.w += (float)b[3];
-    }
-    if (MODE == EPI_PARTIAL) {
-      *(float4*)(p.partial + ((int64_t)split * p.M + row) * p.N + col) = v;
-    } else if (MODE == EPI_F32) {
-      float4* C = (float4*)((float*)p.C + (int64_t)row * p.ldc + col);
-      if (p.beta != 0.0f) { const float4 o = *C; v.x += p.beta * o.x; v.y += p.beta * o.y; v.z += p.beta * o.z; v.w += p.beta * o.w; }
-      *C = v;
-    } else {
-      const int64_t o = (int64_t)row * p.ldc + col;
-      if (MODE == EPI_ACT_RES && p.drop.thr) {
-        float f[4];
-        drop_row_factors<4>(p, row, col, f);
-        v.x *= f[0]; v.y *= f[1]; v.z *= f[2]; v.w *= f[3];
-      }
-      if (MODE == EPI_ACT_RES || MODE == EPI_ACT_DGELU) {
-        const bf16x4 a = *(const bf16x4*)(aux + (int64_t)row * p.ldaux + col);
-        if (MODE == EPI_ACT_RES) { v.x += (float)a[0]; v.y += (float)a[1]; v.z += (float)a[2]; v.w += (float)a[3]; }
-        else { v.x *= gelu_grad_fast((float)a[0]); v.y *= gelu_grad_fast((float)a[1]); v.z *= gelu_grad_fast((float)a[2]); v.w *= gelu_grad_fast((float)a[3]); }
-      }
-      bf16x4 c;
-      c[0] = (bf16)v.x; c[1] = (bf16)v.y; c[2] = (bf16)v.z; c[3] = (bf16)v.w;
-      *(bf16x4*)((bf16*)p.C + o) = c;
-      if (MODE == EPI_ACT_GELU) {
-        bf16x4 g;
-        g[0] = (bf16)gelu_fast(v.x); g[1] = (bf16)gelu_fast(v.y); g[2] = (bf16)gelu_fast(v.z); g[3] = (bf16)gelu_fast(v.w);
-        *(bf16x4*)((bf16*)p.C2 + o) = g;
-      }
-    }
-  } else {
-    const float e[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-    for (int t = 0; t < 4; ++t) {
-      if (col + t >= p.N) break;
-      float x = e[t];
-      if (MODE == EPI_PARTIAL) { p.partial[((int64_t)split * p.M + row) * p.N + col + t] = x; continue; }
-      if (bias) x += (float)bias[col + t];
-      if (MODE == EPI_F32) {
-        float* C = (float*)p.C + (int64_t)row * p.ldc + col + t;
-        *C = (p.beta != 0.0f) ? p.beta * *C + x : x;
-      } else {
-        const int64_t o = (int64_t)row * p.ldc + col + t;
-        if (MODE == EPI_ACT_RES && p.drop.thr) x *= drop_elem(p, row, col + t);
-        if (MODE == EPI_ACT_RES) x += (float)aux[(int64_t)row * p.ldaux + col + t];
-        if (MODE == EPI_ACT_DGELU) x *= gelu_grad_fast((float)aux[(int64_t)row * p.ldaux + col + t]);
-        ((bf16*)p.C)[o] = (bf16)x;
-        if (MODE == EPI_ACT_GELU) ((bf16*)p.C2)[o] = (bf16)gelu_fast(x);
-      }
-    }
-  }
-}
-
-// whether 4-element accesses are aligned for everything this mode touches
-template <int MODE>
-__device__ __forceinline__ bool quad_aligned(const GemmDev& p) {
-  if (MODE == EPI_PARTIAL) return (p.N & 3) == 0;
-  bool ok = (p.ldc & 3) == 0 && ((uintptr_t)p.C & 15) == 0;
-  if (p.bias) ok = ok && ((uintptr_t)p.bias & 7) == 0;
-  if (MODE == EPI_ACT_RES || MODE == EPI_ACT_DGELU) ok = ok && (p.ldaux & 3) == 0 && ((uintptr_t)p.aux & 7) == 0;
-  if (MODE == EPI_ACT_GELU) ok = ok && ((uintptr_t)p.C2 & 7) == 0;
-  return ok;
-}
-
-// Writes the TI x TJ grid of 32x32 result tiles of one wave.  Register r of lane l of a tile is
-// row 8*(r/4) + 4*(l/32) + r%4, column l%32: one store instruction covers 64 contiguous bytes of two
-// rows (measured faster than 8-byte pieces of 32 rows from transposed tiles).
-template <int MODE, int TI, int TJ>
-__device__ __forceinline__ void tile_epilogue(const GemmDev& p, const f32x16 (&acc)[TI][TJ], int rbase, int cbase, int lane, int split) {
-  const bf16* bias = (const bf16*)p.bias;
-  float bv[TJ];
-  bool col_ok[TJ];
-#pragma unroll
-  for (int j = 0; j < TJ; ++j) {
-    const int col = cbase + j * 32 + (lane & 31);
-    col_ok[j] = col < p.N;
-    bv[j] = (MODE != EPI_PARTIAL && bias && col_ok[j]) ? (float)bias[col] : 0.f;
-  }
-  const int col0 = cbase + (lane & 31);
-#pragma unroll
-  for (int i = 0; i < TI; ++i) {
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const int row = rbase + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-      if (row < p.M) {
-        // row offsets are computed once per row and used for the TJ columns of this lane
-        const int64_t oc = (MODE == EPI_PARTIAL) ? ((int64_t)split * p.M + row) * p.N + col0 : (int64_t)row * p.ldc + col0;
-        const int64_t oa = (int64_t)row * p.ldaux + col0;
-#pragma unroll
-        for (int j = 0; j < TJ; ++j) {
-          if (!col_ok[j]) continue;
-          float v = acc[i][j][r] + bv[j];
-          if (MODE == EPI_PARTIAL) {
-            p.partial[oc + j * 32] = v;
-          } else if (MODE == EPI_F32) {
-            float* C = (float*)p.C + oc + j * 32;
-            *C = (p.beta != 0.0f) ? p.beta * *C + v : v;
-          } else {
-            if (MODE == EPI_ACT_RES && p.drop.thr) v *= drop_elem(p, row, col0 + j * 32);
-            if (MODE == EPI_ACT_RES) v += (float)((const bf16*)p.aux)[oa + j * 32];
-            if (MODE == EPI_ACT_DGELU) v *= gelu_grad_fast((float)((const bf16*)p.aux)[oa + j * 32]);
-            ((bf16*)p.C)[oc + j * 32] = (bf16)v;
-            if (MODE == EPI_ACT_GELU) ((bf16*)p.C2)[oc + j * 32] = (bf16)gelu_fast(v);
-          }
-        }
-      }
-    }
-    // keep the scheduler from overlapping the loads and address arithmetic of different tile rows:
-    // that would cost more registers than the main loop needs and lower the occupancy
-    __builtin_amdgcn_sched_barrier(0);
-  }
-}
-
-// Eight consecutive output columns of one row (as two float4): bias, epilogue, store.  `vec` says
-// that all eight columns exist and every pointer involved is aligned for 16-byte accesses.
-template <int MODE>
-__device__ __forceinline__ void store_octet(const GemmDev& p, int row, int col, float4 lo, float4 hi, bool vec, int split) {
-  const bf16* bias = (const bf16*)p.bias;
-  const bf16* aux = (const bf16*)p.aux;
-  float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
-  if (vec) {
-    if (MODE == EPI_PARTIAL) {
-      float* dst = p.partial + ((int64_t)split * p.M + row) * p.N + col;
-      *(float4*)dst = lo; *(float4*)(dst + 4) = hi;
-      return;
-    }
-    if (bias) {
-      const bf16x8 b = *(const bf16x8*)(bias + col);
-#pragma unroll
-      for (int t = 0; t < 8; ++t) v[t] += (float)b[t];
-    }
-    if (MODE == EPI_F32) {
-      float* C = (float*)p.C + (int64_t)row * p.ldc + col;
-      if (p.beta != 0.0f) {
-        const float4 o0 = *(const float4*)C, o1 = *(const float4*)(C + 4);
-        v[0] += p.beta * o0.x; v[1] += p.beta * o0.y; v[2] += p.beta * o0.z; v[3] += p.beta * o0.w;
-        v[4] += p.beta * o1.x; v[5] += p.beta * o1.y; v[6] += p.beta * o1.z; v[7] += p.beta * o1.w;
-      }
-      *(float4*)C = make_float4(v[0], v[1], v[2], v[3]);
-      *(float4*)(C + 4) = make_float4(v[4], v[5], v[6], v[7]);
-    } else {
-      const int64_t o = (int64_t)row * p.ldc + col;
-      if (MODE == EPI_ACT_RES && p.drop.thr) {
-        float f[8];
-        drop_row_factors<8>(p, row, col, f);
-#pragma unroll
-        for (int t = 0; t < 8; ++t) v[t] *= f[t];
-      }
-      if (MODE == EPI_ACT_RES || MODE == EPI_ACT_DGELU) {
-        const bf16x8 a = *(const bf16x8*)(aux + (int64_t)row * p.ldaux + col);
-#pragma unroll
-        for (int t = 0; t < 8; ++t) v[t] = (MODE == EPI_ACT_RES) ? v[t] + (float)a[t] : v[t] * gelu_grad_fast((float)a[t]);
-      }
-      bf16x8 c;
-#pragma unroll
-      for (int t = 0; t < 8; ++t) c[t] = (bf16)v[t];
-      *(bf16x8*)((bf16*)p.C + o) = c;
-      if (MODE == EPI_ACT_GELU) {
-        bf16x8 g;
-#pragma unroll
-        for (int t = 0; t < 8; ++t) g[t] = (bf16)gelu_fast(v[t]);
-        *(bf16x8*)((bf16*)p.C2 + o) = g;
-      }
-    }
-  } else {
-#pragma unroll
-    for (int t = 0; t < 8; ++t) {
-      if (col + t >= p.N) break;
-      float x = v[t];
-      if (MODE == EPI_PARTIAL) { p.partial[((int64_t)split * p.M + row) * p.N + col + t] = x; continue; }
-      if (bias) x += (float)bias[col + t];
-      if (MODE == EPI_F32) {
-        float* C = (float*)p.C + (int64_t)row * p.ldc + col + t;
-        *C = (p.beta != 0.0f) ? p.beta * *C + x : x;
-      } else {
-        const int64_t o = (int64_t)row * p.ldc + col + t;
-        if (MODE == EPI_ACT_RES && p.drop.thr) x *= drop_elem(p, row, col + t);
-        if (MODE == EPI_ACT_RES) x += (float)aux[(int64_t)row * p.ldaux + col + t];
-        if (MODE == EPI_ACT_DGELU) x *= gelu_grad_fast((float)aux[(int64_t)row * p.ldaux + col + t]);
-        ((bf16*)p.C)[o] = (bf16)x;
-        if (MODE == EPI_ACT_GELU) ((bf16*)p.C2)[o] = (bf16)gelu_fast(x);
-      }
-    }
-  }
-}
-
-template <int MODE>
-__device__ __forceinline__ bool octet_aligned(const GemmDev& p) {
-  if (MODE == EPI_PARTIAL) return (p.N & 3) == 0;
-  if (MODE == EPI_F32) return (p.ldc & 3) == 0 && ((uintptr_t)p.C & 15) == 0 && (!p.bias || ((uintptr_t)p.bias & 15) == 0);
-  bool ok = (p.ldc & 7) == 0 && ((uintptr_t)p.C & 15) == 0 && (!p.bias || ((uintptr_t)p.bias & 15) == 0);
-  if (MODE == EPI_ACT_RES || MODE == EPI_ACT_DGELU) ok = ok && (p.ldaux & 7) == 0 && ((uintptr_t)p.aux & 15) == 0;
-  if (MODE == EPI_ACT_GELU) ok = ok && ((uintptr_t)p.C2 & 15) == 0;
-  return ok;
-}
-
-// Epilogue through LDS: each wave writes one 32-row slab of its result tile to its own LDS region in
-// row-major order and reads it back so that a lane holds 8 consecutive columns of one row; global
-// accesses are then 16 bytes per lane and whole 128-byte lines per row.  LDS operations of one wave
-// execute in order, so no barrier is needed inside a wave's region.
-template <int MODE, int TI, int TJ>
-__device__ __forceinline__ void tile_epilogue_lds(const GemmDev& p, const f32x16 (&acc)[TI][TJ], int rbase, int cbase, int lane, int split,
-                                                  float* stage) {
-  constexpr int WN = 32 * TJ, LDW = WN + 4;
-  constexpr int LPR = WN / 8;           // 8-column pieces per row
-  const bool vec = octet_aligned<MODE>(p);
-#pragma unroll
-  for (int i = 0; i < TI; ++i) {
-#pragma unroll
-    for (int j = 0; j < TJ; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) stage[(8 * (r >> 2) + 4 * (lane >> 5) + (r & 3)) * LDW + j * 32 + (lane & 31)] = acc[i][j][r];
-#pragma unroll
-    for (int it = 0; it < 32 * LPR / 64; ++it) {
-      const int piece = it * 64 + lane;
-      const int lr = piece / LPR, lc = (piece % LPR) * 8;
-      const float4 lo = *(const float4*)(stage + lr * LDW + lc), hi = *(const float4*)(stage + lr * LDW + lc + 4);
-      const int row = rbase + i * 32 + lr, col = cbase + lc;
-      if (row < p.M && col < p.N) store_octet<MODE>(p, row, col, lo, hi, vec && col + 7 < p.N, split);
-    }
-    __builtin_amdgcn_sched_barrier(0);
-  }
-}
-
-constexpr int MPAD = 32;   // m-major LDS rows: R + 32 elements  (row stride = 64 B mod 256 B)
 
 template <bool KMAJ, int R, int BK, int NT>
 struct OperandTile {
@@ -634,23 +350,44 @@ hipError_t launch_cfg(const GemmArgs& g, const GemmDev& p, int splits, hipStream
   return launch_one<false, false, BM, BN, BK, WGM, WGN>(p, grid, s);
 }
 
+// Tile configurations.  0 is gemm_bf16_mfma (128 x 128 x 32, three blocks per CU); the others are gemm_bf16_wide.
+struct TileCfg { int bm, bn, bk; };
+constexpr TileCfg kTileCfg[] = {{128, 128, 32}, {256, 256, 64}, {256, 192, 64}, {128, 192, 64}, {256, 128, 32}, {128, 128, 64}, {256, 128, 64}};
+constexpr int kNumTileCfg = sizeof(kTileCfg) / sizeof(kTileCfg[0]);
+int gemm_cfg_override = -1;    // >= 0: use this configuration for every bf16 product (tuning runs)
+
 // The one tile shape in use: 128 x 128 x 32 with 2 x 2 waves, three blocks per CU.  Measured alternatives
 // were equal or slower over the shapes of the training step and are not built: 256 x 128 and 256 x 256
 // block tiles, 8-wave blocks, 64-deep k-tiles, asynchronous global->LDS rings with 4 stages, and a
 // three-stage LDS pipeline with two fragment sets and a prescribed MFMA/LDS/global issue order (faster
 // only with a single block per CU: 128 x 192 tiles gained 5-15 % on the N = 768 shapes and lost on the
 // weight-gradient shapes).
-constexpr int kBM = 128, kBN = 128, kBK = 32;
+constexpr int kMaxBK = 64;
 
 }  // namespace
 
-hs_status launch_gemm(hs_ctx* ctx, const GemmArgs& g, hipStream_t s) {
-  if (g.M <= 0 || g.N <= 0) return HS_OK;  // nothing to write
+static hs_status check_gemm_args(hs_ctx* ctx, const GemmArgs& g) {
   if (g.K < 0) return hs_fail(ctx, HS_ERR_INVALID_ARG, "gemm: K < 0");
   if (!g.A || !g.B || !g.C) return hs_fail(ctx, HS_ERR_INVALID_ARG, "gemm: NULL operand");
   if ((g.epi == 1 || g.epi == 3) && !g.aux) return hs_fail(ctx, HS_ERR_INVALID_ARG, "gemm: epilogue needs aux");
   if (g.epi == 2 && (!g.C2 || g.c_f32)) return hs_fail(ctx, HS_ERR_INVALID_ARG, "gemm: GELU epilogue needs C2 and an activation-type C");
   if (g.epi < 0 || g.epi > 3) return hs_fail(ctx, HS_ERR_INVALID_ARG, "gemm: bad epilogue");
+  if (g.dtype == HS_BF16) {
+    if ((g.lda % 8) || (g.ldb % 8) || ((uintptr_t)g.A % 16) || ((uintptr_t)g.B % 16))
+      return hs_fail(ctx, HS_ERR_SHAPE, "gemm(bf16): operand rows must be 16-byte aligned");
+    if (g.a_kmajor && g.b_kmajor && (g.K % 8))
+      return hs_fail(ctx, HS_ERR_SHAPE, "gemm(bf16): K must be a multiple of 8 when both operands are k-major");
+    if (!g.a_kmajor && g.b_kmajor) return hs_fail(ctx, HS_ERR_UNIMPLEMENTED, "gemm(bf16): A m-major with B k-major is not built");
+    // the kernels address each operand with 32-bit byte offsets from its start (a few k-tiles of slack)
+    const int64_t a_rows = g.a_kmajor ? g.M : g.K, b_rows = g.b_kmajor ? g.N : g.K;
+    const int64_t lim = ((int64_t)1 << 32) - 1;
+    if ((a_rows + 3 * kMaxBK) * g.lda * 2 + 4 * kMaxBK > lim || (b_rows + 3 * kMaxBK) * g.ldb * 2 + 4 * kMaxBK > lim)
+      return hs_fail(ctx, HS_ERR_SHAPE, "gemm(bf16): an operand exceeds 4 GiB");
+  }
+  return HS_OK;
+}
+
+static GemmDev gemm_dev_args(const GemmArgs& g) {
   GemmDev p;
   p.A = g.A; p.B = g.B; p.C = g.C; p.C2 = g.C2; p.bias = g.bias; p.aux = g.aux;
   p.lda = g.lda; p.ldb = g.ldb; p.ldc = g.ldc; p.ldaux = g.ldaux;
@@ -658,6 +395,57 @@ hs_status launch_gemm(hs_ctx* ctx, const GemmArgs& g, hipStream_t s) {
   p.partial = nullptr; p.k_per_split = g.K;
   p.drop = (g.drop && g.drop->thr && g.epi == 1) ? *g.drop : DropCfg{0u, 1.0f, 0u, 0u, 0u};
   p.drop_site = g.drop_site;
+  return p;
+}
+
+// Several weight-gradient products (A m-major, B n-major, fp32 C = beta C + A^T-style product, no epilogue) in ONE
+// launch of the grouped kernel: no split-K, no partial sums in memory.  Anything else, or more than 8 products,
+// runs as separate launches.
+hs_status launch_gemm_group(hs_ctx* ctx, const GemmArgs* gs, int n, hipStream_t s) {
+  bool groupable = n >= 1 && n <= 8;
+  for (int i = 0; i < n && groupable; ++i) {
+    const GemmArgs& g = gs[i];
+    groupable = g.dtype == HS_BF16 && !g.a_kmajor && !g.b_kmajor && g.c_f32 && g.epi == 0 && !g.bias && g.M > 0 && g.N > 0 && g.K > 0;
+  }
+  if (!groupable) {
+    for (int i = 0; i < n; ++i) { hs_status st = launch_gemm(ctx, gs[i], s); if (st != HS_OK) return st; }
+    return HS_OK;
+  }
+  GemmGroupDev gd;
+  gd.n = n;
+  int tiles = 0;
+  double flops = 0, bytes = 0;
+  for (int i = 0; i < n; ++i) {
+    hs_status st = check_gemm_args(ctx, gs[i]);
+    if (st != HS_OK) return st;
+    gd.prob[i] = gemm_dev_args(gs[i]);
+    gd.first_tile[i] = tiles;
+    tiles += ((gs[i].M + kGroupBM - 1) / kGroupBM) * ((gs[i].N + kGroupBN - 1) / kGroupBN);
+    flops += 2.0 * gs[i].M * gs[i].N * (double)gs[i].K;
+    bytes += ((double)gs[i].M * gs[i].K + (double)gs[i].N * gs[i].K) * 2 + (double)gs[i].M * gs[i].N * 4;
+  }
+  for (int i = n; i <= 8; ++i) gd.first_tile[i] = tiles;
+  KScope scope(ctx ? ctx->prof : nullptr, KC_GEMM_DW, flops, bytes, s);
+  hipError_t e = gemm_wide_group_launch_nn(gd, s);
+  if (e == hipSuccess) e = hipGetLastError();
+  if (e != hipSuccess) return hs_fail(ctx, HS_ERR_HIP, std::string("grouped gemm launch: ") + hipGetErrorString(e));
+  return HS_OK;
+}
+
+// whether gemm_bf16_wide is built with the epilogue this product needs (see wide_epilogues in gemm_wide.h)
+static bool wide_supports(const GemmArgs& g) {
+  if (g.a_kmajor && g.b_kmajor) return g.c_f32 ? true : (g.epi == 0 || g.epi == 1 || g.epi == 2);
+  if (g.a_kmajor) return !g.c_f32 && (g.epi == 0 || g.epi == 1 || g.epi == 3);
+  return g.c_f32 != 0;
+}
+
+hs_status launch_gemm(hs_ctx* ctx, const GemmArgs& g, hipStream_t s) {
+  if (g.M <= 0 || g.N <= 0) return HS_OK;  // nothing to write
+  {
+    hs_status st = check_gemm_args(ctx, g);
+    if (st != HS_OK) return st;
+  }
+  GemmDev p = gemm_dev_args(g);
   const double flops = 2.0 * g.M * g.N * (double)g.K;
   const double bytes = ((double)g.M * g.K + (double)g.N * g.K) * esize(g.dtype) + (double)g.M * g.N * (g.c_f32 ? 4 : esize(g.dtype));
   const int kc = (g.a_kmajor && g.b_kmajor) ? KC_GEMM_FWD : (g.a_kmajor ? KC_GEMM_DX : KC_GEMM_DW);
@@ -666,16 +454,9 @@ hs_status launch_gemm(hs_ctx* ctx, const GemmArgs& g, hipStream_t s) {
     dim3 grid((g.N + 63) / 64, (g.M + 63) / 64);
     hipLaunchKernelGGL(gemm_simt<float>, grid, dim3(256), 0, s, p, g.a_kmajor, g.b_kmajor);
   } else {
-    if ((g.lda % 8) || (g.ldb % 8) || ((uintptr_t)g.A % 16) || ((uintptr_t)g.B % 16))
-      return hs_fail(ctx, HS_ERR_SHAPE, "gemm(bf16): operand rows must be 16-byte aligned");
-    if (g.a_kmajor && g.b_kmajor && (g.K % 8))
-      return hs_fail(ctx, HS_ERR_SHAPE, "gemm(bf16): K must be a multiple of 8 when both operands are k-major");
-    if (!g.a_kmajor && g.b_kmajor) return hs_fail(ctx, HS_ERR_UNIMPLEMENTED, "gemm(bf16): A m-major with B k-major is not built");
-    // the kernel addresses each operand with 32-bit byte offsets from its start (one k-tile of slack)
-    const int64_t a_rows = g.a_kmajor ? g.M : g.K, b_rows = g.b_kmajor ? g.N : g.K;
-    const int64_t lim = ((int64_t)1 << 32) - 1;
-    if ((a_rows + 2 * kBK) * g.lda * 2 + 4 * kBK > lim || (b_rows + 2 * kBK) * g.ldb * 2 + 4 * kBK > lim)
-      return hs_fail(ctx, HS_ERR_SHAPE, "gemm(bf16): an operand exceeds 4 GiB");
+    int cfg = (gemm_cfg_override >= 0 && gemm_cfg_override < kNumTileCfg) ? gemm_cfg_override : 0;
+    if (cfg != 0 && !wide_supports(g)) cfg = 0;
+    const int kBM = kTileCfg[cfg].bm, kBN = kTileCfg[cfg].bn, kBK = kTileCfg[cfg].bk;
     // split-K when the output has too few tiles to fill the chip and a scratch buffer was given
     const int64_t tiles = (int64_t)((g.M + kBM - 1) / kBM) * ((g.N + kBN - 1) / kBN);
     int splits = 1;
@@ -692,7 +473,11 @@ hs_status launch_gemm(hs_ctx* ctx, const GemmArgs& g, hipStream_t s) {
       p.k_per_split = (int)(((g.K + splits - 1) / splits + kBK - 1) / kBK * kBK);
       splits = (g.K + p.k_per_split - 1) / p.k_per_split;
     }
-    hipError_t e = launch_cfg<kBM, kBN, kBK, 2, 2>(g, p, splits, s);
+    hipError_t e;
+    if (cfg == 0) e = launch_cfg<128, 128, 32, 2, 2>(g, p, splits, s);
+    else if (g.a_kmajor && g.b_kmajor) e = gemm_wide_launch_kk(cfg, p, splits, s);
+    else if (g.a_kmajor) e = gemm_wide_launch_kn(cfg, p, splits, s);
+    else e = gemm_wide_launch_nn(cfg, p, splits, s);
     if (e != hipSuccess) return hs_fail(ctx, HS_ERR_HIP, std::string("gemm launch: ") + hipGetErrorString(e));
     if (splits > 1) {
       const int64_t mn = (int64_t)g.M * g.N;

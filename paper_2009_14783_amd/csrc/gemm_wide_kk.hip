@@ -1,0 +1,4 @@
+// gemm_bf16_wide for A k-major, B k-major
+#include "gemm_wide.h"
+
+hipError_t gemm_wide_launch_kk(int cfg, const GemmDev& p, int splits, hipStream_t s) { return launch_wide_layout<true, true>(cfg, p, splits, s); }

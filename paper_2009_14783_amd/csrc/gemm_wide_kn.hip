@@ -1,0 +1,4 @@
+// gemm_bf16_wide for A k-major, B n-major
+#include "gemm_wide.h"
+
+hipError_t gemm_wide_launch_kn(int cfg, const GemmDev& p, int splits, hipStream_t s) { return launch_wide_layout<true, false>(cfg, p, splits, s); }

@@ -286,6 +286,11 @@ __global__ void gather_rows_kernel(const T* __restrict__ src, const int32_t* __r
   }
 }
 
+template <class T>
+__global__ __launch_bounds__(256) void fill_value_kernel(T* p, size_t n, float value) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < n) p[i] = from_f<T>(value);
+}
 __global__ void fill_bytes_kernel(unsigned char* p, size_t n) {
   const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) p[i] = 0;
@@ -745,6 +750,16 @@ hs_status launch_fill_zero(hs_ctx* ctx, void* p, size_t bytes, hipStream_t s) {
   if (blocks > 4096) blocks = 4096;
   hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)blocks), dim3(256), 0, s, (uint4*)p, n16, (unsigned char*)p + n16 * 16, ntail);
   LAUNCH_CHECK(ctx, "fill_zero");
+  return HS_OK;
+}
+
+hs_status launch_fill_value(hs_ctx* ctx, int dtype, void* p, size_t n, float value, hipStream_t s) {
+  if (n == 0) return HS_OK;
+  KScope scope(prof_of(ctx), KC_ELEMWISE, 0.0, (double)n * esize(dtype), s);
+  dim3 grid((unsigned)((n + 255) / 256));
+  if (dtype == HS_BF16) hipLaunchKernelGGL(fill_value_kernel<bf16>, grid, dim3(256), 0, s, (bf16*)p, n, value);
+  else hipLaunchKernelGGL(fill_value_kernel<float>, grid, dim3(256), 0, s, (float*)p, n, value);
+  LAUNCH_CHECK(ctx, "fill_value");
   return HS_OK;
 }
 
