@@ -454,7 +454,10 @@ hs_status launch_gemm(hs_ctx* ctx, const GemmArgs& g, hipStream_t s) {
     dim3 grid((g.N + 63) / 64, (g.M + 63) / 64);
     hipLaunchKernelGGL(gemm_simt<float>, grid, dim3(256), 0, s, p, g.a_kmajor, g.b_kmajor);
   } else {
-    int cfg = (gemm_cfg_override >= 0 && gemm_cfg_override < kNumTileCfg) ? gemm_cfg_override : 0;
+    // Configuration: 128 x 128 x 64 tiles of the wide kernel (two blocks per CU) for products of some size whose
+    // epilogue it is built with; the three-blocks-per-CU kernel for small or ragged ones and for the rest.
+    int cfg = (gemm_cfg_override >= 0 && gemm_cfg_override < kNumTileCfg) ? gemm_cfg_override
+              : ((g.M >= 256 && g.N >= 256 && g.K >= 256) ? 5 : 0);
     if (cfg != 0 && !wide_supports(g)) cfg = 0;
     const int kBM = kTileCfg[cfg].bm, kBN = kTileCfg[cfg].bn, kBK = kTileCfg[cfg].bk;
     // split-K when the output has too few tiles to fill the chip and a scratch buffer was given

@@ -114,6 +114,90 @@ constexpr size_t wide_lds_bytes() {
   return stage > pipe ? stage : pipe;
 }
 
+// Epilogue of a wave's TI x TJ result tiles for the wide kernels, which run one or two blocks per CU: with so few
+// waves the memory latency of an epilogue has to be covered inside each wave.  Same staging through LDS as
+// tile_epilogue_lds; the residual / pre-activation values (aux) of the next 32-row slab are requested before the
+// current slab is worked on, and nothing keeps the compiler from overlapping slabs.  Regions that touch the matrix
+// edge, unaligned operands and dropout take the general routine.
+template <int MODE, int TI, int TJ>
+__device__ __forceinline__ void tile_epilogue_pipe(const GemmDev& p, const f32x16 (&acc)[TI][TJ], int rbase, int cbase, int lane, int split,
+                                                   float* stage) {
+  constexpr int WN = 32 * TJ, LDW = WN + 4;
+  constexpr int LPR = WN / 8, NIT = 32 * LPR / 64;
+  constexpr bool HAS_AUX = MODE == EPI_ACT_RES || MODE == EPI_ACT_DGELU;
+  const bool inside = octet_aligned<MODE>(p) && rbase + 32 * TI <= p.M && cbase + WN <= p.N && !(MODE == EPI_ACT_RES && p.drop.thr);
+  if (!inside) { tile_epilogue_lds<MODE, TI, TJ>(p, acc, rbase, cbase, lane, split, stage); return; }
+  const bf16* bias = (const bf16*)p.bias;
+  const bf16* aux = (const bf16*)p.aux;
+  bf16x8 anext[NIT];
+  auto load_aux = [&](int i) __attribute__((always_inline)) {
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) {
+      const int piece = it * 64 + lane;
+      const int row = rbase + i * 32 + piece / LPR, col = cbase + (piece % LPR) * 8;
+      anext[it] = *(const bf16x8*)(aux + (int64_t)row * p.ldaux + col);
+    }
+  };
+  if (HAS_AUX) load_aux(0);
+#pragma unroll
+  for (int i = 0; i < TI; ++i) {
+    bf16x8 acur[NIT];
+    if (HAS_AUX) {
+#pragma unroll
+      for (int it = 0; it < NIT; ++it) acur[it] = anext[it];
+      if (i + 1 < TI) load_aux(i + 1);
+    }
+#pragma unroll
+    for (int j = 0; j < TJ; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) stage[(8 * (r >> 2) + 4 * (lane >> 5) + (r & 3)) * LDW + j * 32 + (lane & 31)] = acc[i][j][r];
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) {
+      const int piece = it * 64 + lane;
+      const int lr = piece / LPR, lc = (piece % LPR) * 8;
+      const float4 lo = *(const float4*)(stage + lr * LDW + lc), hi = *(const float4*)(stage + lr * LDW + lc + 4);
+      const int row = rbase + i * 32 + lr, col = cbase + lc;
+      float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+      if (MODE == EPI_PARTIAL) {
+        float* dst = p.partial + ((int64_t)split * p.M + row) * p.N + col;
+        *(float4*)dst = lo; *(float4*)(dst + 4) = hi;
+        continue;
+      }
+      if (bias) {
+        const bf16x8 b = *(const bf16x8*)(bias + col);
+#pragma unroll
+        for (int t = 0; t < 8; ++t) v[t] += (float)b[t];
+      }
+      if (MODE == EPI_F32) {
+        float* C = (float*)p.C + (int64_t)row * p.ldc + col;
+        if (p.beta != 0.0f) {
+          const float4 o0 = *(const float4*)C, o1 = *(const float4*)(C + 4);
+          v[0] += p.beta * o0.x; v[1] += p.beta * o0.y; v[2] += p.beta * o0.z; v[3] += p.beta * o0.w;
+          v[4] += p.beta * o1.x; v[5] += p.beta * o1.y; v[6] += p.beta * o1.z; v[7] += p.beta * o1.w;
+        }
+        *(float4*)C = make_float4(v[0], v[1], v[2], v[3]);
+        *(float4*)(C + 4) = make_float4(v[4], v[5], v[6], v[7]);
+      } else {
+        const int64_t o = (int64_t)row * p.ldc + col;
+        if (HAS_AUX) {
+#pragma unroll
+          for (int t = 0; t < 8; ++t) v[t] = (MODE == EPI_ACT_RES) ? v[t] + (float)acur[it][t] : v[t] * gelu_grad_fast((float)acur[it][t]);
+        }
+        bf16x8 c;
+#pragma unroll
+        for (int t = 0; t < 8; ++t) c[t] = (bf16)v[t];
+        *(bf16x8*)((bf16*)p.C + o) = c;
+        if (MODE == EPI_ACT_GELU) {
+          bf16x8 g;
+#pragma unroll
+          for (int t = 0; t < 8; ++t) g[t] = (bf16)gelu_fast(v[t]);
+          *(bf16x8*)((bf16*)p.C2 + o) = g;
+        }
+      }
+    }
+  }
+}
+
 // One block tile of C for the k-range of `split`: main loop and epilogue.
 // NSETS register sets hold the k-tiles in flight from global memory: a tile is requested NSETS iterations
 // before it is written to LDS.  EPIS: bit mask (1 << mode) of the epilogues that are compiled in.
@@ -180,7 +264,11 @@ __device__ __forceinline__ void wide_tile(const GemmDev& p, int m0, int n0, int 
   // `set` holds tile t+1.  Step 0 moves tile t+1 to the other LDS buffer and requests tile t+1+NSETS into the
   // freed registers; every step reads the fragments of the next one while its MFMAs run; the barrier sits
   // before the last step, whose MFMAs cover the wait and the first fragment reads of tile t+1.
-  // FAST: tiles t+1 and t+1+NSETS exist and are full: no guards, and the whole body is one basic block.
+  // FAST: the contraction range is a whole number of k-tiles: no guards, the body is one basic block, and it also runs
+  // for the last iterations, whose requests go to tiles that do not exist: those are sent beyond the end of the
+  // operand (see `past`), where a buffer load returns zeros without touching memory, and what they bring is written
+  // to the LDS buffer nobody reads any more.
+  const unsigned past = 0x80000000u;            // beyond any operand this kernel accepts less one k-tile row range
   auto body = [&](auto fast_tag, auto cur_tag, int t) __attribute__((always_inline)) {
     constexpr bool FAST = decltype(fast_tag)::value;
     constexpr int cur = decltype(cur_tag)::value, nxt = cur ^ 1, set = (NSETS == 2) ? nxt : 0;
@@ -237,19 +325,28 @@ __device__ __forceinline__ void wide_tile(const GemmDev& p, int m0, int n0, int 
           }
         }
       }
-      if (s == 0) { ca.soff += ca.step; cb.soff += cb.step; }
+      if (s == 0) {
+        // the next request: one k-tile on, or nowhere once the range is used up (FAST only: the guarded loads look at kleft)
+        const bool more = !FAST || t + 2 + NSETS < nk;
+        ca.soff = more ? ca.soff + ca.step : past;
+        cb.soff = more ? cb.soff + cb.step : past;
+      }
     }
   };
   {
-    int t = 0;
-    // iterations t with t + 1 + NSETS < nfull are FAST; they are taken in pairs so that buffer indices are static
-    for (; t + 2 + NSETS < nfull; t += 2) {
-      body(std::true_type{}, std::integral_constant<int, 0>{}, t);
-      body(std::true_type{}, std::integral_constant<int, 1>{}, t + 1);
-    }
-    for (; t < nk; t += 2) {
-      body(std::false_type{}, std::integral_constant<int, 0>{}, t);
-      if (t + 1 < nk) body(std::false_type{}, std::integral_constant<int, 1>{}, t + 1);
+    typedef std::integral_constant<int, 0> I0;
+    typedef std::integral_constant<int, 1> I1;
+    if (nfull == nk && nk > NSETS) {
+      for (int t = 0; t < nk; t += 2) {
+        body(std::true_type{}, I0{}, t);
+        if (t + 1 < nk) body(std::true_type{}, I1{}, t + 1);
+      }
+    } else {
+      // a partial last k-tile, or fewer tiles than the pipeline is deep: every iteration guarded
+      for (int t = 0; t < nk; t += 2) {
+        body(std::false_type{}, I0{}, t);
+        if (t + 1 < nk) body(std::false_type{}, I1{}, t + 1);
+      }
     }
   }
   __syncthreads();   // every wave is done with the operand buffers: they become the staging area of the epilogue
@@ -258,12 +355,12 @@ __device__ __forceinline__ void wide_tile(const GemmDev& p, int m0, int n0, int 
   constexpr int STAGE_FLOATS = 32 * (32 * TJ + 4);
   float* stage = (float*)lds_raw + wave * STAGE_FLOATS;
   constexpr auto has = [](int mode) { return (EPIS >> mode) & 1; };
-  if (p.partial) { if constexpr (has(EPI_PARTIAL)) tile_epilogue_lds<EPI_PARTIAL, TI, TJ>(p, acc, rbase, cbase, lane, split, stage); }
-  else if (p.c_f32) { if constexpr (has(EPI_F32)) tile_epilogue_lds<EPI_F32, TI, TJ>(p, acc, rbase, cbase, lane, 0, stage); }
-  else if (p.epi == 0) { if constexpr (has(EPI_ACT)) tile_epilogue_lds<EPI_ACT, TI, TJ>(p, acc, rbase, cbase, lane, 0, stage); }
-  else if (p.epi == 1) { if constexpr (has(EPI_ACT_RES)) tile_epilogue_lds<EPI_ACT_RES, TI, TJ>(p, acc, rbase, cbase, lane, 0, stage); }
-  else if (p.epi == 2) { if constexpr (has(EPI_ACT_GELU)) tile_epilogue_lds<EPI_ACT_GELU, TI, TJ>(p, acc, rbase, cbase, lane, 0, stage); }
-  else { if constexpr (has(EPI_ACT_DGELU)) tile_epilogue_lds<EPI_ACT_DGELU, TI, TJ>(p, acc, rbase, cbase, lane, 0, stage); }
+  if (p.partial) { if constexpr (has(EPI_PARTIAL)) tile_epilogue_pipe<EPI_PARTIAL, TI, TJ>(p, acc, rbase, cbase, lane, split, stage); }
+  else if (p.c_f32) { if constexpr (has(EPI_F32)) tile_epilogue_pipe<EPI_F32, TI, TJ>(p, acc, rbase, cbase, lane, 0, stage); }
+  else if (p.epi == 0) { if constexpr (has(EPI_ACT)) tile_epilogue_pipe<EPI_ACT, TI, TJ>(p, acc, rbase, cbase, lane, 0, stage); }
+  else if (p.epi == 1) { if constexpr (has(EPI_ACT_RES)) tile_epilogue_pipe<EPI_ACT_RES, TI, TJ>(p, acc, rbase, cbase, lane, 0, stage); }
+  else if (p.epi == 2) { if constexpr (has(EPI_ACT_GELU)) tile_epilogue_pipe<EPI_ACT_GELU, TI, TJ>(p, acc, rbase, cbase, lane, 0, stage); }
+  else { if constexpr (has(EPI_ACT_DGELU)) tile_epilogue_pipe<EPI_ACT_DGELU, TI, TJ>(p, acc, rbase, cbase, lane, 0, stage); }
 }
 
 // the epilogues each operand layout is built with (the training step needs no others; launch_gemm falls back
