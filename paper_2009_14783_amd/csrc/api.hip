@@ -180,7 +180,8 @@ hs_status hs_encoder_fwd(hs_ctx* ctx, const void* w, const int32_t* ids, const i
   // other half's work.  Every kernel sees a row range of the same buffers, so the results are those of one
   // pass (dropout numbers the elements of the whole batch: each half gets the state with its offset).  Not with
   // per-launch timing.
-  const bool split = ctx->prof == nullptr && B >= 2 && T >= 4096;
+  static const int fwd_parts_env = getenv("HS_FWD_PARTS") ? atoi(getenv("HS_FWD_PARTS")) : 2;
+  const bool split = ctx->prof == nullptr && B >= 2 && T >= 4096 && fwd_parts_env == 2;
   const int nparts = split ? 2 : 1;
   if (split) HS_TRY(ensure_side_stream(ctx, 2));
   if (split) {
@@ -387,7 +388,7 @@ static hs_status encoder_bwd_impl(hs_ctx* ctx, const hs_ctx::Armed& upd, const v
   // stays on the caller's stream so that the timings do not overlap.
   const bool overlap = ctx->prof == nullptr;
   const int NL = c.n_layers;
-  if (overlap) HS_TRY(ensure_side_stream(ctx, (size_t)6 * NL + 3));
+  if (overlap) HS_TRY(ensure_side_stream(ctx, (size_t)6 * NL + 5));
   hipStream_t sd = overlap ? ctx->side : s;
   // third stream for an armed optimizer update (events 6 NL .. 6 NL + 2: head ready, embeddings ready, done)
   if (overlap && upd.on && !ctx->upd) HS_HIP_CHECK(ctx, hipStreamCreateWithFlags(&ctx->upd, hipStreamNonBlocking));
@@ -422,6 +423,14 @@ static hs_status encoder_bwd_impl(hs_ctx* ctx, const hs_ctx::Armed& upd, const v
   // bf16: the weight gradients of a layer go out as one grouped launch once the layer's last operand (d qkv) exists
   const bool grouped = dt == HS_BF16;
   if (grouped) HS_TRY(launch_fill_value(ctx, dt, ws.ones, (size_t)T * 8, 1.0f, s));
+  // The sort of the token ids that the embedding gradient needs depends on nothing computed here: on the second
+  // stream, ahead of everything else (events 6 NL + 3: the caller's stream has got here, 6 NL + 4: sorted).
+  if (overlap) {
+    HS_HIP_CHECK(ctx, hipEventRecord(ctx->events[(size_t)6 * NL + 3], s));
+    HS_HIP_CHECK(ctx, hipStreamWaitEvent(sd, ctx->events[(size_t)6 * NL + 3], 0));
+    HS_TRY(launch_embed_sort(ctx, ids, T, c.vocab, ws.emb, sd));
+    HS_HIP_CHECK(ctx, hipEventRecord(ctx->events[(size_t)6 * NL + 4], sd));
+  }
   const void* dcur = d_hidden;
   for (int i = NL - 1; i >= 0; --i) {
     const LayerOff& lo = o.layer[i];
@@ -507,7 +516,8 @@ static hs_status encoder_bwd_impl(hs_ctx* ctx, const hs_ctx::Armed& upd, const v
   // embedding LayerNorm, then the two embedding tables
   HS_TRY(launch_layernorm_bwd(ctx, dt, dcur, a.e_pre, a.emb_stats, W(ctx, w, o.emb_ln_g), ws.dxa, g + o.emb_ln_g,
                               g + o.emb_ln_b, nullptr, beta, T, H, ws.ln_part, s, drop, site_embedding(), drop ? 1 : 0, nullptr));
-  HS_TRY(launch_embed_bwd(ctx, dt, ws.dxa, ids, B, L, H, c.vocab, c.max_pos, g + o.emb_word, g + o.emb_pos, beta, ws.emb, s));
+  if (overlap) HS_HIP_CHECK(ctx, hipStreamWaitEvent(s, ctx->events[(size_t)6 * NL + 4], 0));
+  HS_TRY(launch_embed_bwd(ctx, dt, ws.dxa, ids, B, L, H, c.vocab, c.max_pos, g + o.emb_word, g + o.emb_pos, beta, ws.emb, s, overlap));
   if (upd.on) {      // the embedding tables and their LayerNorm last
     HS_TRY(after_main(ctx->events[(size_t)6 * NL + 1]));
     HS_TRY(update_slice(ctx, upd, 0, o.layer[0].qkv_w, su));

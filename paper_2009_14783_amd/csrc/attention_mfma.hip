@@ -96,10 +96,10 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma(const bf16* __restrict__ qk
     }
   }
   lsum += __shfl_xor(lsum, 32);
-  if (q < L) {
-    store_owned_rows(out + ((int64_t)b * L + q) * H + h * DH, o, 1.0f / lsum, lane);
-    if (lane < 32) lse[((int64_t)b * A + h) * L + q] = (m2 + __log2f(lsum)) * LN2;
-  }
+  if (q < L && lane < 32) lse[((int64_t)b * A + h) * L + q] = (m2 + __log2f(lsum)) * LN2;
+  __syncthreads();      // every wave is done with the key/value tiles: each wave takes 32 rows of them as its staging area
+  store_owned_rows_lds(out + (int64_t)b * L * H + h * DH, H, blockIdx.x * 128 + wave * 32, L, o, 1.0f / lsum, lane,
+                       (wave < 2 ? Ks : Vs) + (wave & 1) * 32 * LDT);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -382,17 +382,20 @@ __global__ __launch_bounds__(256) void attn_bwd_fused128_mfma(const bf16* __rest
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[db][r] = 0.f;
   }
-  if (own < L) store_owned_rows(dqkv + ((int64_t)b * L + own) * ld + h * DH, acc, 0.125f, lane);
-
   // ---- keys owned: dk, dv ----
+  // The owned key/value fragments are the last thing read from the K and V tiles: after the barrier a wave's own 32
+  // rows of those tiles are its staging areas for whole-row stores of dq, dk and dv.
+  bf16x8 kf[4], vf[4];
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) { kf[ks] = frag_rows(Ks, wave * 32, ks, lane); vf[ks] = frag_rows(Vs, wave * 32, ks, lane); }
+  __syncthreads();
+  bf16* const dst = dqkv + (int64_t)b * L * ld + h * DH;
+  store_owned_rows_lds(dst, ld, wave * 32, L, acc, 0.125f, lane, Ks + wave * 32 * LDT);
 #pragma unroll
   for (int db = 0; db < 2; ++db)
 #pragma unroll
     for (int r = 0; r < 16; ++r) { acc[db][r] = 0.f; acc2[db][r] = 0.f; }
   if (wave_active) {
-    bf16x8 kf[4], vf[4];
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks) { kf[ks] = frag_rows(Ks, wave * 32, ks, lane); vf[ks] = frag_rows(Vs, wave * 32, ks, lane); }
     for (int qb = 0; qb < len; qb += 32) {
       f32x16 st, dp;
 #pragma unroll
@@ -423,11 +426,8 @@ __global__ __launch_bounds__(256) void attn_bwd_fused128_mfma(const bf16* __rest
       }
     }
   }
-  if (own < L) {
-    bf16* row = dqkv + ((int64_t)b * L + own) * ld + h * DH;
-    store_owned_rows(row + H, acc, 0.125f, lane);
-    store_owned_rows(row + 2 * H, acc2, 1.0f, lane);
-  }
+  store_owned_rows_lds(dst + H, ld, wave * 32, L, acc, 0.125f, lane, Ks + wave * 32 * LDT);
+  store_owned_rows_lds(dst + 2 * H, ld, wave * 32, L, acc2, 1.0f, lane, Vs + wave * 32 * LDT);
 }
 
 }  // namespace

@@ -107,4 +107,28 @@ __device__ __forceinline__ void store_owned_rows(bf16* __restrict__ dst_row, con
     }
 }
 
+// The same rows through a wave-private LDS area of 32 x LDT elements, so that global memory sees whole 128-byte
+// rows (8 lanes x 16 bytes) instead of 8-byte pieces: lane l first puts its pieces of row l % 32 into the area,
+// then the wave writes the 32 rows out, 8 rows per store instruction.  LDS operations of one wave execute in
+// order, so no barrier is needed.  Rows row0 + r >= row_limit are not written.
+__device__ __forceinline__ void store_owned_rows_lds(bf16* __restrict__ dst, int64_t ld, int row0, int row_limit, const f32x16 (&acc)[2],
+                                                     float scale, int lane, bf16* stage) {
+#pragma unroll
+  for (int db = 0; db < 2; ++db)
+#pragma unroll
+    for (int qd = 0; qd < 4; ++qd) {
+      bf16x4 o;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) o[e] = (bf16)(acc[db][4 * qd + e] * scale);
+      *(bf16x4*)(stage + (lane & 31) * LDT + 32 * db + 8 * qd + 4 * (lane >> 5)) = o;
+    }
+#pragma unroll
+  for (int it = 0; it < 4; ++it) {
+    const int c = it * 64 + lane;
+    const int r = c >> 3, col = (c & 7) * 8;
+    const uint4 v = *(const uint4*)(stage + r * LDT + col);
+    if (row0 + r < row_limit) *(uint4*)(dst + (int64_t)(row0 + r) * ld + col) = v;
+  }
+}
+
 }  // namespace attn_tiles

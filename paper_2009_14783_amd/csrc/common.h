@@ -228,8 +228,10 @@ hs_status launch_embed_ln_fwd(hs_ctx* ctx, int dtype, const void* word, const vo
                               const int32_t* ids, void* e_pre, void* x0, float* stats, int B, int L, int H, int V, float eps,
                               hipStream_t s, const DropCfg* drop = nullptr, int stat_ld = 0);
 size_t embed_bwd_scratch(int T, int H);
+// sorted: launch_embed_sort has already run on the same scratch (ordered before this call)
+hs_status launch_embed_sort(hs_ctx* ctx, const int32_t* ids, int T, int V, void* scratch, hipStream_t s);
 hs_status launch_embed_bwd(hs_ctx* ctx, int dtype, const void* de, const int32_t* ids, int B, int L, int H, int V, int max_pos,
-                           float* g_word, float* g_pos, float beta_pos, void* scratch, hipStream_t s);
+                           float* g_word, float* g_pos, float beta_pos, void* scratch, hipStream_t s, bool sorted = false);
 // drop/site: dropout of the attention probabilities (element ((b*A + h)*L + query)*L + key of the site)
 hs_status launch_attention_fwd(hs_ctx* ctx, int dtype, const void* qkv, const int32_t* lens, int B, int L, int A, void* out,
                                float* lse, hipStream_t s, const DropCfg* drop = nullptr, uint32_t site = 0);

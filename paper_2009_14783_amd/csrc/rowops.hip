@@ -671,10 +671,27 @@ size_t embed_bwd_scratch(int T, int H) {
   return align_up(4 * (size_t)T * sizeof(int32_t), 256) + align_up(chunks * 2 * H * sizeof(float), 256);
 }
 
+// stable sort of the token ids (keys) with their positions (values) into the first two arrays of `scratch`; needs only the
+// ids, so it can run ahead of the gradient that launch_embed_bwd scatters
+hs_status launch_embed_sort(hs_ctx* ctx, const int32_t* ids, int T, int V, void* scratch, hipStream_t s) {
+  if (T <= 0) return HS_OK;
+  KScope scope(prof_of(ctx), KC_EMBED, 0.0, 16.0 * T, s);
+  int32_t* k0 = (int32_t*)scratch;
+  int32_t* v0 = k0 + T; int32_t* k1 = v0 + T; int32_t* v1 = k1 + T;
+  int bits = 1;
+  while ((1 << bits) < V) ++bits;
+  int npass = (bits + 3) / 4;
+  if (npass & 1) ++npass;  // an even number of passes leaves the result in (k0, v0)
+  hipLaunchKernelGGL(sort_ids_kernel, dim3(1), dim3(512), 0, s, ids, T, V, k0, v0, k1, v1, npass);
+  LAUNCH_CHECK(ctx, "sort_ids");
+  return HS_OK;
+}
+
 hs_status launch_embed_bwd(hs_ctx* ctx, int dtype, const void* de, const int32_t* ids, int B, int L, int H, int V, int max_pos,
-                           float* g_word, float* g_pos, float beta_pos, void* scratch, hipStream_t s) {
+                           float* g_word, float* g_pos, float beta_pos, void* scratch, hipStream_t s, bool sorted) {
   const int T = B * L;
   if (T <= 0) return HS_OK;
+  if (!sorted) { hs_status st = launch_embed_sort(ctx, ids, T, V, scratch, s); if (st != HS_OK) return st; }
   KScope scope(prof_of(ctx), KC_EMBED, 2.0 * T * H, (double)T * H * (2.0 * esize(dtype) + 8.0) + 8.0 * max_pos * H, s);
   if (g_pos) {     // a model with a fixed position table has no position gradient
     const int64_t n = (int64_t)max_pos * H;
@@ -684,14 +701,8 @@ hs_status launch_embed_bwd(hs_ctx* ctx, int dtype, const void* de, const int32_t
     LAUNCH_CHECK(ctx, "pos_grad");
   }
   int32_t* k0 = (int32_t*)scratch;
-  int32_t* v0 = k0 + T; int32_t* k1 = v0 + T; int32_t* v1 = k1 + T;
+  int32_t* v0 = k0 + T;
   float* carry = (float*)((char*)scratch + align_up(4 * (size_t)T * sizeof(int32_t), 256));
-  int bits = 1;
-  while ((1 << bits) < V) ++bits;
-  int npass = (bits + 3) / 4;
-  if (npass & 1) ++npass;  // an even number of passes leaves the result in (k0, v0)
-  hipLaunchKernelGGL(sort_ids_kernel, dim3(1), dim3(512), 0, s, ids, T, V, k0, v0, k1, v1, npass);
-  LAUNCH_CHECK(ctx, "sort_ids");
   const int chunks = (T + CH - 1) / CH;
   dim3 grid((chunks + 3) / 4);
   if (dtype == HS_BF16) hipLaunchKernelGGL(word_grad_chunks_kernel<bf16>, grid, dim3(256), 0, s, (const bf16*)de, k0, v0, T, H, g_word, carry);
