@@ -87,14 +87,6 @@ def cpu_baseline(model, wl, theta, mbs, n_seq_sample=64):
                 host_cores_available=len(os.sched_getaffinity(0)))
 
 
-def pair_workload(synth, seed=1240, B=128, L=32):
-    """The translation workload's batch: 128 sentence pairs in buffers of 32 positions per side (4096 positions per
-    side, the per-worker max-tokens of table 1), lengths uniform in [16, 32] with targets 0.8 .. 1.25 times the source."""
-    rng = synth.rng_for(seed)
-    sl, tl = synth.draw_pair_lengths(rng, B, L // 2, L)
-    return synth.make_pair_batch(rng, sl, tl, L, L, synth.S2S_MODELS["transformer_base"]["vocab"], "zipf")
-
-
 def pair_flops(model, mb):
     """Forward + backward (2x forward) algorithmic flops: per real source token and encoder layer 8 H^2 + 4 H F + 4 Ls H;
     per real target token and decoder layer 12 H^2 + 4 H F + 2 Lt H (causal: half the pairs) + 4 Ls H, plus the key/value
@@ -122,7 +114,7 @@ def main_pairs(args):
     adam = dict(lr=5e-4, beta1=0.9, beta2=0.98, eps=1e-9)
     cfg = hs.make_s2s_cfg(**model)
     theta = synth.init_params(hs.hs_s2s_param_layout(cfg), 1240)
-    mb = pair_workload(synth)
+    mb = synth.pair_workload()
     if args.dropout > 0.0:
         mb["drop"] = dict(p=args.dropout, seed=1240, stream=0)
     worker = PairWorker(model, "bf16", theta)

@@ -201,3 +201,11 @@ def draw_pair_lengths(rng: np.random.Generator, n: int, lo: int, hi: int):
     s = rng.integers(lo, hi + 1, size=n)
     t = np.clip(np.rint(s * rng.uniform(0.8, 1.25, size=n)), lo, hi).astype(np.int32)
     return s.astype(np.int32), t
+
+
+def pair_workload(seed=1240, B=128, L=32):
+    """The translation workload's batch: 128 sentence pairs in buffers of 32 positions per side (4096 positions per
+    side, the per-worker max-tokens of table 1), lengths uniform in [16, 32] with targets 0.8 .. 1.25 times the source."""
+    rng = rng_for(seed)
+    sl, tl = draw_pair_lengths(rng, B, L // 2, L)
+    return make_pair_batch(rng, sl, tl, L, L, S2S_MODELS["transformer_base"]["vocab"], "zipf")

@@ -1,14 +1,15 @@
 """Parity of the translation workload (encoder-decoder step) on the GPU against its CPU oracle, through the C ABI.
 
 Tolerances as for the encoder-only path: relative L2 error per tensor (|a-b|/|b| for scalars) below 1e-4 in fp32
-mode and 2e-2 in bf16 mode, with a floor in bf16 mode that the test computes.  Two kinds of gradient in this model are
+mode and 2e-2 in bf16 mode: every tensor is held to that, with one named exemption in bf16 mode.  Two kinds of gradient in this model are
 ill-conditioned in the weights, so that rounding the WEIGHTS to bf16 alone, with everything else exact, already moves
-them by more than that: (1) the first linear map of a feed-forward block (ffn1.w, ffn1.b) sits behind the ReLU gate
+them by more than 2e-2: (1) the first linear map of a feed-forward block (ffn1.w, ffn1.b) sits behind the ReLU gate
 [pre-activation > 0], a decision that floating point takes; a few gates per thousand flip and each flip changes that
 unit's contribution by 100 %, a relative L2 change of about sqrt(fraction flipped) = 3e-2 .. 7e-2; (2) at small random
-weights attention is uniform to three digits and the gradients of the query projections (cq.*) are what is left when
-nearly equal terms cancel (about 1e-2 from weight rounding alone).  A tensor's bf16 bound is therefore
-max(2e-2, 3 x the change that bf16 rounding of the weights alone produces in the oracle's gradient), never above 1e-1."""
+weights attention is uniform to three digits and the gradients of the query projections of the attention over the
+encoder output (cq.w, cq.b) are what is left when nearly equal terms cancel (about 1e-2 from weight rounding alone).
+EXEMPT names exactly these tensors; their bf16 bound is max(2e-2, 3 x the change that bf16 rounding of the weights alone
+produces in the oracle's gradient of that tensor), and the full-size test prints error and bound of every tensor."""
 import numpy as np
 import pytest
 
@@ -38,14 +39,20 @@ def rel(a, b):
     return float(np.linalg.norm(a - b) / nb) if nb > 1e-12 else float(np.linalg.norm(a - b))
 
 
-def compare_flat(layout, got, want, tol, what, gated=None):
-    """gated: the oracle's gradient on bf16-rounded weights (bf16 mode only): the floor the module text describes."""
+EXEMPT = ("ffn1.w", "ffn1.b", "cq.w", "cq.b")     # bf16 mode only, see the module text
+
+
+def compare_flat(layout, got, want, tol, what, gated=None, table=None):
+    """gated: the oracle's gradient on bf16-rounded weights (bf16 mode only).  It widens the bound of the EXEMPT tensors
+    and of no other.  table: list that receives (name, error, bound) of every tensor."""
     worst = ("", 0.0)
     for name, off, r, c in layout:
         e = rel(got[off:off + r * c], want[off:off + r * c])
         t = tol
-        if gated is not None:
-            t = min(1e-1, max(tol, 3.0 * rel(gated[off:off + r * c], want[off:off + r * c])))
+        if gated is not None and name.endswith(EXEMPT):
+            t = max(tol, 3.0 * rel(gated[off:off + r * c], want[off:off + r * c]))
+        if table is not None:
+            table.append((name, e, t))
         if e / t > worst[1]:
             worst = (name, e / t)
         assert e < t, f"{what}: {name} rel err {e:.3e} >= {t:.3e}"
@@ -241,13 +248,12 @@ def test_bad_arguments_are_refused(hs):
 
 def test_full_size_translation_batch_matches_oracle_bf16(hs):
     """The batch and launch configuration that bench.py --workload transformer_base times (Transformer-base, 128 sentence
-    pairs, 4096 positions per side), against the oracle in fp32: both losses, and the gradient tensors of the first and
-    last layer of each stack and of the shared embedding (the oracle takes about half a minute)."""
-    import bench
+    pairs, 4096 positions per side), against the oracle in fp32: both losses and every gradient tensor of all twelve
+    layers and of the shared embedding (the oracle takes about half a minute).  Prints error and bound per tensor."""
     model = synth.S2S_MODELS["transformer_base"]
     ocfg = S.S2SCfg(**model)
     theta = synth.init_params(S.param_layout(ocfg), 1240)
-    mb = bench.pair_workload(synth)
+    mb = synth.pair_workload()
     assert mb["src"].shape == (128, 32) and mb["tgt_in"].shape == (128, 32)
     from paper_2009_14783_amd.step import PairWorker
     wk = PairWorker(model, "bf16", theta)
@@ -257,8 +263,16 @@ def test_full_size_translation_batch_matches_oracle_bf16(hs):
     assert n_seq == 128 and n_tok == mb["n_tgt_tokens"]
     assert abs(loss - ol) / abs(ol) < 2e-2 and abs(nll - on) / abs(on) < 2e-2
     gated = rounded_weights_grad(ocfg, theta, mb)
-    keep = [e for e in S.param_layout(ocfg) if e[0] == "emb" or e[0].startswith(("enc0.", "enc5.", "dec0.", "dec5."))]
-    worst = compare_flat(keep, g, og, 2e-2, "grad", gated)
+    table = []
+    try:
+        worst = compare_flat(S.param_layout(ocfg), g, og, 2e-2, "grad", gated, table)
+    finally:
+        print("tensor                 rel. L2 error   bound")
+        for name, e, t in table:
+            if e > 5e-3 or name.endswith(EXEMPT):
+                print(f"{name:22s} {e:12.3e}   {t:.3e}")
+        plain = [e for name, e, t in table if not name.endswith(EXEMPT)]
+        print(f"{len(table)} tensors; worst of the {len(plain)} held to 2e-2: {max(plain):.3e}")
     print(f"full size: loss {loss:.1f} (oracle {ol:.1f}), {n_tok} target tokens, worst tensor {worst[0]} at {worst[1]:.2f} of its bound")
 
 
@@ -374,7 +388,6 @@ def test_projection_over_real_rows_only_equals_projection_over_all_rows(hs, comp
 def test_full_size_three_updates_with_dropout_follow_oracle_bf16(hs):
     """Three whole steps of the Transformer-base model on the benchmark batch with the paper's dropout of 0.1 (masks numbered
     over the whole batch while the forward pass runs as two halves): the loss of every step against the oracle's loop."""
-    import bench
     model = synth.S2S_MODELS["transformer_base"]
     ocfg = S.S2SCfg(**model)
     theta = synth.init_params(S.param_layout(ocfg), 1240)
@@ -383,7 +396,7 @@ def test_full_size_three_updates_with_dropout_follow_oracle_bf16(hs):
     th, m, v = theta.copy(), np.zeros_like(theta), np.zeros_like(theta)
     first = None
     for t in range(1, 4):
-        mb = bench.pair_workload(synth, seed=1240 + t)
+        mb = synth.pair_workload(seed=1240 + t)
         mb["drop"] = dict(p=0.1, seed=1240, stream=t)
         D = wk.train_step([wk.upload(mb)], ADAM)
         loss, nll = wk.reported_loss(D)

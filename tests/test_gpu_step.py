@@ -35,13 +35,45 @@ def rel(a, b):
     return float(np.linalg.norm(a - b) / nb) if nb > 1e-12 else float(np.linalg.norm(a - b))
 
 
+ROWWISE = ("emb.word", "emb.pos", "head.dec.b")     # tensors whose rows (entries) belong to single tokens / positions
+
+
 def compare_flat(layout, got, want, tol, what):
+    """Per tensor: relative L2 error below tol.  On top of that, so that one wrong row or entry cannot hide inside a
+    large tensor: (1) no single element is off by more than 4 tol of its own size plus 48 tol times the scale of its row
+    and column, RMS(row) x RMS(column) / RMS(tensor) (a weight gradient is a sum of outer products, so its rounding noise
+    has that rank-one profile, and heavy tails: rounding the weights to bf16 alone moves single elements of the oracle's
+    gradient by up to 0.4 of that scale at BERT-base size; at least a quarter of the tensor's RMS, the RMS itself for
+    vectors); (2) for the embedding tables and the decoder bias every row (entry)
+    that carries real signal (norm above a tenth of the RMS row norm) is held to 2 tol on its own."""
     worst = ("", 0.0)
     for name, off, r, c in layout:
-        e = rel(got[off:off + r * c], want[off:off + r * c])
+        g = np.asarray(got[off:off + r * c], np.float64)
+        w = np.asarray(want[off:off + r * c], np.float64)
+        e = rel(g, w)
         if e > worst[1]:
             worst = (name, e)
         assert e < tol, f"{what}: {name} rel err {e:.3e} >= {tol}"
+        rms = float(np.sqrt(np.mean(w * w)))
+        if rms > 1e-12:
+            g2, w2 = g.reshape(r, c), w.reshape(r, c)
+            row_rms = np.sqrt(np.mean(w2 * w2, axis=1, keepdims=True))
+            col_rms = np.sqrt(np.mean(w2 * w2, axis=0, keepdims=True))
+            scale = np.maximum(row_rms * col_rms / rms, 0.25 * rms) if r > 1 else np.full_like(w2, rms)
+            excess = (np.abs(g2 - w2) - 4 * tol * np.abs(w2)) / scale
+            k = int(np.argmax(excess))
+            assert excess.flat[k] < 48 * tol, (f"{what}: {name}[{k // c}, {k % c}] = {g2.flat[k]:.6e}, oracle {w2.flat[k]:.6e}: off by more "
+                                               f"than 4 tol of itself + 48 tol x the scale of its row and column ({scale.flat[k]:.3e})")
+        if name in ROWWISE:
+            rows = (r, c) if r > 1 else (c, 1)
+            g2, w2 = g.reshape(rows), w.reshape(rows)
+            wn = np.linalg.norm(w2, axis=1)
+            floor = 0.1 * float(np.sqrt(np.mean(wn * wn)))
+            big = wn > floor
+            if big.any():
+                err = np.linalg.norm(g2 - w2, axis=1)[big] / wn[big]
+                k = int(np.argmax(err))
+                assert err[k] < 2 * tol, f"{what}: {name} row {np.flatnonzero(big)[k]} rel err {err[k]:.3e} >= {2 * tol} ({int(big.sum())} rows checked)"
     return worst
 
 
@@ -253,9 +285,9 @@ def test_workload3_unequal_shares_equal_one_batch(W, base):
 
 
 def test_workload2_variable_length_buckets(W, base):
-    """Batches formed by the library's batcher under the 16384-real-token cap; the first batch
-    (shortest bucket, most sequences) and the last (longest bucket, partial) are run against the
-    oracle."""
+    """Batches formed by the library's batcher under the 16384-real-token cap, bit for bit the oracle's.  Against the
+    oracle: the whole first batch (shortest bucket, most sequences), the whole last one (longest bucket, partial), and
+    for every padded length in between the first eight sequences of that bucket's first batch."""
     from paper_2009_14783_amd import binding as hs
     model, ocfg, layout = base
     wl = synth.WORKLOADS[2]
@@ -267,21 +299,27 @@ def test_workload2_variable_length_buckets(W, base):
     theta = synth.init_params(layout, wl["seed"])
     worker = W(model, "bf16", theta)
     nb = len(pads)
-    for j in (0, nb - 1):
+    assert sorted(set(pads.tolist())) == [64 * k for k in range(1, 9)]
+    first_of = {int(L): int(np.flatnonzero(pads == L)[0]) for L in sorted(set(pads.tolist()))}
+    cases = [(0, None), (nb - 1, None)] + [(j, 8) for L, j in first_of.items() if j not in (0, nb - 1)]
+    for j, take in cases:
         lens = lengths[seq[offs[j]:offs[j + 1]]]
-        assert lens.sum() <= 16384 and lens.max() <= pads[j]
+        assert lens.sum() <= 16384 and lens.max() <= pads[j] and lens.min() > pads[j] - 64
+        if take:
+            lens = lens[:take]
         mb = synth.make_micro_batch(synth.rng_for(wl["seed"] + 100 + j), lens, int(pads[j]), ocfg.vocab, "zipf")
         loss, g = gpu_micro_grad(worker, mb)
         ol, og = oracle_micro_grad(ocfg, theta, mb, np.float32)
+        print(f"batch {j}: B={len(lens)} L={pads[j]} loss {loss:.2f} (oracle {ol:.2f})", flush=True)
         assert abs(loss - ol) / abs(ol) < TOL["bf16"]
         compare_flat(layout, g, og, TOL["bf16"], f"batch {j} (B={len(lens)}, L={pads[j]})")
     worker.close()
 
 
 def test_workload4_bert_large_shape(W):
-    """BERT-large layers at L = 512.  The oracle runs the same layer shapes with 2 layers and 4
-    sequences (element-wise parity); the full 24-layer, 4 x 32-sequence step is checked through
-    properties: loss near ln V and accumulation of 4 micro-batches equal to 4 x one of them when the
+    """BERT-large at L = 512.  Against the oracle, element by element: 2 layers with 4 sequences, then the whole
+    24-layer model with 16 ragged sequences (every gradient tensor; about a minute of oracle time).  The full
+    4 x 32-sequence step on top: loss near ln V and accumulation of 4 micro-batches equal to 4 x one of them when the
     same micro-batch is repeated."""
     model = dict(synth.MODELS["bert_large"])
     small = dict(model, n_layers=2)
@@ -295,11 +333,34 @@ def test_workload4_bert_large_shape(W):
     ol, og = oracle_micro_grad(ocfg, theta, mb, np.float32)
     assert abs(loss - ol) / abs(ol) < TOL["bf16"]
     compare_flat(layout, g, og, TOL["bf16"], "bert-large layers")
-    # full size
-    full_layout = O.param_layout(O.ModelCfg(**model))
+    # Full depth: all 24 layers, sixteen ragged sequences at L = 512, every gradient tensor.  At this depth rounding the
+    # WEIGHTS to bf16 alone, with exact arithmetic otherwise, already moves the oracle's own gradient by about 2e-2
+    # (printed below), which no bf16 kernel can undo; the kernels are responsible for the gradient of the function they
+    # are given, so the 2e-2 bar is applied against the oracle at the bf16-rounded weights the GPU path really uses, and
+    # the distance to the oracle at the fp32 weights is held to that bar plus the measured effect of the rounding.
+    full_cfg = O.ModelCfg(**model)
+    full_layout = O.param_layout(full_cfg)
     theta = synth.init_params(full_layout, 1238)
-    mbs = synth.workload_micro_batches(4)
+    lens16 = [512, 300, 512, 77, 512, 409, 512, 181, 512, 64, 256, 512, 333, 512, 129, 480]
+    mb16 = synth.make_micro_batch(synth.rng_for(1239), lens16, 512, full_cfg.vocab, "zipf")
     worker = W(model, "bf16", theta)
+    loss, g = gpu_micro_grad(worker, mb16)
+    theta_r = worker.w_lowp.float().cpu().numpy()                      # the weights the forward and backward passes read
+    assert np.array_equal(theta_r, torch.from_numpy(theta).to(torch.bfloat16).float().numpy())
+    print("24 layers: oracle at the rounded weights running", flush=True)
+    olr, ogr = oracle_micro_grad(full_cfg, theta_r, mb16, np.float32)
+    print(f"24 layers, 16 sequences: loss {loss:.2f} (oracle at the rounded weights {olr:.2f}); oracle at the fp32 weights running", flush=True)
+    ol, og = oracle_micro_grad(full_cfg, theta, mb16, np.float32)
+    assert abs(loss - olr) / abs(olr) < TOL["bf16"] and abs(loss - ol) / abs(ol) < TOL["bf16"]
+    worst = compare_flat(full_layout, g, ogr, TOL["bf16"], "bert-large, 24 layers, oracle at the rounded weights")
+    drift = max(rel(ogr[off:off + r * c], og[off:off + r * c]) for _, off, r, c in full_layout)
+    far = max(rel(g[off:off + r * c], og[off:off + r * c]) for _, off, r, c in full_layout)
+    print(f"24 layers: worst tensor against the oracle at the rounded weights {worst}; bf16 rounding of the weights alone moves the "
+          f"oracle's gradient by up to {drift:.3e} per tensor; GPU against the oracle at the fp32 weights: up to {far:.3e}", flush=True)
+    assert far < TOL["bf16"] + drift
+    del og, ogr
+    # full size
+    mbs = synth.workload_micro_batches(4)
     up = worker.upload(mbs[0])
     n = worker.accumulate_micro_batches([up, up, up, up])
     torch.cuda.synchronize()
