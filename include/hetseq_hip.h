@@ -13,9 +13,12 @@
  *
  * Conventions (all calls):
  *  - "dev" pointers are device (HBM) addresses, "host" pointers are host addresses.
- *  - The caller owns every buffer and the stream.  The library allocates no device memory and
- *    keeps no pointer after a call returns; hs_ctx holds host state only: tables, the error text,
- *    and the handles of up to two further HIP streams (default priority) with the events that
+ *  - The caller owns every buffer and the stream.  The library allocates no device memory (the one
+ *    built-in array of hs_op_layernorm_bwd_noalloc aside) and keeps no pointer after a call returns, with one
+ *    exception: hs_arm_update records the pointers of w, m, v, G and the low-precision copy in the context
+ *    until the next hs_encoder_bwd / hs_s2s_bwd call on it has used them; those buffers must stay valid
+ *    until then.  hs_ctx holds host state only: tables, the error text, that armed update, the dropout
+ *    state, and the handles of up to two further HIP streams (default priority) with the events that
  *    order them, created on first use and destroyed with the context.
  *  - Device calls enqueue on `stream` (a hipStream_t passed as void*; NULL = the default stream)
  *    and return without synchronising.  Results are valid once the caller synchronises that
@@ -284,6 +287,18 @@ hs_status hs_grad_accum_normalize(float* G, const float* g, size_t n, int32_t ig
 hs_status hs_adam_step(float* w, float* m, float* v, const float* G, void* w_lowp_out, size_t n,
                        double lr, double beta1, double beta2, double eps, double weight_decay, int64_t t,
                        void* stream);
+
+/* The loss that a step reports (section "Optimizer and Learning Rate Scheduler": every worker's loss comes with a
+ * weight, and the weighted sum over all workers divided by the global weight equals the non-distributed loss):
+ * *loss_out = (loss_sums[0] + ... + loss_sums[n - 1]) / denom, the sums added in index order.  loss_sums [n] dev:
+ * the loss SUMs that hs_mlm_loss (hs_s2s_loss) wrote for the micro-batches of the step, zeros for workers or passes
+ * without data; denom > 0: the global weight, the one given to hs_grad_accum_normalize; loss_out: dev scalar. */
+hs_status hs_weighted_loss(const float* loss_sums, int32_t n, double denom, float* loss_out, void* stream);
+
+/* Zero-fills `bytes` bytes at dst (dev): the start state of the gradient buffer of an update whose first micro-batch
+ * has no target, and of the loss sums of workers without data (sections "Backpropagation" and "Delayed Update
+ * (Gradient Accumulation)": such a worker contributes nothing).  Buffers above 4096 bytes must be 16-byte aligned. */
+hs_status hs_fill_zero(void* dst, size_t bytes, void* stream);
 
 /* fp32 -> activation-type copy of a flat buffer (dst bfloat16 [n] for HS_BF16, float for
  * HS_FP32); used once to seed the low-precision weights before the first step. */

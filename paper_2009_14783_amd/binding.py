@@ -85,6 +85,8 @@ _SIGNATURES = {
     "hs_checkpoint_read": (_I32, [C.c_char_p, C.POINTER(hs_ckpt_header), _P, _P, _P, _SZ]),
     "hs_profile_enable": (_I32, [_P, _I32]),
     "hs_profile_read": (_I32, [_P, C.POINTER(hs_profile_entry), C.POINTER(_I32)]),
+    "hs_fill_zero": (_I32, [_P, _SZ, _P]),
+    "hs_weighted_loss": (_I32, [_P, _I32, _D, _P, _P]),
     "hs_op_gemm": (_I32, [_I32, _I32, _I32, _I32, _I32, _I32, _P, _I64, _P, _I64, _P, _I64, _I32, _F, _P, _I32, _P, _I64, _P, _P, _SZ, _P]),
     "hs_op_layernorm_fwd": (_I32, [_I32, _P, _P, _P, _P, _P, _I32, _I32, _F, _P]),
     "hs_op_layernorm_bwd_scratch": (_SZ, [_I32, _I32]),
@@ -359,6 +361,14 @@ def hs_op_gemm(dtype, a_kmajor, b_kmajor, M, N, K, A, lda, B, ldb, Cm, ldc, c_f3
 
 def hs_op_layernorm_fwd(dtype, x, gain, bias, y, stats, R, H, eps, stream=None):
     _check(lib().hs_op_layernorm_fwd(dtype, _ptr(x), _ptr(gain), _ptr(bias), _ptr(y), _ptr(stats), R, H, eps, _stream(stream)))
+
+
+def hs_fill_zero(dst, nbytes, stream=None):
+    _check(lib().hs_fill_zero(_ptr(dst), nbytes, _stream(stream)))
+
+
+def hs_weighted_loss(loss_sums, n, denom, loss_out, stream=None):
+    _check(lib().hs_weighted_loss(_ptr(loss_sums), n, float(denom), _ptr(loss_out), _stream(stream)))
 
 
 def hs_op_layernorm_bwd_scratch(R, H) -> int:

@@ -100,6 +100,14 @@ hs_status check_launch(const char* what) {
   return HS_OK;
 }
 
+// the loss sums of the workers / passes added in index order by one wave, times 1 / (global weight)
+__global__ __launch_bounds__(64) void weighted_loss_kernel(const float* __restrict__ x, int n, float inv_denom, float* __restrict__ out) {
+  float s = 0.f;
+  for (int i = threadIdx.x; i < n; i += 64) s += x[i];
+  s = wave_sum(s);
+  if (threadIdx.x == 0) *out = s * inv_denom;
+}
+
 }  // namespace
 
 extern "C" {
@@ -132,6 +140,19 @@ hs_status hs_adam_step(float* w, float* m, float* v, const float* G, void* w_low
   k.lr_wd = lr * weight_decay;
   hipLaunchKernelGGL(adam_kernel, dim3(flat_grid(n / 4 + 1)), dim3(256), 0, (hipStream_t)stream, w, m, v, G, (bf16*)w_lowp_out, n, k);
   return check_launch("hs_adam_step");
+}
+
+hs_status hs_fill_zero(void* dst, size_t bytes, void* stream) {
+  if (bytes == 0) return HS_OK;
+  if (!dst) return hs_fail(nullptr, HS_ERR_INVALID_ARG, "hs_fill_zero: NULL buffer");
+  return launch_fill_zero(nullptr, dst, bytes, (hipStream_t)stream);
+}
+
+hs_status hs_weighted_loss(const float* loss_sums, int32_t n, double denom, float* loss_out, void* stream) {
+  if (n < 0 || !(denom > 0.0) || std::isinf(denom)) return hs_fail(nullptr, HS_ERR_INVALID_ARG, "hs_weighted_loss: n < 0 or denom not positive and finite");
+  if (!loss_out || (n > 0 && !loss_sums)) return hs_fail(nullptr, HS_ERR_INVALID_ARG, "hs_weighted_loss: NULL buffer");
+  hipLaunchKernelGGL(weighted_loss_kernel, dim3(1), dim3(64), 0, (hipStream_t)stream, loss_sums, n, (float)(1.0 / denom), loss_out);
+  return check_launch("hs_weighted_loss");
 }
 
 hs_status hs_cast_params(const float* src, void* dst, size_t n, int32_t dst_dtype, void* stream) {

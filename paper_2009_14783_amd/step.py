@@ -41,6 +41,7 @@ class Worker:
         self._acts = self._ws = self._hidden = self._dhidden = None
         self._acts_bytes = self._ws_bytes = 0
         self.loss_buf = torch.zeros(64, dtype=torch.float32, device=dev)
+        self.loss_out = torch.zeros(2, dtype=torch.float32, device=dev)     # the reported loss of a step
 
     def close(self):
         if self.ctx is not None:
@@ -104,7 +105,7 @@ class Worker:
         the optimizer update that its backward pass then carries out)."""
         n_total, first = 0, True
         assert len(batches) <= self.loss_buf.numel()
-        self.loss_buf.zero_()
+        hs.hs_fill_zero(self.loss_buf, 4 * self.loss_buf.numel())
         real = [i for i, d in enumerate(batches) if d is not None and not d.get("dummy", False)]
         for i, d in enumerate(batches):
             if d is None or d.get("dummy", False):
@@ -112,7 +113,7 @@ class Worker:
                 continue
             if fused:
                 if first and d["M"] == 0:
-                    self.G.zero_()
+                    hs.hs_fill_zero(self.G, 4 * self.P)
                     first = False
                 if arm_last is not None and i == real[-1]:
                     arm_last()
@@ -121,15 +122,15 @@ class Worker:
                 if self.g is None:
                     self.g = torch.zeros(self.P, dtype=torch.float32, device=self.device)
                 if first:
-                    self.G.zero_()
+                    hs.hs_fill_zero(self.G, 4 * self.P)
                 if d["M"] == 0:
-                    self.g.zero_()
+                    hs.hs_fill_zero(self.g, 4 * self.P)
                 self.forward_backward(d, self.g, 0, i)
                 hs.hs_grad_accum_normalize(self.G, self.g, self.P, 0, 0.0)
             first = False
             n_total += d["n_seq"]
         if first:
-            self.G.zero_()
+            hs.hs_fill_zero(self.G, 4 * self.P)
         return n_total
 
     def train_step(self, batches: list, adam: dict, denom=None, fused: bool = True, update_in_backward: bool = True):
@@ -156,7 +157,9 @@ class Worker:
         return D
 
     def reported_loss(self, D) -> float:
-        return float(self.loss_buf.sum().item()) / D
+        """The weighted average of the step's loss sums (hs_weighted_loss); synchronises."""
+        hs.hs_weighted_loss(self.loss_buf, self.loss_buf.numel(), float(D), self.loss_out)
+        return float(self.loss_out[0].item())
 
     # ---- multi-step loop: schedule and checkpoints (call order only, like the rest of this class) ----
     def train(self, n_steps: int, micro_batches_of, adam: dict, schedule: dict) -> list:
@@ -230,6 +233,7 @@ class PairWorker:
         self._acts = self._ws = self._out = self._dout = None
         self._acts_bytes = self._ws_bytes = 0
         self.loss_buf = torch.zeros(128, dtype=torch.float32, device=dev)      # slot i: loss sum, slot 64 + i: nll sum
+        self.loss_out = torch.zeros(2, dtype=torch.float32, device=dev)
 
     def close(self):
         if self.ctx is not None:
@@ -284,7 +288,7 @@ class PairWorker:
         arithmetic, same bits as the two separate calls).  Off by default: at this model's sizes the update's memory
         traffic beside the small GEMMs of the backward pass costs more than it hides (6.58 against 6.49 ms per step)."""
         assert len(batches) <= 64
-        self.loss_buf.zero_()
+        hs.hs_fill_zero(self.loss_buf, 4 * self.loss_buf.numel())
         real = [i for i, d in enumerate(batches) if d is not None]
         D = float(denom if denom is not None else max(sum(batches[i]["n_tok"] for i in real), 1))
         self.t += 1
@@ -299,7 +303,7 @@ class PairWorker:
             self.forward_backward(d, self.G, 0 if first else 1, i)
             first = False
         if first:
-            self.G.zero_()
+            hs.hs_fill_zero(self.G, 4 * self.P)
         if first or not update_in_backward:
             hs.hs_grad_accum_normalize(self.G, None, self.P, 0, D)
             hs.hs_adam_step(self.w, self.m, self.v, self.G, self.w_lowp, self.P, adam["lr"], adam["beta1"], adam["beta2"], adam["eps"],
@@ -308,5 +312,7 @@ class PairWorker:
 
     def reported_loss(self, D):
         """(smoothed loss, negative log-likelihood), both per unit of weight; synchronises."""
-        lb = self.loss_buf.cpu().numpy().astype(np.float64)
-        return lb[:64].sum() / D, lb[64:].sum() / D
+        hs.hs_weighted_loss(self.loss_buf, 64, float(D), self.loss_out)
+        hs.hs_weighted_loss(self.loss_buf.data_ptr() + 256, 64, float(D), self.loss_out.data_ptr() + 4)
+        out = self.loss_out.cpu().numpy().astype(np.float64)
+        return float(out[0]), float(out[1])
