@@ -43,7 +43,7 @@ def algorithmic_flops(model, mbs):
     return total
 
 
-GEMM_SOURCES = ("gemm.hip", "gemm_dev.h", "gemm_wide.h", "gemm_wide_kk.hip", "gemm_wide_kn.hip", "gemm_wide_nn.hip")
+GEMM_SOURCES = ("gemm.hip", "gemm_dev.h", "gemm_wide.h", "gemm_dma.h", "gemm_wide_kk.hip", "gemm_wide_kn.hip", "gemm_wide_nn.hip")
 
 
 def gemm_source_hash():

@@ -405,6 +405,15 @@ hs_status hs_op_gemm(int32_t dtype, int32_t a_kmajor, int32_t b_kmajor, int32_t 
                      int32_t c_f32, float beta, const void* bias, int32_t epi, const void* aux,
                      int64_t ldaux, void* C2, void* scratch, size_t scratch_bytes, void* stream);
 
+/* Timing aid, not part of the method: the library holds several tilings of its bf16 GEMM kernel (numbered 0 .. 11: block
+ * tile, k-tile depth, blocks per CU, operands staged through registers or loaded into LDS directly) and normally picks
+ * one per product from its shape.  variant >= 0 makes every later bf16 product of this process with M, N, K >= 256
+ * that the variant can serve use it (the grouped weight-gradient launch of the backward pass keeps its own tiling);
+ * -1 restores the automatic choice.
+ * Results stay within the same tolerance for every variant.  Host call, process-wide, not thread-safe: set it while no
+ * other thread launches work.  HS_ERR_INVALID_ARG for numbers outside [-1, 11]. */
+hs_status hs_tune_gemm_variant(int32_t variant);
+
 /* y = LN(x) over rows of length H; writes mean and reciprocal std per row (stats [2, R] float). */
 hs_status hs_op_layernorm_fwd(int32_t dtype, const void* x, const void* gain, const void* bias, void* y,
                               float* stats, int32_t R, int32_t H, float eps, void* stream);

@@ -87,6 +87,7 @@ _SIGNATURES = {
     "hs_profile_read": (_I32, [_P, C.POINTER(hs_profile_entry), C.POINTER(_I32)]),
     "hs_fill_zero": (_I32, [_P, _SZ, _P]),
     "hs_weighted_loss": (_I32, [_P, _I32, _D, _P, _P]),
+    "hs_tune_gemm_variant": (_I32, [_I32]),
     "hs_op_gemm": (_I32, [_I32, _I32, _I32, _I32, _I32, _I32, _P, _I64, _P, _I64, _P, _I64, _I32, _F, _P, _I32, _P, _I64, _P, _P, _SZ, _P]),
     "hs_op_layernorm_fwd": (_I32, [_I32, _P, _P, _P, _P, _P, _I32, _I32, _F, _P]),
     "hs_op_layernorm_bwd_scratch": (_SZ, [_I32, _I32]),
@@ -357,6 +358,10 @@ def hs_op_gemm(dtype, a_kmajor, b_kmajor, M, N, K, A, lda, B, ldb, Cm, ldc, c_f3
                ldaux=0, C2=None, scratch=None, scratch_bytes=0, stream=None):
     _check(lib().hs_op_gemm(dtype, a_kmajor, b_kmajor, M, N, K, _ptr(A), lda, _ptr(B), ldb, _ptr(Cm), ldc, c_f32, beta,
                             _ptr(bias), epi, _ptr(aux), ldaux, _ptr(C2), _ptr(scratch), scratch_bytes, _stream(stream)))
+
+
+def hs_tune_gemm_variant(variant: int):
+    _check(lib().hs_tune_gemm_variant(int(variant)))
 
 
 def hs_op_layernorm_fwd(dtype, x, gain, bias, y, stats, R, H, eps, stream=None):

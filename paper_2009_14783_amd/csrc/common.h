@@ -207,6 +207,9 @@ struct GemmArgs {
 hs_status launch_gemm(hs_ctx* ctx, const GemmArgs& g, hipStream_t s);
 // up to 8 weight-gradient products (A m-major, B n-major, fp32 C = beta C + product) in one launch; other argument
 // sets run one by one
+// timing runs: every bf16 product with M, N, K >= 256 that configuration `variant` can serve uses it (-1: automatic choice); process-wide
+int gemm_variant_count();
+void gemm_set_variant(int variant);
 hs_status launch_gemm_group(hs_ctx* ctx, const GemmArgs* gs, int n, hipStream_t s);
 
 // stats: R means, then (stat_ld floats after the first mean; default R) R reciprocal standard deviations

@@ -350,18 +350,46 @@ hipError_t launch_cfg(const GemmArgs& g, const GemmDev& p, int splits, hipStream
   return launch_one<false, false, BM, BN, BK, WGM, WGN>(p, grid, s);
 }
 
-// Tile configurations.  0 is gemm_bf16_mfma (128 x 128 x 32, three blocks per CU); the others are gemm_bf16_wide.
-struct TileCfg { int bm, bn, bk; };
-constexpr TileCfg kTileCfg[] = {{128, 128, 32}, {256, 256, 64}, {256, 192, 64}, {128, 192, 64}, {256, 128, 32}, {128, 128, 64}, {256, 128, 64}};
-constexpr int kNumTileCfg = sizeof(kTileCfg) / sizeof(kTileCfg[0]);
-int gemm_cfg_override = -1;    // >= 0: use this configuration for every bf16 product (tuning runs)
+// the two tables of gelu_tab_eval, filled once per process by a kernel on the stream of the first product that needs them
+static __device__ float2 gelu_tables[2][kGeluTabN];
+__global__ __launch_bounds__(256) void gelu_table_kernel(float2* tab) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= 2 * kGeluTabN) return;
+  const int which = i / kGeluTabN, k = i % kGeluTabN;
+  const double h = 2.0 * (double)kGeluTabR / kGeluTabN;
+  auto f = [&](double x) {
+    const double cdf = 0.5 * (1.0 + erf(x * 0.70710678118654752440));
+    return which == 0 ? cdf : cdf + x * 0.39894228040143267794 * exp(-0.5 * x * x);
+  };
+  const double a = f(-(double)kGeluTabR + k * h), b = f(-(double)kGeluTabR + (k + 1) * h);
+  tab[i] = make_float2((float)a, (float)(b - a));
+}
+static hipError_t gelu_table(int which, hipStream_t s, const float2** out) {
+  static float2* dev_tab = nullptr;
+  if (!dev_tab) {
+    void* p = nullptr;
+    hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(gelu_tables));
+    if (e != hipSuccess) return e;
+    // every later use is ordered behind this launch only on `s`; other streams wait for it once, here
+    hipLaunchKernelGGL(gelu_table_kernel, dim3(2 * kGeluTabN / 256), dim3(256), 0, s, (float2*)p);
+    e = hipStreamSynchronize(s);
+    if (e != hipSuccess) return e;
+    dev_tab = (float2*)p;
+  }
+  *out = dev_tab + which * kGeluTabN;
+  return hipSuccess;
+}
 
-// The one tile shape in use: 128 x 128 x 32 with 2 x 2 waves, three blocks per CU.  Measured alternatives
-// were equal or slower over the shapes of the training step and are not built: 256 x 128 and 256 x 256
-// block tiles, 8-wave blocks, 64-deep k-tiles, asynchronous global->LDS rings with 4 stages, and a
-// three-stage LDS pipeline with two fragment sets and a prescribed MFMA/LDS/global issue order (faster
-// only with a single block per CU: 128 x 192 tiles gained 5-15 % on the N = 768 shapes and lost on the
-// weight-gradient shapes).
+// Tile configurations.  0 is gemm_bf16_mfma (128 x 128 x 32, three blocks per CU); 1..6 are gemm_bf16_wide (global ->
+// registers -> LDS), 7..11 gemm_bf16_dma (global -> LDS directly).  In use: 0, 5 and 9 (see launch_gemm) and, for the
+// grouped weight-gradient launch, the tile of 6.  The others are kept as measured alternatives, selectable for
+// timing runs through gemm_set_variant: on the shapes of the training step they were equal or slower.
+struct TileCfg { int bm, bn, bk; };
+constexpr TileCfg kTileCfg[] = {{128, 128, 32}, {256, 256, 64}, {256, 192, 64}, {128, 192, 64}, {256, 128, 32}, {128, 128, 64}, {256, 128, 64},
+                                {128, 128, 32}, {128, 128, 32}, {128, 128, 64}, {256, 128, 64}, {256, 128, 64}};
+constexpr int kNumTileCfg = sizeof(kTileCfg) / sizeof(kTileCfg[0]);
+int gemm_cfg_override = -1;    // >= 0: use this configuration for every bf16 product of some size that it can serve (timing runs)
+
 constexpr int kMaxBK = 64;
 
 }  // namespace
@@ -392,11 +420,14 @@ static GemmDev gemm_dev_args(const GemmArgs& g) {
   p.A = g.A; p.B = g.B; p.C = g.C; p.C2 = g.C2; p.bias = g.bias; p.aux = g.aux;
   p.lda = g.lda; p.ldb = g.ldb; p.ldc = g.ldc; p.ldaux = g.ldaux;
   p.M = g.M; p.N = g.N; p.K = g.K; p.c_f32 = g.c_f32; p.epi = g.epi; p.beta = g.beta;
-  p.partial = nullptr; p.k_per_split = g.K;
+  p.partial = nullptr; p.k_per_split = g.K; p.gelu_tab = nullptr;
   p.drop = (g.drop && g.drop->thr && g.epi == 1) ? *g.drop : DropCfg{0u, 1.0f, 0u, 0u, 0u};
   p.drop_site = g.drop_site;
   return p;
 }
+
+int gemm_variant_count() { return kNumTileCfg; }
+void gemm_set_variant(int variant) { gemm_cfg_override = variant; }
 
 // Several weight-gradient products (A m-major, B n-major, fp32 C = beta C + A^T-style product, no epilogue) in ONE
 // launch of the grouped kernel: no split-K, no partial sums in memory.  Anything else, or more than 8 products,
@@ -454,11 +485,15 @@ hs_status launch_gemm(hs_ctx* ctx, const GemmArgs& g, hipStream_t s) {
     dim3 grid((g.N + 63) / 64, (g.M + 63) / 64);
     hipLaunchKernelGGL(gemm_simt<float>, grid, dim3(256), 0, s, p, g.a_kmajor, g.b_kmajor);
   } else {
-    // Configuration: 128 x 128 x 64 tiles of the wide kernel (two blocks per CU) for products of some size whose
-    // epilogue it is built with; the three-blocks-per-CU kernel for small or ragged ones and for the rest.
-    int cfg = (gemm_cfg_override >= 0 && gemm_cfg_override < kNumTileCfg) ? gemm_cfg_override
-              : ((g.M >= 256 && g.N >= 256 && g.K >= 256) ? 5 : 0);
+    // Configuration for products of some size whose epilogue the wide kernels are built with: 128 x 128 x 64 tiles, two
+    // blocks per CU - the direct-to-LDS kernel for the activation-gradient products (A k-major, B n-major; it gained 6-12 %
+    // on their shapes, whole output matrices of 8192 rows, and lost on the forward pass's half batches), the
+    // register-staged kernel otherwise.  Small or ragged products and the remaining epilogues: the three-blocks-per-CU kernel.
+    int cfg = !(g.M >= 256 && g.N >= 256 && g.K >= 256) ? 0
+              : (gemm_cfg_override >= 0 && gemm_cfg_override < kNumTileCfg) ? gemm_cfg_override
+              : ((g.a_kmajor && !g.b_kmajor) ? 9 : 5);
     if (cfg != 0 && !wide_supports(g)) cfg = 0;
+    if (cfg >= 7 && g.K % kTileCfg[cfg].bk) cfg = 5;      // the direct-to-LDS kernel takes whole k-tiles only
     const int kBM = kTileCfg[cfg].bm, kBN = kTileCfg[cfg].bn, kBK = kTileCfg[cfg].bk;
     // split-K when the output has too few tiles to fill the chip and a scratch buffer was given
     const int64_t tiles = (int64_t)((g.M + kBM - 1) / kBM) * ((g.N + kBN - 1) / kBN);
@@ -477,6 +512,10 @@ hs_status launch_gemm(hs_ctx* ctx, const GemmArgs& g, hipStream_t s) {
       splits = (g.K + p.k_per_split - 1) / p.k_per_split;
     }
     hipError_t e;
+    if (cfg != 0 && (g.epi == 2 || g.epi == 3)) {
+      e = gelu_table(g.epi == 2 ? 0 : 1, s, &p.gelu_tab);
+      if (e != hipSuccess) return hs_fail(ctx, HS_ERR_HIP, std::string("gemm: GELU table: ") + hipGetErrorString(e));
+    }
     if (cfg == 0) e = launch_cfg<128, 128, 32, 2, 2>(g, p, splits, s);
     else if (g.a_kmajor && g.b_kmajor) e = gemm_wide_launch_kk(cfg, p, splits, s);
     else if (g.a_kmajor) e = gemm_wide_launch_kn(cfg, p, splits, s);

@@ -11,6 +11,7 @@ struct GemmDev {
   float beta;
   float* partial;      // split-K partial sums [splits][M][N], or null
   int k_per_split;     // multiple of the k-tile
+  const float2* gelu_tab;   // wide kernels, GELU epilogues: table for gelu_tab_eval (the cdf for epi 2, GELU' for epi 3)
   DropCfg drop;        // dropout of (product + bias) before the residual is added (epi == 1 only; thr == 0: off)
   uint32_t drop_site;  // element index of the site = row * N + col
 };
@@ -22,6 +23,13 @@ struct GemmGroupDev {
   GemmDev prob[8];
 };
 constexpr int kGroupBM = 256, kGroupBN = 128;   // tile of the grouped kernel
+
+// Piecewise-linear tables of the normal cdf Phi (GELU(x) = x Phi(x)) and of GELU'(x) = Phi(x) + x pdf(x) on
+// [-6, 6]: entry i holds the value at -6 + i h and the increment to the next node, h = 12 / 1024.  Error of the
+// interpolation below 5e-6 (Phi) and 1.4e-5 (GELU'), three orders under bf16 resolution; outside the interval
+// both functions equal their end values to 1e-7.
+constexpr int kGeluTabN = 1024;
+constexpr float kGeluTabR = 6.0f;
 
 namespace {
 // dropout factors of n (4 or 8) consecutive output columns of one row, starting at a column that is a
@@ -297,6 +305,14 @@ __device__ __forceinline__ void tile_epilogue_lds(const GemmDev& p, const f32x16
     }
     __builtin_amdgcn_sched_barrier(0);
   }
+}
+
+// table lookup for the epilogues of the wide kernels: tab (in LDS) as described at kGeluTabN
+__device__ __forceinline__ float gelu_tab_eval(const float2* tab, float x) {
+  const float xc = __builtin_amdgcn_fmed3f(x, -kGeluTabR, kGeluTabR * 0.9999999f);
+  const float t = fmaf(xc, (float)kGeluTabN / (2.0f * kGeluTabR), 0.5f * (float)kGeluTabN);
+  const float2 e = tab[(int)t];
+  return fmaf(e.y, __builtin_amdgcn_fractf(t), e.x);
 }
 
 constexpr int MPAD = 32;   // m-major LDS rows: R + 32 elements  (row stride = 64 B mod 256 B)

@@ -110,7 +110,7 @@ template <bool AK, bool BKM, int TI, int TJ, int WGM, int WGN, int BK>
 constexpr size_t wide_lds_bytes() {
   constexpr int NT = 64 * WGM * WGN;
   const size_t pipe = 2 * sizeof(bf16) * (size_t)(WideTile<AK, 32 * TI * WGM, BK, NT>::ELEMS + WideTile<BKM, 32 * TJ * WGN, BK, NT>::ELEMS);
-  const size_t stage = (size_t)WGM * WGN * 32 * (32 * TJ + 4) * sizeof(float);
+  const size_t stage = (size_t)WGM * WGN * 32 * (32 * TJ + 4) * sizeof(float) + kGeluTabN * sizeof(float2);   // + the GELU table
   return stage > pipe ? stage : pipe;
 }
 
@@ -121,7 +121,7 @@ constexpr size_t wide_lds_bytes() {
 // edge, unaligned operands and dropout take the general routine.
 template <int MODE, int TI, int TJ>
 __device__ __forceinline__ void tile_epilogue_pipe(const GemmDev& p, const f32x16 (&acc)[TI][TJ], int rbase, int cbase, int lane, int split,
-                                                   float* stage) {
+                                                   float* stage, const float2* tab) {
   constexpr int WN = 32 * TJ, LDW = WN + 4;
   constexpr int LPR = WN / 8, NIT = 32 * LPR / 64;
   constexpr bool HAS_AUX = MODE == EPI_ACT_RES || MODE == EPI_ACT_DGELU;
@@ -181,7 +181,7 @@ __device__ __forceinline__ void tile_epilogue_pipe(const GemmDev& p, const f32x1
         const int64_t o = (int64_t)row * p.ldc + col;
         if (HAS_AUX) {
 #pragma unroll
-          for (int t = 0; t < 8; ++t) v[t] = (MODE == EPI_ACT_RES) ? v[t] + (float)acur[it][t] : v[t] * gelu_grad_fast((float)acur[it][t]);
+          for (int t = 0; t < 8; ++t) v[t] = (MODE == EPI_ACT_RES) ? v[t] + (float)acur[it][t] : v[t] * gelu_tab_eval(tab, (float)acur[it][t]);
         }
         bf16x8 c;
 #pragma unroll
@@ -190,7 +190,7 @@ __device__ __forceinline__ void tile_epilogue_pipe(const GemmDev& p, const f32x1
         if (MODE == EPI_ACT_GELU) {
           bf16x8 g;
 #pragma unroll
-          for (int t = 0; t < 8; ++t) g[t] = (bf16)gelu_fast(v[t]);
+          for (int t = 0; t < 8; ++t) g[t] = (bf16)(v[t] * gelu_tab_eval(tab, v[t]));
           *(bf16x8*)((bf16*)p.C2 + o) = g;
         }
       }
@@ -354,13 +354,19 @@ __device__ __forceinline__ void wide_tile(const GemmDev& p, int m0, int n0, int 
   const int rbase = m0 + wm * TI * 32, cbase = n0 + wn * TJ * 32;
   constexpr int STAGE_FLOATS = 32 * (32 * TJ + 4);
   float* stage = (float*)lds_raw + wave * STAGE_FLOATS;
+  // GELU epilogues: the table moves into LDS behind the staging areas
+  float2* const tab = (float2*)((float*)lds_raw + WGM * WGN * STAGE_FLOATS);
+  if (p.gelu_tab && (((EPIS >> EPI_ACT_GELU) | (EPIS >> EPI_ACT_DGELU)) & 1)) {
+    for (int i = tid; i < kGeluTabN / 2; i += NT) ((float4*)tab)[i] = ((const float4*)p.gelu_tab)[i];
+    __syncthreads();
+  }
   constexpr auto has = [](int mode) { return (EPIS >> mode) & 1; };
-  if (p.partial) { if constexpr (has(EPI_PARTIAL)) tile_epilogue_pipe<EPI_PARTIAL, TI, TJ>(p, acc, rbase, cbase, lane, split, stage); }
-  else if (p.c_f32) { if constexpr (has(EPI_F32)) tile_epilogue_pipe<EPI_F32, TI, TJ>(p, acc, rbase, cbase, lane, 0, stage); }
-  else if (p.epi == 0) { if constexpr (has(EPI_ACT)) tile_epilogue_pipe<EPI_ACT, TI, TJ>(p, acc, rbase, cbase, lane, 0, stage); }
-  else if (p.epi == 1) { if constexpr (has(EPI_ACT_RES)) tile_epilogue_pipe<EPI_ACT_RES, TI, TJ>(p, acc, rbase, cbase, lane, 0, stage); }
-  else if (p.epi == 2) { if constexpr (has(EPI_ACT_GELU)) tile_epilogue_pipe<EPI_ACT_GELU, TI, TJ>(p, acc, rbase, cbase, lane, 0, stage); }
-  else { if constexpr (has(EPI_ACT_DGELU)) tile_epilogue_pipe<EPI_ACT_DGELU, TI, TJ>(p, acc, rbase, cbase, lane, 0, stage); }
+  if (p.partial) { if constexpr (has(EPI_PARTIAL)) tile_epilogue_pipe<EPI_PARTIAL, TI, TJ>(p, acc, rbase, cbase, lane, split, stage, tab); }
+  else if (p.c_f32) { if constexpr (has(EPI_F32)) tile_epilogue_pipe<EPI_F32, TI, TJ>(p, acc, rbase, cbase, lane, 0, stage, tab); }
+  else if (p.epi == 0) { if constexpr (has(EPI_ACT)) tile_epilogue_pipe<EPI_ACT, TI, TJ>(p, acc, rbase, cbase, lane, 0, stage, tab); }
+  else if (p.epi == 1) { if constexpr (has(EPI_ACT_RES)) tile_epilogue_pipe<EPI_ACT_RES, TI, TJ>(p, acc, rbase, cbase, lane, 0, stage, tab); }
+  else if (p.epi == 2) { if constexpr (has(EPI_ACT_GELU)) tile_epilogue_pipe<EPI_ACT_GELU, TI, TJ>(p, acc, rbase, cbase, lane, 0, stage, tab); }
+  else { if constexpr (has(EPI_ACT_DGELU)) tile_epilogue_pipe<EPI_ACT_DGELU, TI, TJ>(p, acc, rbase, cbase, lane, 0, stage, tab); }
 }
 
 // the epilogues each operand layout is built with (the training step needs no others; launch_gemm falls back

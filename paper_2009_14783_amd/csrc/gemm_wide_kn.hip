@@ -1,4 +1,6 @@
 // gemm_bf16_wide for A k-major, B n-major
-#include "gemm_wide.h"
+#include "gemm_dma.h"
 
-hipError_t gemm_wide_launch_kn(int cfg, const GemmDev& p, int splits, hipStream_t s) { return launch_wide_layout<true, false>(cfg, p, splits, s); }
+hipError_t gemm_wide_launch_kn(int cfg, const GemmDev& p, int splits, hipStream_t s) {
+  return cfg >= kFirstDmaCfg ? launch_dma_layout<true, false>(cfg, p, splits, s) : launch_wide_layout<true, false>(cfg, p, splits, s);
+}

@@ -110,33 +110,34 @@ __global__ __launch_bounds__(256) void embed_ln_fwd_kernel(const T* __restrict__
 // LayerNorm backward.  Each wave walks rows with a fixed stride and keeps per-column partial
 // sums of dy*xhat, dy and dx; blocks write partials, a second kernel adds them in block order.
 // ------------------------------------------------------------------------------------------
-template <class T, int drop_mode>
-__global__ __launch_bounds__(256) void ln_bwd_kernel(const T* __restrict__ dy, const T* __restrict__ x, const float* __restrict__ stats,
+// NC: 256-column slots per row that the registers hold (hidden <= 256 NC); EXACT: hidden == 256 NC, no slot is partly used.
+template <class T, int drop_mode, int NC, bool EXACT>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(NC <= 3 ? 4 : 2, 4))) void ln_bwd_kernel(const T* __restrict__ dy, const T* __restrict__ x, const float* __restrict__ stats,
                                                      const T* __restrict__ gain, T* __restrict__ dx, float* __restrict__ partials,
                                                      int R, int H, DropCfg drop, uint32_t site, T* __restrict__ dxm) {
   // drop_mode 1: dy is the gradient of a dropped OUTPUT of this LayerNorm and is masked as it is read.
   // drop_mode 2: dx feeds a dropped branch (site) besides a residual path: dxm gets the masked copy and the
   //              column sums of dx (the bias gradient of that branch) are taken over the masked values.
-  __shared__ float4 red[4][MAXCH * 64];
+  __shared__ float4 red[4][NC * 64];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int nch = H / 4;
   const float inv_h = 1.0f / (float)H;
-  float4 g[MAXCH], ag[MAXCH], ab[MAXCH], as[MAXCH];
+  float4 g[NC], ag[NC], ab[NC], as[NC];
 #pragma unroll
-  for (int c = 0; c < MAXCH; ++c) {
+  for (int c = 0; c < NC; ++c) {
     ag[c] = ab[c] = as[c] = make_float4(0.f, 0.f, 0.f, 0.f);
-    g[c] = (c * 64 + lane < nch) ? Vec4<T>::ld(gain + 4 * (c * 64 + lane)) : make_float4(0.f, 0.f, 0.f, 0.f);
+    g[c] = (EXACT || c * 64 + lane < nch) ? Vec4<T>::ld(gain + 4 * (c * 64 + lane)) : make_float4(0.f, 0.f, 0.f, 0.f);
   }
   // Rows of one wave are software-pipelined: the loads of the wave's next row are issued before the
   // reductions of the current one, so two rows are in flight per wave.
   const int stride = gridDim.x * 4;
   int row = blockIdx.x * 4 + wave;
-  float4 nx[MAXCH], ndy[MAXCH];
+  float4 nx[NC], ndy[NC];
   float nmu = 0.f, nrstd = 0.f;
   if (row < R) {
     nmu = stats[row]; nrstd = stats[R + row];
 #pragma unroll
-    for (int c = 0; c < MAXCH; ++c) if (c * 64 + lane < nch) {
+    for (int c = 0; c < NC; ++c) if (EXACT || c * 64 + lane < nch) {
       const int64_t o = (int64_t)row * H + 4 * (c * 64 + lane);
       nx[c] = Vec4<T>::ld(x + o);
       ndy[c] = Vec4<T>::ld(dy + o);
@@ -144,12 +145,12 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(const T* __restrict__ dy, c
   }
   for (; row < R; row += stride) {
     const float mu = nmu, rstd = nrstd;
-    float4 xh[MAXCH], dyv[MAXCH];
+    float4 xh[NC], dyv[NC];
 #pragma unroll
-    for (int c = 0; c < MAXCH; ++c) { xh[c] = nx[c]; dyv[c] = ndy[c]; }
+    for (int c = 0; c < NC; ++c) { xh[c] = nx[c]; dyv[c] = ndy[c]; }
     if (drop_mode == 1) {
 #pragma unroll
-      for (int c = 0; c < MAXCH; ++c) if (c * 64 + lane < nch) {
+      for (int c = 0; c < NC; ++c) if (EXACT || c * 64 + lane < nch) {
         float f[4];
         drop_factors4(drop, site, (uint64_t)((int64_t)row * H + 4 * (c * 64 + lane)) >> 2, f);
         dyv[c].x *= f[0]; dyv[c].y *= f[1]; dyv[c].z *= f[2]; dyv[c].w *= f[3];
@@ -159,7 +160,7 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(const T* __restrict__ dy, c
     if (next < R) {
       nmu = stats[next]; nrstd = stats[R + next];
 #pragma unroll
-      for (int c = 0; c < MAXCH; ++c) if (c * 64 + lane < nch) {
+      for (int c = 0; c < NC; ++c) if (EXACT || c * 64 + lane < nch) {
         const int64_t o = (int64_t)next * H + 4 * (c * 64 + lane);
         nx[c] = Vec4<T>::ld(x + o);
         ndy[c] = Vec4<T>::ld(dy + o);
@@ -167,7 +168,7 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(const T* __restrict__ dy, c
     }
     float s1 = 0.f, s2 = 0.f;
 #pragma unroll
-    for (int c = 0; c < MAXCH; ++c) if (c * 64 + lane < nch) {
+    for (int c = 0; c < NC; ++c) if (EXACT || c * 64 + lane < nch) {
       const float4 xv = xh[c];
       xh[c] = make_float4((xv.x - mu) * rstd, (xv.y - mu) * rstd, (xv.z - mu) * rstd, (xv.w - mu) * rstd);
       const float4 d = make_float4(dyv[c].x * g[c].x, dyv[c].y * g[c].y, dyv[c].z * g[c].z, dyv[c].w * g[c].w);
@@ -177,7 +178,7 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(const T* __restrict__ dy, c
     s1 = wave_sum(s1) * inv_h;
     s2 = wave_sum(s2) * inv_h;
 #pragma unroll
-    for (int c = 0; c < MAXCH; ++c) if (c * 64 + lane < nch) {
+    for (int c = 0; c < NC; ++c) if (EXACT || c * 64 + lane < nch) {
       float4 d;
       d.x = rstd * (dyv[c].x * g[c].x - s1 - xh[c].x * s2); d.y = rstd * (dyv[c].y * g[c].y - s1 - xh[c].y * s2);
       d.z = rstd * (dyv[c].z * g[c].z - s1 - xh[c].z * s2); d.w = rstd * (dyv[c].w * g[c].w - s1 - xh[c].w * s2);
@@ -199,9 +200,10 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(const T* __restrict__ dy, c
   }
   // combine the four waves of the block in wave order, one quantity at a time
   float* out = partials + (int64_t)blockIdx.x * 3 * H;
+#pragma unroll
   for (int q = 0; q < 3; ++q) {
 #pragma unroll
-    for (int c = 0; c < MAXCH; ++c) if (c * 64 + lane < nch) red[wave][c * 64 + lane] = (q == 0) ? ag[c] : (q == 1 ? ab[c] : as[c]);
+    for (int c = 0; c < NC; ++c) if (EXACT || c * 64 + lane < nch) red[wave][c * 64 + lane] = (q == 0) ? ag[c] : (q == 1 ? ab[c] : as[c]);
     __syncthreads();
     for (int ch = threadIdx.x; ch < nch; ch += 256) {
       const float4 a = red[0][ch], b = red[1][ch], c2 = red[2][ch], d = red[3][ch];
@@ -611,23 +613,35 @@ hs_status launch_layernorm_fwd(hs_ctx* ctx, int dtype, const void* x, const void
   return HS_OK;
 }
 
-static int ln_bwd_blocks(int R) { int nb = (R + 7) / 8; return nb < 1 ? 1 : (nb > 768 ? 768 : nb); }
-size_t layernorm_bwd_scratch(int R, int H) { return align_up((size_t)ln_bwd_blocks(R) * 3 * H * sizeof(float), 256); }
+// Blocks of ln_bwd_kernel: eight rows per block (two per wave, both in flight at once) up to the number of blocks
+// that are resident together, which the kernel's register use sets: four per CU up to 768 columns, three beyond.
+static int ln_bwd_blocks(int R, int H) {
+  const int cap = H <= 768 ? 1024 : 768;
+  const int nb = (R + 7) / 8;
+  return nb < 1 ? 1 : (nb > cap ? cap : nb);
+}
+size_t layernorm_bwd_scratch(int R, int H) { return align_up((size_t)ln_bwd_blocks(R, H) * 3 * H * sizeof(float), 256); }
 
 // main kernel: dx and the per-block partial column sums
 hs_status launch_layernorm_bwd_rows(hs_ctx* ctx, int dtype, const void* dy, const void* x, const float* stats, const void* gain, void* dx,
                                     int R, int H, void* partials, hipStream_t s, const DropCfg* drop, uint32_t site, int drop_mode,
                                     void* dxm) {
   if (R <= 0) return HS_OK;
-  const int nb = ln_bwd_blocks(R);
+  const int nb = ln_bwd_blocks(R, H);
   KScope scope(prof_of(ctx), KC_LN_BWD, 14.0 * R * H, 3.0 * R * H * esize(dtype), s);
   DropCfg d{0u, 1.0f, 0u, 0u, 0u};
   if (drop && drop->thr && drop_mode) d = *drop; else drop_mode = 0;
   if (drop_mode == 2 && !dxm) return hs_fail(ctx, HS_ERR_INVALID_ARG, "layernorm_bwd: masked output buffer missing");
-#define HS_LN_BWD(TT, MODE) hipLaunchKernelGGL((ln_bwd_kernel<TT, MODE>), dim3(nb), dim3(256), 0, s, (const TT*)dy, (const TT*)x, stats, \
-                                              (const TT*)gain, (TT*)dx, (float*)partials, R, H, d, site, (TT*)dxm)
+  const int nc = H <= 512 ? 2 : (H + 255) / 256;      // the NC the kernel is built with
+  const bool exact = H == 256 * nc;
+#define HS_LN_BWD4(TT, MODE, NC, EX) hipLaunchKernelGGL((ln_bwd_kernel<TT, MODE, NC, EX>), dim3(nb), dim3(256), 0, s, (const TT*)dy, (const TT*)x, stats, \
+                                                       (const TT*)gain, (TT*)dx, (float*)partials, R, H, d, site, (TT*)dxm)
+#define HS_LN_BWD3(TT, MODE, NC) do { if (exact) HS_LN_BWD4(TT, MODE, NC, true); else HS_LN_BWD4(TT, MODE, NC, false); } while (0)
+#define HS_LN_BWD(TT, MODE) do { if (nc == 2) HS_LN_BWD3(TT, MODE, 2); else if (nc == 3) HS_LN_BWD3(TT, MODE, 3); else HS_LN_BWD3(TT, MODE, 4); } while (0)
   if (dtype == HS_BF16) { if (drop_mode == 0) HS_LN_BWD(bf16, 0); else if (drop_mode == 1) HS_LN_BWD(bf16, 1); else HS_LN_BWD(bf16, 2); }
   else { if (drop_mode == 0) HS_LN_BWD(float, 0); else if (drop_mode == 1) HS_LN_BWD(float, 1); else HS_LN_BWD(float, 2); }
+#undef HS_LN_BWD4
+#undef HS_LN_BWD3
 #undef HS_LN_BWD
   LAUNCH_CHECK(ctx, "layernorm_bwd");
   return HS_OK;
@@ -637,7 +651,7 @@ hs_status launch_layernorm_bwd_cols(hs_ctx* ctx, const void* partials, float* d_
                                     hipStream_t s) {
   if (R <= 0 || !(d_gain || d_bias || d_colsum)) return HS_OK;
   KScope scope(prof_of(ctx), KC_LN_BWD, 0.0, 0.0, s);
-  hipLaunchKernelGGL(sum_partials_kernel, dim3((H + 63) / 64, 3), dim3(64 * SP_WAVES), 0, s, (const float*)partials, ln_bwd_blocks(R), (int64_t)3 * H,
+  hipLaunchKernelGGL(sum_partials_kernel, dim3((H + 63) / 64, 3), dim3(64 * SP_WAVES), 0, s, (const float*)partials, ln_bwd_blocks(R, H), (int64_t)3 * H,
                      (int64_t)H, H, d_gain, d_bias, d_colsum, beta);
   LAUNCH_CHECK(ctx, "layernorm_bwd finalize");
   return HS_OK;
