@@ -1,6 +1,6 @@
 """Times every tiling of the library's bf16 GEMM kernel on the products of one BERT-base layer (64 x 128 tokens).
 
-    python -m paper_2009_14783_amd.gemm_variants [--iters 50] [--step]
+    python -m paper_2009_14783_amd.gemm_variants [--iters 50] [--step] [--variants -1,5,9]
 
 Stand-alone: each product runs `iters` times back to back on fixed buffers with the epilogue it has in the training
 step (bias, bias + residual, bias + GELU with both outputs, GELU' of a saved pre-activation, fp32 accumulate); the
@@ -60,6 +60,7 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--iters", type=int, default=50)
     ap.add_argument("--step", action="store_true")
+    ap.add_argument("--variants", default="", help="comma-separated variant numbers (-1: automatic); default: all")
     args = ap.parse_args()
     hs.lib()
     g = torch.Generator(device="cuda").manual_seed(1)
@@ -70,7 +71,9 @@ def main():
     bufs = (A, B, torch.empty(n, dtype=torch.bfloat16, device="cuda"), torch.zeros(F * 3 * H, dtype=torch.float32, device="cuda"),
             torch.empty(n, dtype=torch.bfloat16, device="cuda"), aux, torch.zeros(F, dtype=torch.bfloat16, device="cuda"),
             torch.empty(96 << 20, dtype=torch.uint8, device="cuda"))
-    variants = [-1] + list(range(12))
+    variants = [int(v) for v in args.variants.split(",")] if args.variants else [-1] + list(range(12))
+    for prod in PRODUCTS:      # untimed pass: clocks up, code loaded
+        time_product(prod, 10, bufs)
     print("| variant | " + " | ".join(p[0] for p in PRODUCTS) + " | layer sum (us) |")
     print("|---|" + "---|" * (len(PRODUCTS) + 1))
     for v in variants:
