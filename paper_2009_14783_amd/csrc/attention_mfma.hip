@@ -274,9 +274,12 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma(const bf16* __restrict_
 }
 
 // ------------------------------------------------------------------------------------------
-// backward for sequences of at most 128 positions: one block per (sequence, head) keeps Q, K, V
-// and dO in LDS; every wave first owns 32 queries (dq), then 32 keys (dk, dv).  One staging phase,
-// one barrier, no second launch and no re-reading of the operands.
+// backward for sequences of at most 128 positions: one block per (sequence, head), no second launch.  Every
+// wave first owns 32 queries (dq) with K and V streamed from two LDS tiles, then 32 keys (dk, dv) with Q and dO
+// streamed from the SAME two tiles: owned rows never need LDS (their fragments come straight from global memory,
+// or out of the tiles just before they are overwritten), so a block takes 37 KiB of LDS and three of them share a CU -
+// one round for the 768 blocks of 64 sequences x 12 heads, and the second staging phase of one block runs under
+// the arithmetic of the others.
 // ------------------------------------------------------------------------------------------
 __device__ __forceinline__ void stage128(bf16* tile, const bf16* __restrict__ src, int64_t ld, int row_limit, int tid) {
 #pragma unroll
@@ -290,16 +293,14 @@ __device__ __forceinline__ void stage128(bf16* tile, const bf16* __restrict__ sr
 }
 
 template <bool DROP>
-__global__ __launch_bounds__(256) void attn_bwd_fused128_mfma(const bf16* __restrict__ qkv, const bf16* __restrict__ out,
-                                                              const float* __restrict__ lse, const bf16* __restrict__ d_out,
-                                                              const int32_t* __restrict__ lens, int L, int A, bf16* __restrict__ dqkv,
-                                                              DropCfg drop, uint32_t site) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3)))
+void attn_bwd_fused128_mfma(const bf16* __restrict__ qkv, const bf16* __restrict__ out, const float* __restrict__ lse,
+                            const bf16* __restrict__ d_out, const int32_t* __restrict__ lens, int L, int A, bf16* __restrict__ dqkv,
+                            DropCfg drop, uint32_t site) {
   extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
-  bf16* Qs = (bf16*)lds_raw;
-  bf16* Ks = Qs + 128 * LDT;
-  bf16* Vs = Ks + 128 * LDT;
-  bf16* Gs = Vs + 128 * LDT;
-  float* lse2_s = (float*)(Gs + 128 * LDT);
+  bf16* T0 = (bf16*)lds_raw;               // K, then Q
+  bf16* T1 = T0 + 128 * LDT;               // V, then dO
+  float* lse2_s = (float*)(T1 + 128 * LDT);
   float* dvec_s = lse2_s + 128;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int b = blockIdx.y, h = blockIdx.x;
@@ -310,52 +311,42 @@ __global__ __launch_bounds__(256) void attn_bwd_fused128_mfma(const bf16* __rest
   const bf16* base = qkv + (int64_t)b * L * ld + h * DH;
   const bf16* go = d_out + (int64_t)b * L * H + h * DH;
   const bf16* oo = out + (int64_t)b * L * H + h * DH;
-
-  stage128(Qs, base, ld, len, tid);
-  stage128(Ks, base + H, ld, len, tid);
-  stage128(Vs, base + 2 * H, ld, len, tid);
-  stage128(Gs, go, H, len, tid);
-  {
-    // row dot products sum_d dO*O: two threads per row, 32 columns each
-    const int r = tid >> 1, c0 = (tid & 1) * 32;
-    float part = 0.f;
-    if (r < len) {
-#pragma unroll
-      for (int c = 0; c < 32; c += 8) {
-        const bf16x8 g = *(const bf16x8*)(go + (int64_t)r * H + c0 + c), o = *(const bf16x8*)(oo + (int64_t)r * H + c0 + c);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) part = fmaf((float)g[e], (float)o[e], part);
-      }
-    }
-    part += __shfl_xor(part, 1);
-    if ((tid & 1) == 0) {
-      dvec_s[r] = part;
-      lse2_s[r] = (r < len) ? lse[((int64_t)b * A + h) * L + r] * LOG2E : 0.f;
-    }
-  }
-  __syncthreads();
-
   const int own = wave * 32 + (lane & 31);       // the query, then the key, this lane owns
   const bool wave_active = wave * 32 < len;      // wave-uniform
+
+  stage128(T0, base + H, ld, len, tid);
+  stage128(T1, base + 2 * H, ld, len, tid);
+  // the owned queries' fragments of Q and dO, and the row dot product sum_d dO*O (lanes l and l + 32 hold the two halves of a row)
+  bf16x8 qf[4], gf[4];
+  float drow = 0.f;
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) {
+    qf[ks] = frag_rows_global(base, ld, own, len, ks, lane);
+    gf[ks] = frag_rows_global(go, H, own, len, ks, lane);
+    const bf16x8 of = frag_rows_global(oo, H, own, len, ks, lane);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) drow = fmaf((float)gf[ks][e], (float)of[e], drow);
+  }
+  drow += __shfl_xor(drow, 32);
+  const float lse2 = (own < len) ? lse[((int64_t)b * A + h) * L + own] * LOG2E : 0.f;
+  if (lane < 32) { dvec_s[own] = drow; lse2_s[own] = lse2; }
+  __syncthreads();
+
   f32x16 acc[2], acc2[2];
+#pragma unroll
+  for (int db = 0; db < 2; ++db)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[db][r] = 0.f;
   // ---- queries owned: dq ----
   if (wave_active) {
-    bf16x8 qf[4], gf[4];
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks) { qf[ks] = frag_rows(Qs, wave * 32, ks, lane); gf[ks] = frag_rows(Gs, wave * 32, ks, lane); }
-    const float lse2 = lse2_s[own], drow = dvec_s[own];
-#pragma unroll
-    for (int db = 0; db < 2; ++db)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[db][r] = 0.f;
     for (int kb = 0; kb < len; kb += 32) {
       f32x16 st, dp;
 #pragma unroll
       for (int r = 0; r < 16; ++r) { st[r] = 0.f; dp[r] = 0.f; }
 #pragma unroll
       for (int ks = 0; ks < 4; ++ks) {
-        st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(Ks, kb, ks, lane), qf[ks], st, 0, 0, 0);
-        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(Vs, kb, ks, lane), gf[ks], dp, 0, 0, 0);
+        st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(T0, kb, ks, lane), qf[ks], st, 0, 0, 0);
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(T1, kb, ks, lane), gf[ks], dp, 0, 0, 0);
       }
       if (DROP) {
         f32x16 f;
@@ -372,25 +363,24 @@ __global__ __launch_bounds__(256) void attn_bwd_fused128_mfma(const bf16* __rest
       const bf16x8 s0 = pack8(st, 0), s1 = pack8(st, 1);
 #pragma unroll
       for (int db = 0; db < 2; ++db) {
-        acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols_t(Ks, kb, 0, 32 * db, lane), s0, acc[db], 0, 0, 0);
-        acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols_t(Ks, kb, 1, 32 * db, lane), s1, acc[db], 0, 0, 0);
+        acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols_t(T0, kb, 0, 32 * db, lane), s0, acc[db], 0, 0, 0);
+        acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols_t(T0, kb, 1, 32 * db, lane), s1, acc[db], 0, 0, 0);
       }
     }
-  } else {
-#pragma unroll
-    for (int db = 0; db < 2; ++db)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[db][r] = 0.f;
   }
   // ---- keys owned: dk, dv ----
-  // The owned key/value fragments are the last thing read from the K and V tiles: after the barrier a wave's own 32
-  // rows of those tiles are its staging areas for whole-row stores of dq, dk and dv.
+  // The owned key/value fragments are the last thing read from K and V.  After the barrier a wave's own 32 rows of
+  // tile 0 stage the whole-row stores of dq; after the next one the tiles are refilled with Q and dO.
   bf16x8 kf[4], vf[4];
 #pragma unroll
-  for (int ks = 0; ks < 4; ++ks) { kf[ks] = frag_rows(Ks, wave * 32, ks, lane); vf[ks] = frag_rows(Vs, wave * 32, ks, lane); }
+  for (int ks = 0; ks < 4; ++ks) { kf[ks] = frag_rows(T0, wave * 32, ks, lane); vf[ks] = frag_rows(T1, wave * 32, ks, lane); }
   __syncthreads();
   bf16* const dst = dqkv + (int64_t)b * L * ld + h * DH;
-  store_owned_rows_lds(dst, ld, wave * 32, L, acc, 0.125f, lane, Ks + wave * 32 * LDT);
+  store_owned_rows_lds(dst, ld, wave * 32, L, acc, 0.125f, lane, T0 + wave * 32 * LDT);
+  __syncthreads();
+  stage128(T0, base, ld, len, tid);
+  stage128(T1, go, H, len, tid);
+  __syncthreads();
 #pragma unroll
   for (int db = 0; db < 2; ++db)
 #pragma unroll
@@ -402,8 +392,8 @@ __global__ __launch_bounds__(256) void attn_bwd_fused128_mfma(const bf16* __rest
       for (int r = 0; r < 16; ++r) { st[r] = 0.f; dp[r] = 0.f; }
 #pragma unroll
       for (int ks = 0; ks < 4; ++ks) {
-        st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(Qs, qb, ks, lane), kf[ks], st, 0, 0, 0);
-        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(Gs, qb, ks, lane), vf[ks], dp, 0, 0, 0);
+        st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(T0, qb, ks, lane), kf[ks], st, 0, 0, 0);
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(T1, qb, ks, lane), vf[ks], dp, 0, 0, 0);
       }
       f32x16 f;
       if (DROP) drop_tile_queries(drop, site, ((uint64_t)b * A + h) * L, L, qb, own, lane, f);
@@ -419,15 +409,16 @@ __global__ __launch_bounds__(256) void attn_bwd_fused128_mfma(const bf16* __rest
       const bf16x8 p0 = pack8(st, 0), p1 = pack8(st, 1), s0 = pack8(dp, 0), s1 = pack8(dp, 1);
 #pragma unroll
       for (int db = 0; db < 2; ++db) {
-        acc2[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols_t(Gs, qb, 0, 32 * db, lane), p0, acc2[db], 0, 0, 0);
-        acc2[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols_t(Gs, qb, 1, 32 * db, lane), p1, acc2[db], 0, 0, 0);
-        acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols_t(Qs, qb, 0, 32 * db, lane), s0, acc[db], 0, 0, 0);
-        acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols_t(Qs, qb, 1, 32 * db, lane), s1, acc[db], 0, 0, 0);
+        acc2[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols_t(T1, qb, 0, 32 * db, lane), p0, acc2[db], 0, 0, 0);
+        acc2[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols_t(T1, qb, 1, 32 * db, lane), p1, acc2[db], 0, 0, 0);
+        acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols_t(T0, qb, 0, 32 * db, lane), s0, acc[db], 0, 0, 0);
+        acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols_t(T0, qb, 1, 32 * db, lane), s1, acc[db], 0, 0, 0);
       }
     }
   }
-  store_owned_rows_lds(dst + H, ld, wave * 32, L, acc, 0.125f, lane, Ks + wave * 32 * LDT);
-  store_owned_rows_lds(dst + 2 * H, ld, wave * 32, L, acc2, 1.0f, lane, Vs + wave * 32 * LDT);
+  __syncthreads();     // every wave is done with Q and dO: own rows of the tiles stage the stores of dk and dv
+  store_owned_rows_lds(dst + H, ld, wave * 32, L, acc, 0.125f, lane, T0 + wave * 32 * LDT);
+  store_owned_rows_lds(dst + 2 * H, ld, wave * 32, L, acc2, 1.0f, lane, T1 + wave * 32 * LDT);
 }
 
 }  // namespace
@@ -442,7 +433,7 @@ void launch_attention_fwd_mfma(const void* qkv, const int32_t* lens, int B, int 
 void launch_attention_bwd_mfma(const void* qkv, const void* out, const float* lse, const void* d_out, const int32_t* lens, int B, int L,
                                int A, void* dqkv, float* dvec, hipStream_t s, const DropCfg& drop, uint32_t site) {
   if (L <= 128) {
-    constexpr size_t lds = 4 * 128 * LDT * sizeof(bf16) + 2 * 128 * sizeof(float);
+    constexpr size_t lds = 2 * 128 * LDT * sizeof(bf16) + 2 * 128 * sizeof(float);
     static bool configured = false;
     if (!configured) {
       (void)hipFuncSetAttribute((const void*)attn_bwd_fused128_mfma<false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
