@@ -27,7 +27,7 @@ __device__ __forceinline__ int clamp_len(int n, int L) { return n < 1 ? 1 : (n >
 // bf16 MFMA
 // ------------------------------------------------------------------------------------------
 template <bool CAUSAL>
-__global__ __launch_bounds__(256) void gen_fwd_mfma(View a, bf16* __restrict__ out, float* __restrict__ lse) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) void gen_fwd_mfma(View a, bf16* __restrict__ out, float* __restrict__ lse) {
   __shared__ __attribute__((aligned(16))) bf16 Ks[64 * LDT];
   __shared__ __attribute__((aligned(16))) bf16 Vs[64 * LDT];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -108,7 +108,7 @@ __global__ __launch_bounds__(256) void gen_fwd_mfma(View a, bf16* __restrict__ o
 
 // dq and dvec[q] = sum_d dO[q,d] O[q,d]
 template <bool CAUSAL>
-__global__ __launch_bounds__(256) void gen_bwd_dq_mfma(View a, const bf16* __restrict__ out, const float* __restrict__ lse,
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) void gen_bwd_dq_mfma(View a, const bf16* __restrict__ out, const float* __restrict__ lse,
                                                        const bf16* __restrict__ d_out, bf16* __restrict__ dq, int64_t lddq,
                                                        float* __restrict__ dvec) {
   __shared__ __attribute__((aligned(16))) bf16 Ks[64 * LDT];
@@ -186,7 +186,7 @@ __global__ __launch_bounds__(256) void gen_bwd_dq_mfma(View a, const bf16* __res
 
 // wave owns 32 keys, streams queries / output gradients -> dk, dv
 template <bool CAUSAL>
-__global__ __launch_bounds__(256) void gen_bwd_dkv_mfma(View a, const float* __restrict__ lse, const bf16* __restrict__ d_out,
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void gen_bwd_dkv_mfma(View a, const float* __restrict__ lse, const bf16* __restrict__ d_out,
                                                         const float* __restrict__ dvec, bf16* __restrict__ dk_out,
                                                         bf16* __restrict__ dv_out, int64_t lddkv) {
   __shared__ __attribute__((aligned(16))) bf16 Qs[64 * LDT];

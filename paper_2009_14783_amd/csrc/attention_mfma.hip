@@ -19,7 +19,7 @@ using namespace attn_tiles;
 // forward: wave owns 32 queries, streams keys/values
 // ------------------------------------------------------------------------------------------
 template <bool DROP>
-__global__ __launch_bounds__(256) void attn_fwd_mfma(const bf16* __restrict__ qkv, const int32_t* __restrict__ lens, int L, int A,
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) void attn_fwd_mfma(const bf16* __restrict__ qkv, const int32_t* __restrict__ lens, int L, int A,
                                                      bf16* __restrict__ out, float* __restrict__ lse, DropCfg drop, uint32_t site) {
   __shared__ __attribute__((aligned(16))) bf16 Ks[64 * LDT];
   __shared__ __attribute__((aligned(16))) bf16 Vs[64 * LDT];
@@ -106,7 +106,7 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma(const bf16* __restrict__ qk
 // backward 1: wave owns 32 queries, streams keys/values -> dq and dvec[q] = sum_d dO[q,d] O[q,d]
 // ------------------------------------------------------------------------------------------
 template <bool DROP>
-__global__ __launch_bounds__(256) void attn_bwd_dq_mfma(const bf16* __restrict__ qkv, const bf16* __restrict__ out,
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) void attn_bwd_dq_mfma(const bf16* __restrict__ qkv, const bf16* __restrict__ out,
                                                         const float* __restrict__ lse, const bf16* __restrict__ d_out,
                                                         const int32_t* __restrict__ lens, int L, int A, bf16* __restrict__ dqkv,
                                                         float* __restrict__ dvec, DropCfg drop, uint32_t site) {
@@ -190,7 +190,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma(const bf16* __restrict__
 // backward 2: wave owns 32 keys, streams queries / output gradients -> dk, dv
 // ------------------------------------------------------------------------------------------
 template <bool DROP>
-__global__ __launch_bounds__(256) void attn_bwd_dkv_mfma(const bf16* __restrict__ qkv, const float* __restrict__ lse,
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_bwd_dkv_mfma(const bf16* __restrict__ qkv, const float* __restrict__ lse,
                                                          const bf16* __restrict__ d_out, const float* __restrict__ dvec,
                                                          const int32_t* __restrict__ lens, int L, int A, bf16* __restrict__ dqkv, DropCfg drop,
                                                          uint32_t site) {
