@@ -125,6 +125,61 @@ def test_gemm_bf16_large_k_and_many_tiles(hs):
         assert rel(host(dC), want) < 2e-6, (ak, bk)
 
 
+@pytest.mark.parametrize("variant", [-1] + list(range(12)))
+def test_gemm_every_tiling_ragged_edges_and_epilogues(hs, variant):
+    """Every built tiling of the bf16 kernel (hs_tune_gemm_variant; -1: the automatic choice), each operand layout with the
+    epilogues it serves, on a product with several tiles per direction, ragged last tiles in M and N, and a contraction that
+    is (1024) or is not (1000) a whole number of k-tiles."""
+    rng = np.random.default_rng(100 + variant)
+    M, N = 520, 392
+    tol = 4e-3
+    hs.hs_tune_gemm_variant(variant)
+    try:
+        for K in (1024, 1000):
+            for ak, bk in LAYOUTS:
+                A = (rng.standard_normal((M, K) if ak else (K, M)) * 0.1).astype(np.float32)
+                B = (rng.standard_normal((N, K) if bk else (K, N)) * 0.1).astype(np.float32)
+                R = rng.standard_normal((M, N)).astype(np.float32)
+                bias = rng.standard_normal(N).astype(np.float32)
+                dA, dB, dR, dbias = (dev(a, torch.bfloat16) for a in (A, B, R, bias))
+                Ar, Br = rounded(A, 1), rounded(B, 1)
+                prod = (Ar if ak else Ar.T) @ (Br if bk else Br.T).T
+                ws = torch.zeros(8 << 20, dtype=torch.uint8, device="cuda")
+                if not ak:        # weight-gradient layout: fp32 output, accumulated
+                    C0 = rng.standard_normal((M, N)).astype(np.float32)
+                    dC = dev(C0)
+                    hs.hs_op_gemm(1, ak, bk, M, N, K, dA, A.shape[1], dB, B.shape[1], dC, N, c_f32=1, beta=1.0, scratch=ws, scratch_bytes=ws.numel())
+                    torch.cuda.synchronize()
+                    assert rel(host(dC), C0.astype(np.float64) + prod) < 2e-6, (variant, K, ak, bk)
+                    continue
+                base = prod + rounded(bias, 1)
+                out = torch.zeros(M, N, dtype=torch.bfloat16, device="cuda")
+                out2 = torch.zeros(M, N, dtype=torch.bfloat16, device="cuda")
+                hs.hs_op_gemm(1, ak, bk, M, N, K, dA, A.shape[1], dB, B.shape[1], out, N, bias=dbias)
+                torch.cuda.synchronize()
+                assert rel(host(out), base) < tol, (variant, K, ak, bk, "bias")
+                hs.hs_op_gemm(1, ak, bk, M, N, K, dA, A.shape[1], dB, B.shape[1], out, N, bias=dbias, epi=1, aux=dR, ldaux=N)
+                torch.cuda.synchronize()
+                assert rel(host(out), base + rounded(R, 1)) < tol, (variant, K, ak, bk, "residual")
+                if bk:
+                    hs.hs_op_gemm(1, ak, bk, M, N, K, dA, A.shape[1], dB, B.shape[1], out, N, bias=dbias, epi=2, C2=out2)
+                    torch.cuda.synchronize()
+                    assert rel(host(out), base) < tol and rel(host(out2), O.gelu(base)) < tol, (variant, K, ak, bk, "gelu")
+                else:
+                    hs.hs_op_gemm(1, ak, bk, M, N, K, dA, A.shape[1], dB, B.shape[1], out, N, epi=3, aux=dR, ldaux=N)
+                    torch.cuda.synchronize()
+                    assert rel(host(out), prod * O.gelu_grad(rounded(R, 1))) < tol, (variant, K, ak, bk, "gelu'")
+    finally:
+        hs.hs_tune_gemm_variant(-1)
+
+
+def test_gemm_variant_out_of_range_is_an_error(hs):
+    for v in (-2, 12, 1000):
+        with pytest.raises(hs.HsError):
+            hs.hs_tune_gemm_variant(v)
+    hs.hs_tune_gemm_variant(-1)
+
+
 @pytest.mark.parametrize("mode", [0, 1])
 @pytest.mark.parametrize("R,H", [(37, 128), (1030, 768), (5, 1024)])
 def test_layernorm_fwd_bwd(hs, mode, R, H):
