@@ -109,6 +109,7 @@ template <class TA, class TB, int KS, int AHEAD>
 __device__ __forceinline__ void dma_step(typename TA::Cursor& ca, typename TB::Cursor& cb, unsigned char* __restrict__ nxt,
                                          const unsigned char* __restrict__ cur, f32x16 (&acc)[2][2], bool full_ring, bool request, int wm,
                                          int wn, int lane, int wave) {
+  asm volatile("" ::: "memory");      // no LDS access of the step before moves below the barrier, none of this step above it
   if (full_ring) wait_loads<AHEAD*(TA::NI + TB::NI)>(); else wait_loads<0>();
   __builtin_amdgcn_s_barrier();
   asm volatile("" ::: "memory");
@@ -179,6 +180,7 @@ __device__ __forceinline__ void dma_tile(const GemmDev& p, int m0, int n0, int s
                                     lane, wave);
     }
   }
+  asm volatile("" ::: "memory");
   wait_loads<0>();
   __builtin_amdgcn_s_barrier();   // every wave is done with the operand stages: they become the staging area of the epilogue
   asm volatile("" ::: "memory");
