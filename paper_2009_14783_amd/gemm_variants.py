@@ -1,6 +1,6 @@
 """Times every tiling of the library's bf16 GEMM kernel on the products of one BERT-base layer (64 x 128 tokens).
 
-    python -m paper_2009_14783_amd.gemm_variants [--iters 50] [--step] [--variants -1,5,9]
+    python -m paper_2009_14783_amd.gemm_variants [--iters 50] [--step] [--variants -1,5,9] [--products "fwd ffn1,dx qkv"] [--cube]
 
 Stand-alone: each product runs `iters` times back to back on fixed buffers with the epilogue it has in the training
 step (bias, bias + residual, bias + GELU with both outputs, GELU' of a saved pre-activation, fp32 accumulate); the
@@ -8,6 +8,8 @@ table gives TFLOP/s per variant.  A variant that is not built with a product's e
 contraction length, is served by the library's fallback kernel; the automatic choice is the row `auto`.
 --step adds the whole training step (ms per step, 10 warm-up + 30 timed) with the variant forced for every product of the
 forward pass and of the activation-gradient chain (the grouped weight-gradient launch keeps its own tiling).
+--cube times 8192 x 8192 x 8192 products in the three operand layouts instead (no epilogue; fp32 output for the m-major layout).
+--products keeps the named products only (for counter runs under a profiler).
 Prints Markdown.  Needs the GPU and the built library; no oracle, no CPU path.
 """
 from __future__ import annotations
@@ -28,6 +30,8 @@ PRODUCTS = [
     ("dx ffn2", 1, 0, T, F, H, 3, 0), ("dx ffn1", 1, 0, T, H, F, 0, 0), ("dx out", 1, 0, T, H, H, 0, 0), ("dx qkv", 1, 0, T, H, 3 * H, 0, 0),
     ("dW ffn1", 0, 0, F, H, T, 0, 1), ("dW ffn2", 0, 0, H, F, T, 0, 1), ("dW out", 0, 0, H, H, T, 0, 1), ("dW qkv", 0, 0, 3 * H, H, T, 0, 1),
 ]
+# A and B k-major; A k-major, B n-major; A and B m-major
+CUBES = [("cube kk", 1, 1, 8192, 8192, 8192, 0, 0), ("cube kn", 1, 0, 8192, 8192, 8192, 0, 0), ("cube nn", 0, 0, 8192, 8192, 8192, 0, 1)]
 NAMES = {-1: "auto", 0: "0: 128x128x32, 3/CU", 1: "1: 256x256x64", 2: "2: 256x192x64", 3: "3: 128x192x64, 2/CU", 4: "4: 256x128x32, 2/CU",
          5: "5: 128x128x64, 2/CU", 6: "6: 256x128x64", 7: "7: LDS-direct 128x128x32, 4 stages, 2/CU",
          8: "8: LDS-direct 128x128x32, 3 stages, 3/CU", 9: "9: LDS-direct 128x128x64, 2 stages, 2/CU",
@@ -61,25 +65,34 @@ def main():
     ap.add_argument("--iters", type=int, default=50)
     ap.add_argument("--step", action="store_true")
     ap.add_argument("--variants", default="", help="comma-separated variant numbers (-1: automatic); default: all")
+    ap.add_argument("--products", default="", help="comma-separated product names; default: all")
+    ap.add_argument("--cube", action="store_true")
     args = ap.parse_args()
     hs.lib()
+    products = CUBES if args.cube else PRODUCTS
+    if args.products:
+        products = [p for p in products if p[0] in [q.strip() for q in args.products.split(",")]]
+        if not products:
+            raise SystemExit("--products: no such product")
     g = torch.Generator(device="cuda").manual_seed(1)
-    n = T * F
+    n = max(p[3] * p[4] for p in products + [("", 0, 0, T, F, 0, 0, 0)])
+    n = max(n, max(max(p[3], p[4]) * p[5] for p in products))
     A = (torch.randn(n, generator=g, device="cuda") * 0.5).to(torch.bfloat16)
     B = (torch.randn(n, generator=g, device="cuda") * 0.05).to(torch.bfloat16)
     aux = torch.randn(n, generator=g, device="cuda").to(torch.bfloat16)
-    bufs = (A, B, torch.empty(n, dtype=torch.bfloat16, device="cuda"), torch.zeros(F * 3 * H, dtype=torch.float32, device="cuda"),
-            torch.empty(n, dtype=torch.bfloat16, device="cuda"), aux, torch.zeros(F, dtype=torch.bfloat16, device="cuda"),
+    bufs = (A, B, torch.empty(n, dtype=torch.bfloat16, device="cuda"),
+            torch.zeros(max([F * 3 * H] + [p[3] * p[4] for p in products if p[7]]), dtype=torch.float32, device="cuda"),
+            torch.empty(n, dtype=torch.bfloat16, device="cuda"), aux, torch.zeros(max([F] + [p[4] for p in products]), dtype=torch.bfloat16, device="cuda"),
             torch.empty(96 << 20, dtype=torch.uint8, device="cuda"))
     variants = [int(v) for v in args.variants.split(",")] if args.variants else [-1] + list(range(12))
-    for prod in PRODUCTS:      # untimed pass: clocks up, code loaded
-        time_product(prod, 10, bufs)
-    print("| variant | " + " | ".join(p[0] for p in PRODUCTS) + " | layer sum (us) |")
-    print("|---|" + "---|" * (len(PRODUCTS) + 1))
+    for prod in products:      # untimed pass: clocks up, code loaded
+        time_product(prod, 3, bufs)
+    print("| variant | " + " | ".join(p[0] for p in products) + " | sum (us) |")
+    print("|---|" + "---|" * (len(products) + 1))
     for v in variants:
         hs.hs_tune_gemm_variant(v)
         cells, tot = [], 0.0
-        for prod in PRODUCTS:
+        for prod in products:
             us, tf = time_product(prod, args.iters, bufs)
             cells.append(f"{tf:.0f}")
             tot += us
